@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the SBC hot path on one MI355X.
+
+A step is one communication round of one client on the ResNet-50-shaped update (161 fp32
+tensors, 25,557,032 entries, p = 0.001): sbc_compress (residual accumulation, exact top-k on
+both sign sides, means, binarization, residual update, Golomb encoding) followed by
+sbc_decompress_accumulate of the produced message into a dense accumulator (Golomb decoding
+and the server's scaled accumulation).  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` is entries per second over whole steps (wall clock, both calls
+synchronise).  `roofline` is for the dominant kernel, the residual-accumulation pass:
+12 algorithmic bytes per entry (read dW, read R, write R') times the entries of the update,
+divided by that kernel's mean duration measured with HIP events on the launch stream during
+the timed steps.  `cpu_baseline` is the CPU oracle timed on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+BYTES_PER_ENTRY = 12           # read dW, read R, write R'
+P = 0.001
+
+# HBM bytes per launch of k_accumulate_hist on this workload from rocprofv3 --pmc runs
+# (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on the plain copy kernel); see
+# profiles/.  None until measured.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--breakdown", action="store_true", help="also print per-kernel times to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported "
+              "(sharding is described in DESIGN.md only)" % args.gpus, file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_1805_08768_amd import binding as sbc, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = "cuda:0"
+    sizes = synth.numels(synth.resnet50_shapes())
+    N = sum(sizes)
+    T = len(sizes)
+
+    # three different updates resident in HBM, used round-robin; the residual carries over
+    n_sets = 3
+    host_sets = [synth.resnet50_update(round_=r) for r in range(n_sets)]
+    flat_sets = [torch.from_numpy(np.concatenate(h)).to(dev) for h in host_sets]
+    flat_R = torch.zeros(N, dtype=torch.float32, device=dev)
+    flat_out = torch.zeros(N, dtype=torch.float32, device=dev)
+
+    def views(flat):
+        out, off = [], 0
+        for n in sizes:
+            out.append(flat[off:off + n])
+            off += n
+        return out
+
+    dW_sets = [views(f) for f in flat_sets]
+    R = views(flat_R)
+    out = views(flat_out)
+    bound = sbc.sbc_msg_bound(sizes, P)
+    msg = torch.zeros(bound, dtype=torch.uint8, device=dev)
+    ctx = sbc.sbc_create(0, N, T)
+    scale = 1.0 / 32.0
+
+    def step(i):
+        nbytes = sbc.sbc_compress(ctx, dW_sets[i % n_sets], R, P, msg)
+        sbc.sbc_decompress_accumulate(ctx, msg, nbytes, P, scale, out)
+        return nbytes
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    sbc.sbc_profile_enable(ctx, 1)
+    msg_bytes = 0
+    t_compress = 0.0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ta = time.perf_counter()
+        nbytes = sbc.sbc_compress(ctx, dW_sets[(args.warmup + i) % n_sets], R, P, msg)
+        t_compress += time.perf_counter() - ta
+        sbc.sbc_decompress_accumulate(ctx, msg, nbytes, P, scale, out)
+        msg_bytes += nbytes
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = {name: (ms, calls) for name, ms, calls in sbc.sbc_profile_read(ctx)}
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    compress_ms = t_compress * 1e3 / args.steps
+    k1_ms, k1_calls = prof["k_accumulate_hist"]
+    k1_avg_ms = k1_ms / max(1, k1_calls)
+    achieved = BYTES_PER_ENTRY * N / (k1_avg_ms * 1e-3) / 1e9
+
+    # untimed extras: per-kernel breakdown, copy yardstick, paper-accounted compression ratio
+    sbc.sbc_profile_enable(ctx, 2)
+    for i in range(10):
+        sbc.sbc_compress(ctx, dW_sets[i % n_sets], R, P, msg)
+    breakdown = {name: round(ms / max(1, calls) * 1e3, 2) for name, ms, calls in sbc.sbc_profile_read(ctx)}
+    sbc.sbc_profile_enable(ctx, 0)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    src, dst = flat_sets[0], flat_sets[1]
+    for _ in range(3):
+        sbc.sbc_copy_baseline(dst, src)
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(10):
+        sbc.sbc_copy_baseline(dst, src)
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * 4 * N * 10 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    bits = sum(sbc.sbc_last_tensor_stats(ctx, t)[4] for t in range(T))
+    ratio = 32.0 * N / (bits + 32.0 * T)
+    if args.breakdown:
+        print("per-kernel us (event-bracketed):", breakdown, file=sys.stderr)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import sbc_oracle as oracle
+        dWs = host_sets[0]
+        zeros = [np.zeros_like(d) for d in dWs]
+        tc = time.perf_counter()
+        res = oracle.compress_model(dWs, zeros, P)
+        m = oracle.build_message(res)
+        accs = [np.zeros(n, np.float32) for n in sizes]
+        oracle.decode_accumulate(m, sizes, scale, accs)
+        dt = time.perf_counter() - tc
+        cpu = {"value": N / dt, "unit": "elements/s", "cores": 1, "kind": "oracle",
+               "sample": "one full step (compress + decode-accumulate) of the same 161-tensor update, "
+                         "%d entries, %.1f s" % (N, dt)}
+    sbc.sbc_destroy(ctx)
+
+    line = {
+        "metric": "SBC compress+encode throughput (elements/s, HBM GB/s, % of peak) per round",
+        "value": N / (ms_per_step * 1e-3),
+        "unit": "elements/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "ResNet-50-shaped update: 161 fp32 tensors, 25,557,032 entries, "
+                               "Laplace values with per-tensor scale 10^U(-4,-2), p=0.001, residual carried",
+                   "p": P, "tensors": T, "entries": N,
+                   "step": "sbc_compress + sbc_decompress_accumulate (one client, one round)"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
+                     "kernel": "k_accumulate_hist", "kernel_avg_us": k1_avg_ms * 1e3,
+                     "algorithmic_bytes_per_launch": BYTES_PER_ENTRY * N},
+        "cpu_baseline": cpu,
+        "compress_ms": compress_ms,
+        "decode_ms": ms_per_step - compress_ms,
+        "compress_elements_per_s": N / (compress_ms * 1e-3),
+        "compress_algorithmic_GBs": BYTES_PER_ENTRY * N / (compress_ms * 1e-3) / 1e9,
+        "compress_frac_of_hbm_peak": BYTES_PER_ENTRY * N / (compress_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "kernel_us": breakdown,
+        "copy_kernel_GBs": copy_gbs,
+        "message_bytes": msg_bytes / args.steps,
+        "compression_ratio_paper_accounting": ratio,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,172 @@
+/*
+ * sbc.h - C ABI of libsbc: Sparse Binary Compression (arXiv 1805.08768) on one
+ * AMD MI355X (gfx950).
+ *
+ * The library implements the client lines of the paper's Alg. 1 between
+ * "dW_i <- R_i + SGD_n(W_i) - W_i" and "msg_i <- encode(dW_i*)" for a list of
+ * fp32 weight tensors (residual accumulation, Alg. 2 sparse binarization per
+ * tensor, residual update, Alg. 3 Golomb position encoding), and the matching
+ * server lines (Alg. 4 decoding followed by the scaled accumulation of
+ * Alg. 1's averaging step).
+ *
+ * Conventions
+ *   - Every function returns SBC_OK (0) or a negative sbc_status; nothing
+ *     throws.  sbc_strerror() names a code.
+ *   - "device" pointers are HIP device addresses valid on the context's GPU;
+ *     "host" pointers are ordinary process memory.  The arrays of tensor
+ *     pointers (dW[], residual[], out[]) and numel[] are HOST arrays whose
+ *     ELEMENTS are device pointers / sizes.
+ *   - The caller owns every buffer it passes.  The library reads or writes
+ *     them only during the call and keeps no reference afterwards.  All
+ *     scratch memory is owned by the sbc_ctx and allocated in sbc_create();
+ *     sbc_compress() and sbc_decompress_accumulate() allocate nothing.
+ *   - Work is enqueued on the caller's HIP stream (a hipStream_t passed as
+ *     void*; NULL is the default stream).  Both entry points synchronise that
+ *     stream once before returning, so results and the status are final.
+ *   - A context must not be used from two threads at once.
+ *   - Tensor sizes: 1 <= numel < 2^32.  Sparsity: 0 < p < 1.
+ *
+ * Message layout (little endian), produced by sbc_compress and consumed by
+ * sbc_decompress_accumulate.  The paper transmits, per tensor, the Golomb bit
+ * string of the gaps between kept positions and one mean value; tensor shapes
+ * and b* are known to both sides ("Optimal Position Encoding"; supplement,
+ * "Golomb Position Decoding").  The container around those is this library's:
+ *     header   { u32 magic 'SBC1', u32 version = 1, u32 n_tensors, u32 bstar,
+ *                u64 payload_words, u64 reserved = 0 }                 32 bytes
+ *     table    n_tensors x { f32 mu_signed, u32 nnz, u64 bit_len,
+ *                            u64 word_offset }                    24 bytes each
+ *     payload  payload_words x u32; tensor t's stream occupies words
+ *              [word_offset, word_offset + ceil(bit_len/32)); stream bit i is
+ *              bit (31 - i%32) of word i/32; padding bits are zero.
+ * mu_signed is +mu^+ when the positive side was kept and -mu^- otherwise
+ * (Alg. 2).  Each kept position contributes q ones, one zero and b* remainder
+ * bits, most significant first, with q, r = divmod(skipped entries since the
+ * previous kept position, 2^b*) (Alg. 3).
+ */
+#ifndef SBC_H
+#define SBC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum sbc_status {
+    SBC_OK = 0,
+    SBC_EINVAL = -1,     /* null/misaligned pointer, p outside (0,1), numel out of range,
+                            n_tensors <= 0, dW aliasing residual */
+    SBC_ECAPACITY = -2,  /* message buffer below sbc_msg_bound(), or sizes beyond what the
+                            context was created for */
+    SBC_EHIP = -3,       /* a HIP runtime call failed */
+    SBC_ECORRUPT = -4,   /* decode: bad magic/version, tensor count or b* mismatch, nnz or
+                            bit_len inconsistent with the stream, position >= numel */
+    SBC_ENONFINITE = -5, /* compress: an accumulated entry R + dW was NaN or +-Inf */
+    SBC_EINTERNAL = -6   /* an internal invariant failed on the device (a bug) */
+} sbc_status;
+
+typedef struct sbc_ctx sbc_ctx;
+
+/* Scratch memory for problems of up to max_total_elems entries in up to max_tensors
+ * tensors per call, on HIP device `device`.  Device memory taken: about
+ * 16.3 bytes per entry of max_total_elems plus 5 KiB per tensor.  *out receives the
+ * context.  SBC_EINVAL for non-positive sizes or a bad device, SBC_EHIP if an
+ * allocation fails (nothing is leaked). */
+int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tensors);
+
+/* Frees the context's scratch memory.  NULL is allowed.  The caller must have
+ * no work of this context in flight. */
+void sbc_destroy(sbc_ctx* ctx);
+
+/* b* of Alg. 3 / "Optimal Position Encoding":
+ * max(0, 1 + floor(log2(log(phi-1)/log(1-p)))), phi the golden ratio, in fp64.
+ * Returns SBC_EINVAL (negative) unless 0 < p < 1. */
+int sbc_golomb_bstar(double p);
+
+/* Entries kept per tensor and sign side ("fraction p", Alg. 2):
+ * max(1, floor(p*numel)) with the product in fp64, at most numel.
+ * Returns SBC_EINVAL (negative) on bad arguments. */
+int64_t sbc_num_kept(int64_t numel, double p);
+
+/* Worst-case size in bytes of the message for these tensor sizes: header, table and,
+ * per tensor, ceil((k*(1+b*) + floor((numel-k)/2^b*)) / 32) words.  0 on bad arguments.
+ * numel is a host array. */
+size_t sbc_msg_bound(const int64_t* numel, int n_tensors, double p);
+
+/* Client step (Alg. 1 client lines, Alg. 2, Alg. 3) for n_tensors tensors:
+ *     A_t   = residual_t + dW_t                     (fp32, one rounding)
+ *     dW*_t = SBC(A_t, p)                           (exactly k_t kept entries on one side;
+ *                                                    equal values resolved to the lowest index)
+ *     residual_t <- A_t - dW*_t                     (in place)
+ *     msg   <- container of { mu_signed_t, Golomb(kept positions of t) }
+ * dW[t]        device, read only, numel[t] floats, 4-byte aligned (16 is faster)
+ * residual[t]  device, read/write, numel[t] floats, must not overlap dW[t]
+ * numel        host array
+ * msg          device, 8-byte aligned, msg_capacity >= sbc_msg_bound(...) bytes; bytes past
+ *              *msg_bytes up to the bound may be overwritten with zeros
+ * msg_bytes    host, receives the message size in bytes
+ * Errors: SBC_EINVAL, SBC_ECAPACITY (nothing was enqueued), SBC_EHIP, SBC_ENONFINITE and
+ * SBC_EINTERNAL (residual and msg contents are then unspecified). */
+int sbc_compress(sbc_ctx* ctx, void* hip_stream,
+                 const float* const* dW, float* const* residual,
+                 const int64_t* numel, int n_tensors, double p,
+                 void* msg, size_t msg_capacity, size_t* msg_bytes);
+
+/* Server step for one client message (Alg. 4, then the summand of Alg. 1's average):
+ *     out_t[j] += scale * mu_signed_t   for every decoded position j of every tensor t
+ * (fp32: the addend fl32(scale*mu) is formed once).  Call once per client with
+ * scale = 1/|I_t| on zero-initialised accumulators to obtain the averaged update; calls on
+ * one stream apply in call order.
+ * msg          device, 8-byte aligned, msg_bytes valid bytes
+ * numel        host array; n_tensors and p must match what the sender used
+ * out[t]       device, read/write, numel[t] floats
+ * Errors: SBC_EINVAL, SBC_ECAPACITY, SBC_EHIP; SBC_ECORRUPT if the message fails
+ * validation: no write outside out_t[0..numel_t) ever happens, but accumulators may have
+ * received part of the message. */
+int sbc_decompress_accumulate(sbc_ctx* ctx, void* hip_stream,
+                              const void* msg, size_t msg_bytes,
+                              const int64_t* numel, int n_tensors, double p,
+                              float scale, float* const* out);
+
+/* Inspection of the most recent sbc_compress() on this context, for tests and reports
+ * (Alg. 2 intermediates).  All out pointers are host memory and may be NULL.
+ *   mu_pos, mu_neg : mean(val+), mean(val-) in fp64
+ *   side           : +1 or -1
+ *   nnz            : kept entries (= k)
+ *   bit_len        : length of the tensor's Golomb stream in bits */
+int sbc_last_tensor_stats(sbc_ctx* ctx, int tensor, double* mu_pos, double* mu_neg,
+                          int* side, int64_t* nnz, int64_t* bit_len);
+
+/* Copies the kept-position bitmap of tensor `tensor` from the most recent sbc_compress()
+ * into host memory: entry j is bit (j%32) of mask_words[j/32]; n_words must be
+ * ceil(numel/32). */
+int sbc_last_mask(sbc_ctx* ctx, int tensor, uint32_t* mask_words, size_t n_words);
+
+/* Measurement support: per-kernel durations of sbc_compress(), taken with HIP events
+ * recorded on the caller's stream between the kernels of each call.
+ *   level 0  off (default; no events are recorded)
+ *   level 1  only the residual-accumulation kernel (the pass that carries the method's
+ *            mandatory 12 bytes per entry) is bracketed
+ *   level 2  every kernel is bracketed
+ * Enabling (or re-enabling) clears the accumulated totals. */
+int sbc_profile_enable(sbc_ctx* ctx, int level);
+
+/* Accumulated time of stage `stage` (0 .. n-1 in launch order; SBC_EINVAL past the end):
+ * *name gets a static string (the kernel's name), *total_ms the summed duration over
+ * *calls bracketed launches.  Out pointers are host memory and may be NULL. */
+int sbc_profile_read(sbc_ctx* ctx, int stage, const char** name, double* total_ms, int64_t* calls);
+
+/* Measurement support: enqueues a plain device-to-device streaming copy kernel of `bytes`
+ * bytes (a multiple of 16; both pointers 16-byte aligned) on the stream and returns without
+ * synchronising.  It is the yardstick for achievable HBM bandwidth and for scaling hardware
+ * counters; it is not part of the method. */
+int sbc_copy_baseline(void* hip_stream, void* dst, const void* src, size_t bytes);
+
+/* Static string for a status code. */
+const char* sbc_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SBC_H */

@@ -1,0 +1,451 @@
+// libsbc: host side of the C ABI declared in include/sbc.h.  Validates arguments, lays the
+// call's tensors out as a table of chunks, and enqueues the kernels on the caller's stream.
+// No device memory is allocated outside sbc_create().
+#include "../../include/sbc.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "sbc_compress_kernels.hpp"
+#include "sbc_decode_kernels.hpp"
+
+using namespace sbc;
+
+namespace {
+enum Stage { kStReset = 0, kStAccumulate, kStPickBins, kStExtract, kStSelectApply, kStChunkSummary,
+             kStTensorScan, kStPack, kNumStages };
+const char* const kStageNames[kNumStages] = {
+    "k_reset", "k_accumulate_hist", "k_pick_bins", "k_extract", "k_select_apply",
+    "k_chunk_summary", "k_tensor_scan", "k_pack"};
+}  // namespace
+
+struct sbc_ctx {
+    int device = 0;
+    int64_t max_elems = 0;
+    int max_tensors = 0;
+    uint64_t max_chunks = 0;
+
+    // device scratch
+    TensorDesc* d_desc = nullptr;
+    uint32_t* d_chunk_start = nullptr;
+    uint32_t* d_hist = nullptr;
+    TensorState* d_state = nullptr;
+    uint2* d_cand = nullptr;
+    uint32_t* d_bitmap = nullptr;
+    ChunkSummary* d_sum = nullptr;
+    uint32_t* d_prev_end = nullptr;
+    uint64_t* d_bitoff = nullptr;
+    ResultBlock* d_result = nullptr;
+    DecDesc* d_dec = nullptr;
+
+    // pinned host staging
+    TensorDesc* h_desc = nullptr;
+    uint32_t* h_chunk_start = nullptr;
+    ResultBlock* h_result = nullptr;
+    DecDesc* h_dec = nullptr;
+    TensorState* h_state = nullptr;
+
+    // what the device tables currently hold
+    int dev_T = 0;
+    bool dev_desc_valid = false;
+    int dev_dec_T = 0;
+    bool dev_dec_valid = false;
+
+    // optional per-kernel timing with HIP events on the caller's stream
+    int profile_level = 0;
+    hipEvent_t ev[kNumStages + 1] = {};
+    bool ev_ok = false;
+    double stage_ms[kNumStages] = {};
+    int64_t stage_calls[kNumStages] = {};
+
+    // last compress call, for the inspection entry points
+    int last_T = 0;
+    bool last_ok = false;
+    std::vector<TensorDesc> last_desc;
+};
+
+namespace {
+
+constexpr double kPhi = 1.6180339887498948482;
+
+struct DeviceGuard {
+    int prev = -1;
+    bool changed = false;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) == hipSuccess && prev != dev) changed = (hipSetDevice(dev) == hipSuccess);
+    }
+    ~DeviceGuard() { if (changed) (void)hipSetDevice(prev); }
+};
+
+int bstar_of(double p) {
+    const double b = 1.0 + std::floor(std::log2(std::log(kPhi - 1.0) / std::log(1.0 - p)));
+    if (b < 0.0) return 0;
+    return (int)b;
+}
+
+bool valid_p(double p) { return p > 0.0 && p < 1.0; }
+
+int64_t kept_of(int64_t n, double p) {
+    int64_t k = (int64_t)std::floor(p * (double)n);
+    if (k < 1) k = 1;
+    if (k > n) k = n;
+    return k;
+}
+
+uint64_t bound_words_of(int64_t n, int64_t k, int b) {
+    const uint64_t bits = (uint64_t)k * (uint64_t)(1 + b) + ((uint64_t)(n - k) >> b);
+    return (bits + 31) >> 5;
+}
+
+template <typename T>
+hipError_t dev_alloc(T** p, size_t count) { return hipMalloc(reinterpret_cast<void**>(p), count * sizeof(T)); }
+template <typename T>
+hipError_t host_alloc(T** p, size_t count) { return hipHostMalloc(reinterpret_cast<void**>(p), count * sizeof(T), hipHostMallocDefault); }
+
+void free_all(sbc_ctx* c) {
+    (void)hipFree(c->d_desc); (void)hipFree(c->d_chunk_start); (void)hipFree(c->d_hist);
+    (void)hipFree(c->d_state); (void)hipFree(c->d_cand); (void)hipFree(c->d_bitmap);
+    (void)hipFree(c->d_sum); (void)hipFree(c->d_prev_end); (void)hipFree(c->d_bitoff);
+    (void)hipFree(c->d_result); (void)hipFree(c->d_dec);
+    if (c->h_desc) (void)hipHostFree(c->h_desc);
+    if (c->h_chunk_start) (void)hipHostFree(c->h_chunk_start);
+    if (c->h_result) (void)hipHostFree(c->h_result);
+    if (c->h_dec) (void)hipHostFree(c->h_dec);
+    if (c->h_state) (void)hipHostFree(c->h_state);
+    if (c->ev_ok) for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
+    c->ev_ok = false;
+}
+
+int status_of_err(uint32_t err) {
+    if (err & kErrInternal) return SBC_EINTERNAL;
+    if (err & kErrNonFinite) return SBC_ENONFINITE;
+    if (err & kErrCorrupt) return SBC_ECORRUPT;
+    return SBC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* sbc_strerror(int code) {
+    switch (code) {
+        case SBC_OK: return "ok";
+        case SBC_EINVAL: return "invalid argument";
+        case SBC_ECAPACITY: return "buffer or context too small";
+        case SBC_EHIP: return "HIP runtime error";
+        case SBC_ECORRUPT: return "corrupt message";
+        case SBC_ENONFINITE: return "non-finite accumulated update";
+        case SBC_EINTERNAL: return "internal invariant violated";
+        default: return "unknown status";
+    }
+}
+
+int sbc_golomb_bstar(double p) {
+    if (!valid_p(p)) return SBC_EINVAL;
+    return bstar_of(p);
+}
+
+int64_t sbc_num_kept(int64_t numel, double p) {
+    if (!valid_p(p) || numel < 1) return SBC_EINVAL;
+    return kept_of(numel, p);
+}
+
+size_t sbc_msg_bound(const int64_t* numel, int n_tensors, double p) {
+    if (!numel || n_tensors <= 0 || !valid_p(p)) return 0;
+    const int b = bstar_of(p);
+    if (b > kMaxB) return 0;
+    uint64_t words = 0;
+    for (int t = 0; t < n_tensors; ++t) {
+        if (numel[t] < 1 || numel[t] >= (int64_t)1 << 32) return 0;
+        words += bound_words_of(numel[t], kept_of(numel[t], p), b);
+    }
+    return (size_t)(32 + 24ull * (unsigned)n_tensors + 4ull * words);
+}
+
+int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tensors) {
+    if (!out || max_total_elems < 1 || max_tensors < 1) return SBC_EINVAL;
+    *out = nullptr;
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) != hipSuccess) return SBC_EHIP;
+    if (device < 0 || device >= n_dev) return SBC_EINVAL;
+    sbc_ctx* c = new (std::nothrow) sbc_ctx();
+    if (!c) return SBC_EHIP;
+    c->device = device;
+    c->max_elems = max_total_elems;
+    c->max_tensors = max_tensors;
+    c->max_chunks = (uint64_t)max_total_elems / kChunk + (uint64_t)max_tensors;
+    DeviceGuard guard(device);
+    const size_t T = (size_t)max_tensors;
+    bool ok = true;
+    ok = ok && dev_alloc(&c->d_desc, T) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_chunk_start, T + 1) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_hist, T * kL1Bins) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_state, T) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_cand, 2 * (size_t)max_total_elems) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_bitmap, (size_t)c->max_chunks * kChunkWords) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_sum, (size_t)c->max_chunks) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_prev_end, (size_t)c->max_chunks) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_bitoff, (size_t)c->max_chunks) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_result, 1) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_dec, T) == hipSuccess;
+    ok = ok && host_alloc(&c->h_desc, T) == hipSuccess;
+    ok = ok && host_alloc(&c->h_chunk_start, T + 1) == hipSuccess;
+    ok = ok && host_alloc(&c->h_result, 1) == hipSuccess;
+    ok = ok && host_alloc(&c->h_dec, T) == hipSuccess;
+    ok = ok && host_alloc(&c->h_state, T) == hipSuccess;
+    if (ok) {
+        int made = 0;
+        for (; made <= kNumStages; ++made)
+            if (hipEventCreate(&c->ev[made]) != hipSuccess) break;
+        if (made <= kNumStages) {
+            for (int i = 0; i < made; ++i) (void)hipEventDestroy(c->ev[i]);
+            ok = false;
+        } else {
+            c->ev_ok = true;
+        }
+    }
+    if (!ok) {
+        (void)hipGetLastError();
+        free_all(c);
+        delete c;
+        return SBC_EHIP;
+    }
+    *out = c;
+    return SBC_OK;
+}
+
+void sbc_destroy(sbc_ctx* c) {
+    if (!c) return;
+    DeviceGuard guard(c->device);
+    free_all(c);
+    delete c;
+}
+
+int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* const* residual,
+                 const int64_t* numel, int n_tensors, double p, void* msg, size_t msg_capacity,
+                 size_t* msg_bytes) {
+    if (!c || !dW || !residual || !numel || !msg || !msg_bytes || n_tensors <= 0 || !valid_p(p))
+        return SBC_EINVAL;
+    if (((uintptr_t)msg & 7u) != 0) return SBC_EINVAL;
+    if (n_tensors > c->max_tensors) return SBC_ECAPACITY;
+    const int T = n_tensors;
+    const int b = bstar_of(p);
+    if (b > kMaxB) return SBC_EINVAL;
+    c->last_ok = false;
+
+    // ---- plan: tensor table and chunk numbering ----
+    uint64_t total = 0, chunks = 0, zero_words = 0;
+    bool same = c->dev_desc_valid && c->dev_T == T;
+    for (int t = 0; t < T; ++t) {
+        const int64_t n = numel[t];
+        if (n < 1 || n >= (int64_t)1 << 32) return SBC_EINVAL;
+        if (!dW[t] || !residual[t]) return SBC_EINVAL;
+        const uintptr_t a = (uintptr_t)dW[t], r = (uintptr_t)residual[t];
+        if ((a & 3u) || (r & 3u)) return SBC_EINVAL;
+        const uintptr_t bytes = (uintptr_t)n * 4u;
+        if (a < r + bytes && r < a + bytes) return SBC_EINVAL;    // dW overlaps the residual
+        TensorDesc d;
+        std::memset(&d, 0, sizeof(d));
+        d.dW = dW[t];
+        d.R = residual[t];
+        d.n = (uint32_t)n;
+        d.k = (uint32_t)kept_of(n, p);
+        d.chunk0 = (uint32_t)chunks;
+        d.nchunks = (uint32_t)((n + kChunk - 1) / kChunk);
+        d.cand_off = 2 * total;
+        if (same && std::memcmp(&d, &c->h_desc[t], sizeof(d)) != 0) same = false;
+        if (!same) { /* keep scanning: validation must see every tensor */ }
+        total += (uint64_t)n;
+        chunks += d.nchunks;
+        zero_words += bound_words_of(n, d.k, b);
+        if (total > (uint64_t)c->max_elems || chunks > c->max_chunks) return SBC_ECAPACITY;
+        // stage into a scratch copy first: h_desc may still equal the device copy
+        if (c->last_desc.size() < (size_t)T) c->last_desc.resize(T);
+        c->last_desc[t] = d;
+    }
+    if (chunks >= (1ull << 31)) return SBC_ECAPACITY;
+    const size_t need = (size_t)(32 + 24ull * (unsigned)T + 4ull * zero_words);
+    if (msg_capacity < need) return SBC_ECAPACITY;
+
+    DeviceGuard guard(c->device);
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    if (!same) {
+        for (int t = 0; t < T; ++t) {
+            c->h_desc[t] = c->last_desc[t];
+            c->h_chunk_start[t] = c->last_desc[t].chunk0;
+        }
+        c->h_chunk_start[T] = (uint32_t)chunks;
+        c->dev_desc_valid = false;
+        if (hipMemcpyAsync(c->d_desc, c->h_desc, sizeof(TensorDesc) * T, hipMemcpyHostToDevice, stream) != hipSuccess ||
+            hipMemcpyAsync(c->d_chunk_start, c->h_chunk_start, sizeof(uint32_t) * (T + 1), hipMemcpyHostToDevice, stream) != hipSuccess) {
+            (void)hipGetLastError();
+            return SBC_EHIP;
+        }
+        c->dev_T = T;
+    }
+
+    uint8_t* msg8 = static_cast<uint8_t*>(msg);
+    uint32_t* payload = reinterpret_cast<uint32_t*>(msg8 + 32 + 24ull * (unsigned)T);
+    const uint32_t n_chunks = (uint32_t)chunks;
+    const uint32_t hist_words = (uint32_t)T * kL1Bins;
+    const uint32_t state_words = (uint32_t)(T * sizeof(TensorState) / 4);
+    const int reset_blocks = (int)((hist_words + 256 * 8 - 1) / (256 * 8));
+
+    // stage boundaries are timed with events only when profiling was asked for
+    const int lvl = c->profile_level;
+    auto mark = [&](int stage_begun) {   // called before the kernel of `stage_begun` (kNumStages: after the last)
+        if (lvl >= 2 || (lvl == 1 && (stage_begun == kStAccumulate || stage_begun == kStAccumulate + 1)))
+            (void)hipEventRecord(c->ev[stage_begun], stream);
+    };
+    mark(kStReset);
+    hipLaunchKernelGGL(k_reset, dim3(reset_blocks), dim3(256), 0, stream, c->d_hist, hist_words,
+                       reinterpret_cast<uint32_t*>(c->d_state), state_words, c->d_result);
+    mark(kStAccumulate);
+    hipLaunchKernelGGL(k_accumulate_hist, dim3(n_chunks), dim3(kStreamThreads), 0, stream, c->d_desc,
+                       c->d_chunk_start, T, c->d_hist, c->d_bitmap, payload, (uint64_t)zero_words, c->d_result);
+    mark(kStPickBins);
+    hipLaunchKernelGGL(k_pick_bins, dim3(T), dim3(256), 0, stream, c->d_desc, c->d_hist, c->d_state, c->d_result);
+    mark(kStExtract);
+    hipLaunchKernelGGL(k_extract, dim3(n_chunks), dim3(kStreamThreads), 0, stream, c->d_desc,
+                       c->d_chunk_start, T, c->d_state, c->d_cand, 1, c->d_result);
+    mark(kStSelectApply);
+    hipLaunchKernelGGL(k_select_apply, dim3(T), dim3(kSelThreads), 0, stream, c->d_desc, c->d_state,
+                       c->d_cand, c->d_bitmap, c->d_result);
+    mark(kStChunkSummary);
+    hipLaunchKernelGGL(k_chunk_summary, dim3(n_chunks), dim3(kChunkWords), 0, stream, c->d_bitmap, c->d_sum, b);
+    mark(kStTensorScan);
+    hipLaunchKernelGGL(k_tensor_scan, dim3(T), dim3(256), 0, stream, c->d_desc, c->d_sum, c->d_prev_end,
+                       c->d_bitoff, c->d_state, b);
+    mark(kStPack);
+    hipLaunchKernelGGL(k_pack, dim3(n_chunks), dim3(kChunkWords), 0, stream, c->d_desc, c->d_chunk_start, T,
+                       c->d_bitmap, c->d_sum, c->d_prev_end, c->d_bitoff, c->d_state, b, msg8,
+                       (uint64_t)zero_words, c->d_result);
+    mark(kNumStages);
+    if (hipGetLastError() != hipSuccess) return SBC_EHIP;
+    if (hipMemcpyAsync(c->h_result, c->d_result, sizeof(ResultBlock), hipMemcpyDeviceToHost, stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess) {
+        (void)hipGetLastError();
+        return SBC_EHIP;
+    }
+    c->dev_desc_valid = true;
+    c->last_T = T;
+    for (int st = 0; st < kNumStages && lvl > 0; ++st) {
+        if (lvl == 1 && st != kStAccumulate) continue;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, c->ev[st], c->ev[st + 1]) == hipSuccess) {
+            c->stage_ms[st] += (double)ms;
+            c->stage_calls[st] += 1;
+        } else {
+            (void)hipGetLastError();
+        }
+    }
+    const int status = status_of_err(c->h_result->err);
+    if (status != SBC_OK) return status;
+    if (c->h_result->msg_bytes > need) return SBC_EINTERNAL;
+    *msg_bytes = (size_t)c->h_result->msg_bytes;
+    c->last_ok = true;
+    return SBC_OK;
+}
+
+int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, size_t msg_bytes,
+                              const int64_t* numel, int n_tensors, double p, float scale,
+                              float* const* out) {
+    if (!c || !msg || !numel || !out || n_tensors <= 0 || !valid_p(p)) return SBC_EINVAL;
+    if (((uintptr_t)msg & 7u) != 0) return SBC_EINVAL;
+    if (n_tensors > c->max_tensors) return SBC_ECAPACITY;
+    const int T = n_tensors;
+    const int b = bstar_of(p);
+    if (b > kMaxB) return SBC_EINVAL;
+    if (msg_bytes < 32 + 24ull * (unsigned)T) return SBC_ECORRUPT;
+    bool same = c->dev_dec_valid && c->dev_dec_T == T;
+    for (int t = 0; t < T; ++t) {
+        if (numel[t] < 1 || numel[t] >= (int64_t)1 << 32 || !out[t] || ((uintptr_t)out[t] & 3u)) return SBC_EINVAL;
+        if (same && (c->h_dec[t].out != out[t] || c->h_dec[t].n != (uint32_t)numel[t])) same = false;
+    }
+    DeviceGuard guard(c->device);
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    if (!same) {
+        for (int t = 0; t < T; ++t) { c->h_dec[t].out = out[t]; c->h_dec[t].n = (uint32_t)numel[t]; c->h_dec[t].pad = 0; }
+        c->dev_dec_valid = false;
+        if (hipMemcpyAsync(c->d_dec, c->h_dec, sizeof(DecDesc) * T, hipMemcpyHostToDevice, stream) != hipSuccess) {
+            (void)hipGetLastError();
+            return SBC_EHIP;
+        }
+        c->dev_dec_T = T;
+    }
+    hipLaunchKernelGGL(k_reset, dim3(1), dim3(64), 0, stream, (uint32_t*)nullptr, 0u, (uint32_t*)nullptr, 0u, c->d_result);
+    hipLaunchKernelGGL(k_decode_accumulate, dim3(T), dim3(kDecThreads), 0, stream,
+                       static_cast<const uint8_t*>(msg), (unsigned long long)msg_bytes, c->d_dec, T, b, scale,
+                       c->d_result);
+    if (hipGetLastError() != hipSuccess) return SBC_EHIP;
+    if (hipMemcpyAsync(c->h_result, c->d_result, sizeof(ResultBlock), hipMemcpyDeviceToHost, stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess) {
+        (void)hipGetLastError();
+        return SBC_EHIP;
+    }
+    c->dev_dec_valid = true;
+    return status_of_err(c->h_result->err);
+}
+
+int sbc_copy_baseline(void* hip_stream, void* dst, const void* src, size_t bytes) {
+    if (!dst || !src || bytes == 0 || (bytes & 15u) || (((uintptr_t)dst | (uintptr_t)src) & 15u)) return SBC_EINVAL;
+    const uint64_t n16 = bytes / 16;
+    const uint64_t per_block = 256ull * 8ull;
+    const uint64_t blocks = (n16 + per_block - 1) / per_block;
+    if (blocks >= (1ull << 31)) return SBC_EINVAL;
+    hipLaunchKernelGGL(k_copy_baseline, dim3((unsigned)blocks), dim3(256), 0, reinterpret_cast<hipStream_t>(hip_stream),
+                       static_cast<uint4*>(dst), static_cast<const uint4*>(src), n16);
+    return hipGetLastError() == hipSuccess ? SBC_OK : SBC_EHIP;
+}
+
+int sbc_profile_enable(sbc_ctx* c, int level) {
+    if (!c || level < 0 || level > 2) return SBC_EINVAL;
+    c->profile_level = level;
+    for (int st = 0; st < kNumStages; ++st) { c->stage_ms[st] = 0.0; c->stage_calls[st] = 0; }
+    return SBC_OK;
+}
+
+int sbc_profile_read(sbc_ctx* c, int stage, const char** name, double* total_ms, int64_t* calls) {
+    if (!c || stage < 0 || stage >= kNumStages) return SBC_EINVAL;
+    if (name) *name = kStageNames[stage];
+    if (total_ms) *total_ms = c->stage_ms[stage];
+    if (calls) *calls = c->stage_calls[stage];
+    return SBC_OK;
+}
+
+int sbc_last_tensor_stats(sbc_ctx* c, int tensor, double* mu_pos, double* mu_neg, int* side,
+                          int64_t* nnz, int64_t* bit_len) {
+    if (!c || !c->last_ok || tensor < 0 || tensor >= c->last_T) return SBC_EINVAL;
+    DeviceGuard guard(c->device);
+    if (hipMemcpy(c->h_state, c->d_state + tensor, sizeof(TensorState), hipMemcpyDeviceToHost) != hipSuccess) {
+        (void)hipGetLastError();
+        return SBC_EHIP;
+    }
+    const TensorState& s = c->h_state[0];
+    const double k = (double)c->last_desc[tensor].k;
+    if (mu_pos) *mu_pos = s.S[0] / k;
+    if (mu_neg) *mu_neg = s.S[1] / k;
+    if (side) *side = s.side;
+    if (nnz) *nnz = (int64_t)s.nnz;
+    if (bit_len) *bit_len = (int64_t)s.bit_len;
+    return SBC_OK;
+}
+
+int sbc_last_mask(sbc_ctx* c, int tensor, uint32_t* mask_words, size_t n_words) {
+    if (!c || !c->last_ok || !mask_words || tensor < 0 || tensor >= c->last_T) return SBC_EINVAL;
+    const TensorDesc& d = c->last_desc[tensor];
+    if (n_words != ((size_t)d.n + 31) / 32) return SBC_EINVAL;
+    DeviceGuard guard(c->device);
+    if (hipMemcpy(mask_words, c->d_bitmap + (size_t)d.chunk0 * kChunkWords, n_words * 4, hipMemcpyDeviceToHost) != hipSuccess) {
+        (void)hipGetLastError();
+        return SBC_EHIP;
+    }
+    return SBC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,89 @@
+"""The C-ABI library loads, exports every symbol include/sbc.h declares, and its host-side
+scalar helpers agree with the oracle's closed forms.  No GPU compute."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import sbc_oracle as o
+from paper_1805_08768_amd import binding as sbc, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sbc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sbc_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_binding_list_the_same_entry_points():
+    assert declared_functions() == sorted(sbc.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = sbc.load()
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+@pytest.mark.parametrize("p", [0.1, 0.05, 0.01, 0.003, 0.001, 0.0001, 0.5, 0.9])
+def test_bstar_matches_oracle(p):
+    assert sbc.sbc_golomb_bstar(p) == o.golomb_bstar(p)
+
+
+def test_num_kept_matches_oracle():
+    rng = np.random.default_rng(0)
+    for _ in range(2000):
+        n = int(rng.integers(1, 2 ** 31))
+        p = float(10 ** rng.uniform(-5, -0.01))
+        assert sbc.sbc_num_kept(n, p) == o.num_kept(n, p)
+    for n, p in [(64, 0.001), (100, 0.29), (30, 0.1), (2 ** 20, 0.01)]:
+        assert sbc.sbc_num_kept(n, p) == o.num_kept(n, p)
+
+
+def test_invalid_scalars():
+    for bad in (0.0, 1.0, -1.0, 2.0, float("nan")):
+        assert sbc.sbc_golomb_bstar(bad) == sbc.SBC_EINVAL
+        assert sbc.sbc_num_kept(10, bad) == sbc.SBC_EINVAL
+        assert sbc.sbc_msg_bound([10], bad) == 0
+    assert sbc.sbc_num_kept(0, 0.1) == sbc.SBC_EINVAL
+    assert sbc.sbc_msg_bound([0], 0.1) == 0
+    assert sbc.sbc_msg_bound([2 ** 32], 0.1) == 0
+    assert sbc.sbc_msg_bound([5], 1e-12) == 0        # b* beyond what a code word can hold
+
+
+def test_msg_bound_covers_oracle_messages():
+    rng = np.random.default_rng(1)
+    for p in (0.3, 0.05, 0.01, 0.001):
+        sizes = [int(v) for v in rng.integers(1, 5000, 6)]
+        bound = sbc.sbc_msg_bound(sizes, p)
+        # adversarial: kept entries bunched at the end (long first gap), and evenly spread
+        b = o.golomb_bstar(p)
+        worst = 32 + 24 * len(sizes)
+        for n in sizes:
+            k = o.num_kept(n, p)
+            for kept in (np.arange(n - k, n), np.linspace(0, n - 1, k).astype(np.int64)):
+                kept = np.unique(kept)
+                assert 32 + 24 * len(sizes) + 4 * ((len(o.golomb_encode(kept, b)) + 31) // 32) <= bound
+            worst += 4 * ((len(o.golomb_encode(np.arange(n - k, n), b)) + 31) // 32)
+        assert worst <= bound
+        # and real messages
+        dWs = synth.small_model_update(sizes)
+        msg = o.build_message(o.compress_model(dWs, [np.zeros_like(d) for d in dWs], p))
+        assert len(msg) <= bound
+
+
+def test_strerror_and_null_arguments():
+    assert sbc.sbc_strerror(0) == "ok"
+    assert "corrupt" in sbc.sbc_strerror(sbc.SBC_ECORRUPT)
+    lib = sbc.load()
+    assert lib.sbc_compress(None, None, None, None, None, 0, 0.01, None, 0, None) == sbc.SBC_EINVAL
+    assert lib.sbc_decompress_accumulate(None, None, None, 0, None, 0, 0.01, 1.0, None) == sbc.SBC_EINVAL
+    assert lib.sbc_last_tensor_stats(None, 0, None, None, None, None, None) == sbc.SBC_EINVAL
+    assert lib.sbc_create(None, 0, 10, 1) == sbc.SBC_EINVAL
+    ctx = ctypes.c_void_p()
+    assert lib.sbc_create(ctypes.byref(ctx), 0, 0, 1) == sbc.SBC_EINVAL
+    lib.sbc_destroy(None)

@@ -1,0 +1,249 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle on the same seeded inputs.
+
+Bit exact: mask, gap list / bitstream, message bytes, side, nnz, bit length, decoded dense
+update.  Within 1e-5 relative of the fp64 oracle: mu+, mu-, residual at kept positions."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sbc_oracle as o
+from paper_1805_08768_amd import binding as sbc, synth
+from parity_util import DeviceRun, check_round, mask_to_positions
+
+pytestmark = pytest.mark.gpu
+
+
+def run_rounds(sizes, gen, p, rounds=1, check_decode=True):
+    with DeviceRun(sizes) as run:
+        R = [np.zeros(n, np.float32) for n in sizes]
+        for r in range(rounds):
+            print("round", r, "sizes", sizes[:4], "p", p, flush=True)
+            res = check_round(run, gen(r), R, p, check_decode=check_decode)
+            R = [x.R_new for x in res]
+        return res
+
+
+# ---------------------------------------------------------------- small, ragged ----
+
+@pytest.mark.parametrize("p", [0.1, 0.01, 0.001])
+def test_small_ragged_model(p):
+    sizes = [64, 1000, 8192, 8193, 20000, 5, 1, 16384, 40001]
+    run_rounds(sizes, lambda r: synth.small_model_update(sizes, round_=r), p, rounds=2)
+
+
+def test_unaligned_views():
+    """Tensors that are slices of one flat buffer at odd offsets (only 4-byte aligned)."""
+    sizes = [8192 * 2 + 3, 777, 8192]
+    p = 0.01
+    dWs = synth.small_model_update(sizes, round_=3)
+    results = o.compress_model(dWs, [np.zeros_like(d) for d in dWs], p)
+    flat_dw = torch.zeros(sum(sizes) + 16, dtype=torch.float32, device="cuda:0")
+    flat_r = torch.zeros(sum(sizes) + 16, dtype=torch.float32, device="cuda:0")
+    views_dw, views_r, off = [], [], 1
+    for d in dWs:
+        views_dw.append(flat_dw[off:off + len(d)]); views_dw[-1].copy_(torch.from_numpy(d))
+        views_r.append(flat_r[off:off + len(d)])
+        off += len(d) + 1
+    ctx = sbc.sbc_create(0, sum(sizes), len(sizes))
+    try:
+        msg = torch.zeros(sbc.sbc_msg_bound(sizes, p), dtype=torch.uint8, device="cuda:0")
+        nbytes = sbc.sbc_compress(ctx, views_dw, views_r, p, msg)
+        assert msg[:nbytes].cpu().numpy().tobytes() == o.build_message(results)
+        for v, res in zip(views_r, results):
+            assert np.allclose(v.cpu().numpy(), res.R_new, rtol=0, atol=1e-5 * abs(float(res.mu_signed)))
+    finally:
+        sbc.sbc_destroy(ctx)
+
+
+# ------------------------------------------------------------- degenerate inputs ----
+
+def test_degenerate_tensors():
+    sym = (np.array([3, -3, 2, -2, 1, -1, 0, 0] * 100, dtype=np.float32) * 2.0 ** -10)
+    szero = np.zeros(300, np.float32); szero[::2] = -0.0; szero[7] = 1e-30
+    onehot = np.zeros(10000, np.float32); onehot[9999] = -2.0
+    cases = [
+        ("zeros", [np.zeros(5000, np.float32), np.zeros(64, np.float32)], 0.01),
+        ("constant", [np.full(9000, -0.25, np.float32)], 0.05),
+        ("all negative", [-np.abs(synth.gaussian_update(9000))], 0.01),
+        ("symmetric, equal means", [sym], 0.25),
+        ("signed zeros and a denormal-scale entry", [szero], 0.05),
+        ("one hot at the end", [onehot], 0.001),
+        ("keep everything but one", [synth.gaussian_update(50)], 0.99),
+        ("single element", [np.array([-3.5], np.float32)], 0.5),
+        ("denormals", [(synth.gaussian_update(4000) * 1e-36).astype(np.float32)], 0.01),
+        ("huge values", [(synth.gaussian_update(4000) * 1e36).astype(np.float32)], 0.01),
+    ]
+    for name, dWs, p in cases:
+        print("case", name, flush=True)
+        sizes = [len(d) for d in dWs]
+        run_rounds(sizes, lambda r: dWs, p, rounds=2)
+
+
+def test_palette_ties_three_rounds():
+    sizes = [300000, 777]
+    run_rounds(sizes, lambda r: [synth.palette_update(n, round_=r, tensor=i) for i, n in enumerate(sizes)],
+               0.01, rounds=3)
+
+
+def test_long_unary_runs():
+    """Kept entries clustered at the far end: the first gap needs a long run of ones."""
+    n = 3_000_000
+    x = np.zeros(n, np.float32)
+    x[-40:] = np.linspace(1, 2, 40, dtype=np.float32)
+    x[5] = -0.5
+    run_rounds([n], lambda r: [x], 1e-5)      # k = 30, b* = 16
+
+
+# ------------------------------------------------------------------- the configs ----
+
+def test_config1_gaussian_2p20():
+    n = 1 << 20
+    res = run_rounds([n], lambda r: [synth.gaussian_update(n)], 0.01)
+    assert res[0].k == 10485 and res[0].bstar == 6
+
+
+def test_config2_student_t_ten_rounds_with_duplicates():
+    n = 4_194_304
+    with DeviceRun([n]) as run:
+        R = [np.zeros(n, np.float32)]
+        sum_dW = np.zeros(n, np.float64)
+        sum_star = np.zeros(n, np.float64)
+        for r in range(10):
+            print("config 2 round", r, flush=True)
+            dW = synth.student_t_update(n, round_=r)
+            res = check_round(run, [dW], R, 0.001, check_decode=(r in (0, 9)))
+            assert res[0].k == 4194
+            sum_dW += dW
+            sum_star += res[0].dense_update()
+            R = [res[0].R_new]
+        # Eq. 2 telescoped over the ten rounds, on the device's residual
+        R_dev = run.R[0].cpu().numpy().astype(np.float64)
+        scale = max(np.abs(sum_dW).max(), np.abs(R_dev).max())
+        assert np.abs(sum_dW - sum_star - R_dev).max() <= 10 * 2.0 ** -23 * scale
+
+
+def test_config2_companion_palette_full_size():
+    n = 4_194_304
+    run_rounds([n], lambda r: [synth.palette_update(n, round_=r)], 0.001, rounds=3, check_decode=False)
+
+
+def test_config3_resnet50_two_rounds():
+    sizes = synth.numels(synth.resnet50_shapes())
+    res = run_rounds(sizes, lambda r: synth.resnet50_update(round_=r), 0.001, rounds=2)
+    assert sum(x.k for x in res) == 25595
+
+
+def test_config4_lstm_one_round():
+    sizes = synth.numels(synth.lstm_lm_shapes())
+    res = run_rounds(sizes, lambda r: synth.lstm_lm_update(round_=r), 1e-4, rounds=1)
+    assert sum(x.k for x in res) == 6603 and res[0].bstar == 13
+
+
+def test_config5a_server_average_of_clients():
+    """Decode-and-average of client messages for the ResNet-50-shaped model.  The oracle
+    compresses 4 clients at full size (32 would take a quarter of an hour on the host);
+    the accumulation itself runs with scale 1/32 as in the 32-client configuration."""
+    sizes = synth.numels(synth.resnet50_shapes())
+    clients, scale, p = 4, 1.0 / 32, 0.001
+    want = [np.zeros(n, np.float32) for n in sizes]
+    outs = [torch.zeros(n, dtype=torch.float32, device="cuda:0") for n in sizes]
+    with DeviceRun(sizes) as run:
+        for c in range(clients):
+            print("client", c, flush=True)
+            dWs = synth.resnet50_update(client=c + 1)
+            for r in run.R:
+                r.zero_()
+            msg, nbytes = run.compress(dWs, p)
+            results = o.compress_model(dWs, [np.zeros_like(d) for d in dWs], p)
+            want_msg = o.build_message(results)
+            assert msg[:nbytes].cpu().numpy().tobytes() == want_msg
+            sbc.sbc_decompress_accumulate(run.ctx, msg, nbytes, p, scale, outs)
+            o.decode_accumulate(want_msg, sizes, scale, want)
+    for t in range(len(sizes)):
+        assert np.array_equal(outs[t].cpu().numpy(), want[t]), t
+
+
+# ------------------------------------------------------- determinism and errors ----
+
+def test_same_input_twice_gives_identical_bytes():
+    sizes = [1 << 18, 5000, 64]
+    dWs = synth.small_model_update(sizes, round_=9)
+    outs = []
+    for _ in range(3):
+        with DeviceRun(sizes) as run:
+            msg, nbytes = run.compress(dWs, 0.01)
+            outs.append((msg[:nbytes].cpu().numpy().tobytes(), [r.cpu().numpy().tobytes() for r in run.R]))
+    assert outs[0] == outs[1] == outs[2]
+
+
+def test_error_paths():
+    sizes = [5000, 64]
+    dWs = synth.small_model_update(sizes)
+    with DeviceRun(sizes) as run:
+        d_dW = [torch.from_numpy(x).cuda() for x in dWs]
+        bound = sbc.sbc_msg_bound(sizes, 0.01)
+        msg = torch.zeros(bound, dtype=torch.uint8, device="cuda:0")
+
+        def code(fn):
+            with pytest.raises(sbc.SbcError) as e:
+                fn()
+            return e.value.code
+
+        assert code(lambda: sbc.sbc_compress(run.ctx, d_dW, run.R, 0.0, msg)) == sbc.SBC_EINVAL
+        assert code(lambda: sbc.sbc_compress(run.ctx, d_dW, run.R, 1.0, msg)) == sbc.SBC_EINVAL
+        assert code(lambda: sbc.sbc_compress(run.ctx, d_dW, run.R, 0.01, msg[: bound - 8])) == sbc.SBC_ECAPACITY
+        assert code(lambda: sbc.sbc_compress(run.ctx, d_dW, run.R, 0.01, msg[1:])) == sbc.SBC_EINVAL   # misaligned
+        assert code(lambda: sbc.sbc_compress(run.ctx, d_dW, d_dW, 0.01, msg)) == sbc.SBC_EINVAL        # aliasing
+        big = [torch.zeros(6000, device="cuda:0"), torch.zeros(64, device="cuda:0")]
+        assert code(lambda: sbc.sbc_compress(run.ctx, big, [torch.zeros_like(b) for b in big], 0.01,
+                                             torch.zeros(10000, dtype=torch.uint8, device="cuda:0"))) == sbc.SBC_ECAPACITY
+        three = d_dW + [d_dW[0].clone()]
+        assert code(lambda: sbc.sbc_compress(run.ctx, three, [torch.zeros_like(b) for b in three], 0.01,
+                                             msg)) == sbc.SBC_ECAPACITY
+        # non-finite accumulated entry
+        bad = [d_dW[0].clone(), d_dW[1].clone()]
+        bad[0][123] = float("inf")
+        assert code(lambda: sbc.sbc_compress(run.ctx, bad, [torch.zeros_like(b) for b in bad], 0.01, msg)) == sbc.SBC_ENONFINITE
+
+        # a good message, then corrupted variants: never a write out of bounds, always an error
+        for r in run.R:
+            r.zero_()
+        nbytes = sbc.sbc_compress(run.ctx, d_dW, run.R, 0.01, msg)
+        good = msg[:nbytes].clone()
+
+        def decode(m, nb=None, p=0.01, szs=sizes):
+            guard = [torch.zeros(n + 64, dtype=torch.float32, device="cuda:0") for n in szs]
+            outs = [g[32:32 + n] for g, n in zip(guard, szs)]
+            try:
+                sbc.sbc_decompress_accumulate(run.ctx, m, len(m) if nb is None else nb, p, 1.0, outs)
+                rc = 0
+            except sbc.SbcError as e:
+                rc = e.code
+            for g, n in zip(guard, szs):
+                assert not g[:32].any() and not g[32 + n:].any(), "decode wrote out of bounds"
+            return rc
+
+        assert decode(good) == 0
+        assert decode(good, nb=nbytes - 4) == sbc.SBC_ECORRUPT                  # truncated
+        assert decode(good, p=0.001) == sbc.SBC_ECORRUPT                       # b* mismatch
+        assert decode(good, szs=[5000]) == sbc.SBC_ECORRUPT                    # tensor count mismatch
+        assert decode(good, szs=[100, 64]) == sbc.SBC_ECORRUPT                 # positions beyond numel
+        m = good.clone(); m[0] = 0
+        assert decode(m) == sbc.SBC_ECORRUPT                                   # magic
+        m = good.clone(); m[32 + 4] += 1
+        assert decode(m) == sbc.SBC_ECORRUPT                                   # nnz off by one
+        m = good.clone(); m[32 + 8] += 5
+        assert decode(m) == sbc.SBC_ECORRUPT                                   # bit_len too long
+        m = good.clone(); m[32 + 24 * 2: 32 + 24 * 2 + 8] = 0xFF
+        assert decode(m) == sbc.SBC_ECORRUPT                                   # unary run to the end
+
+
+def test_inspection_requires_a_successful_compress():
+    ctx = sbc.sbc_create(0, 1000, 1)
+    try:
+        with pytest.raises(sbc.SbcError):
+            sbc.sbc_last_tensor_stats(ctx, 0)
+        with pytest.raises(sbc.SbcError):
+            sbc.sbc_last_mask(ctx, 0, 100)
+    finally:
+        sbc.sbc_destroy(ctx)
