@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 BYTES_PER_ENTRY = 12           # read dW, read R, write R'
 P = 0.001
 
-# HBM bytes per launch of k_accumulate_hist on this workload from rocprofv3 --pmc runs
+# HBM bytes per launch of k_accumulate_filter on this workload from rocprofv3 --pmc runs
 # (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on the plain copy kernel); see
 # profiles/.  None until measured.
 MEASURED_TRAFFIC_BYTES = None
@@ -107,7 +107,7 @@ def main() -> int:
     prof = {name: (ms, calls) for name, ms, calls in sbc.sbc_profile_read(ctx)}
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     compress_ms = t_compress * 1e3 / args.steps
-    k1_ms, k1_calls = prof["k_accumulate_hist"]
+    k1_ms, k1_calls = prof["k_accumulate_filter"]
     k1_avg_ms = k1_ms / max(1, k1_calls)
     achieved = BYTES_PER_ENTRY * N / (k1_avg_ms * 1e-3) / 1e9
 
@@ -168,7 +168,7 @@ def main() -> int:
                    "step": "sbc_compress + sbc_decompress_accumulate (one client, one round)"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
-                     "kernel": "k_accumulate_hist", "kernel_avg_us": k1_avg_ms * 1e3,
+                     "kernel": "k_accumulate_filter", "kernel_avg_us": k1_avg_ms * 1e3,
                      "algorithmic_bytes_per_launch": BYTES_PER_ENTRY * N},
         "cpu_baseline": cpu,
         "compress_ms": compress_ms,

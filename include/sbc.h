@@ -104,7 +104,7 @@ size_t sbc_msg_bound(const int64_t* numel, int n_tensors, double p);
  * residual[t]  device, read/write, numel[t] floats, must not overlap dW[t]
  * numel        host array
  * msg          device, 8-byte aligned, msg_capacity >= sbc_msg_bound(...) bytes; bytes past
- *              *msg_bytes up to the bound may be overwritten with zeros
+ *              *msg_bytes are not written
  * msg_bytes    host, receives the message size in bytes
  * Errors: SBC_EINVAL, SBC_ECAPACITY (nothing was enqueued), SBC_EHIP, SBC_ENONFINITE and
  * SBC_EINTERNAL (residual and msg contents are then unspecified). */
@@ -128,6 +128,19 @@ int sbc_decompress_accumulate(sbc_ctx* ctx, void* hip_stream,
                               const void* msg, size_t msg_bytes,
                               const int64_t* numel, int n_tensors, double p,
                               float scale, float* const* out);
+
+/* Options of a context.
+ *   SBC_OPT_FORCE_EXACT_PATH  (value 0/1, default 0)  sbc_compress normally finds each tensor's
+ *       candidates with a sampled threshold and falls back, per tensor, to an exact histogram
+ *       of a second read when the sample misleads it; 1 makes every tensor take that second
+ *       path.  The results are identical either way (the option exists to exercise and to time
+ *       the histogram path). */
+enum { SBC_OPT_FORCE_EXACT_PATH = 1 };
+int sbc_set_option(sbc_ctx* ctx, int option, int value);
+
+/* 1 if the most recent successful sbc_compress() had to run the histogram path for at least
+ * one tensor, 0 if not; SBC_EINVAL without a successful call. */
+int sbc_last_used_exact_path(sbc_ctx* ctx);
 
 /* Inspection of the most recent sbc_compress() on this context, for tests and reports
  * (Alg. 2 intermediates).  All out pointers are host memory and may be NULL.

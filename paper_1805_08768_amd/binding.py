@@ -23,11 +23,13 @@ SBC_EHIP = -3
 SBC_ECORRUPT = -4
 SBC_ENONFINITE = -5
 SBC_EINTERNAL = -6
+SBC_OPT_FORCE_EXACT_PATH = 1
 
 EXPORTS = (
     "sbc_create", "sbc_destroy", "sbc_golomb_bstar", "sbc_num_kept", "sbc_msg_bound",
     "sbc_compress", "sbc_decompress_accumulate", "sbc_last_tensor_stats", "sbc_last_mask",
-    "sbc_profile_enable", "sbc_profile_read", "sbc_copy_baseline", "sbc_strerror",
+    "sbc_profile_enable", "sbc_profile_read", "sbc_copy_baseline", "sbc_set_option",
+    "sbc_last_used_exact_path", "sbc_strerror",
 )
 
 
@@ -76,6 +78,10 @@ def load() -> ctypes.CDLL:
     lib.sbc_profile_read.restype = ctypes.c_int
     lib.sbc_copy_baseline.argtypes = [vp, vp, vp, sz]
     lib.sbc_copy_baseline.restype = ctypes.c_int
+    lib.sbc_set_option.argtypes = [vp, ctypes.c_int, ctypes.c_int]
+    lib.sbc_set_option.restype = ctypes.c_int
+    lib.sbc_last_used_exact_path.argtypes = [vp]
+    lib.sbc_last_used_exact_path.restype = ctypes.c_int
     lib.sbc_strerror.argtypes = [ctypes.c_int]
     lib.sbc_strerror.restype = ctypes.c_char_p
     _lib = lib
@@ -231,3 +237,16 @@ def sbc_copy_baseline(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None
                                   ctypes.c_void_p(src.data_ptr()), nbytes)
     if rc != SBC_OK:
         raise SbcError(rc, "sbc_copy_baseline")
+
+
+def sbc_set_option(ctx, option: int, value: int) -> None:
+    rc = load().sbc_set_option(ctx, int(option), int(value))
+    if rc != SBC_OK:
+        raise SbcError(rc, "sbc_set_option")
+
+
+def sbc_last_used_exact_path(ctx) -> bool:
+    rc = load().sbc_last_used_exact_path(ctx)
+    if rc < 0:
+        raise SbcError(rc, "sbc_last_used_exact_path")
+    return bool(rc)

@@ -1,0 +1,411 @@
+// Stage 1 of the client step and the candidate search around it.
+//
+// Fast path (two launches):
+//   k_sample_thresholds  per tensor: a stratified sample of A = R + dW gives, for each sign
+//                        side, a key that is with overwhelming probability at or below the
+//                        k-th most extreme entry of the whole tensor (conservative: only a
+//                        filter, never the answer)
+//   k_accumulate_filter  per chunk: A = R + dW written over R (Alg. 1, client line
+//                        dW_i <- R_i + local update); every entry at or beyond a side's
+//                        filter key is appended to that side's candidate list
+// If a side ends up with fewer than k candidates the filter was too tight for that tensor;
+// the histogram path below then finds its candidates exactly from a second read of A:
+//   k_hist_flagged, k_pick_bins, k_extract
+// Either way the select kernel receives, per tensor and side, a list that contains the k most
+// extreme entries, and the result is exact.
+#pragma once
+
+#include "sbc_device.hpp"
+
+namespace sbc {
+
+// --------------------------------------------------------------------------
+// Plain streaming copy of 16-byte units: the yardstick the streaming kernels are measured
+// against (same workgroup shape and loads in flight as the accumulation kernel).
+// --------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_copy_baseline(uint4* __restrict__ dst, const uint4* __restrict__ src,
+                                                       uint64_t n16) {
+    const uint64_t base = (uint64_t)blockIdx.x * 2048ull + threadIdx.x;
+    if (base - threadIdx.x + 2048ull <= n16) {
+        uint4 v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = src[base + 256ull * i];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) dst[base + 256ull * i] = v[i];
+    } else {
+        for (uint64_t j = base; j < n16; j += 256ull) dst[j] = src[j];
+    }
+}
+
+__global__ __launch_bounds__(256) void k_zero_words(uint32_t* __restrict__ p, uint64_t n) {
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0u;
+}
+
+__device__ __forceinline__ uint32_t mix32(uint32_t x) {
+    x ^= x >> 16; x *= 0x7FEB352Du; x ^= x >> 15; x *= 0x846CA68Bu; x ^= x >> 16;
+    return x;
+}
+
+// --------------------------------------------------------------------------
+// Prefilter thresholds from a sample.  One workgroup per tensor.  Tensors of up to
+// kSampleMax entries are read completely (the threshold is then the exact k-th key to 24
+// bits); larger ones contribute 256 runs of 64 consecutive entries, one run at a pseudo-random
+// place in each of 256 equal strata.  With m sampled entries out of n, lambda = k*m/n of them
+// are expected among the tensor's k most extreme; the filter key is the lower edge of the
+// 24-bit key bucket holding the sample's r-th most extreme entry, r = lambda + 5*sqrt(lambda)
+// + 3, so that the chance of cutting into the true top k is negligible (and harmless: the
+// histogram path then redoes the tensor).  Both sides are selected together, the negative side
+// on complemented keys.  The kernel also clears the per-tensor state and the result block.
+// --------------------------------------------------------------------------
+__global__ __launch_bounds__(kSelThreads) void k_sample_thresholds(
+        const TensorDesc* __restrict__ desc, TensorState* __restrict__ st,
+        ResultBlock* __restrict__ result, int force_exact) {
+    constexpr int PER = kSelRegs;                     // 32 sampled entries per thread
+    constexpr int RUNS = kSampleMax / 64;             // 256
+    __shared__ uint32_t hist[3][2][256];
+    __shared__ uint32_t res[8];
+    __shared__ unsigned long long scratch[kSelThreads / 64];
+    const int t = blockIdx.x, tid = threadIdx.x;
+    const TensorDesc d = desc[t];
+    if (tid == 0) {
+        if (t == 0) { result->err = 0u; result->pad = 0u; result->msg_bytes = 0ull; }
+        TensorState z;
+        z.lo_key[0] = z.lo_key[1] = force_exact ? 0xFFFFFFFFu : 0u;
+        z.cand_cnt[0] = z.cand_cnt[1] = 0u;
+        z.bin[0] = z.bin[1] = 0u;
+        z.tau[0] = z.tau[1] = 0u;
+        z.itau[0] = z.itau[1] = 0u;
+        z.S[0] = z.S[1] = 0.0;
+        z.side = 0; z.mu_signed = 0.f; z.nnz = 0u; z.flags = 0u; z.bit_len = 0ull;
+        st[t] = z;
+    }
+    if (force_exact) return;
+
+    const uint32_t n = d.n;
+    const uint32_t m = n < (uint32_t)kSampleMax ? n : (uint32_t)kSampleMax;
+    uint32_t rs = d.k;
+    if (n > (uint32_t)kSampleMax) {
+        const double lambda = (double)d.k * (double)m / (double)n;
+        rs = (uint32_t)ceil(lambda + 5.0 * sqrt(lambda) + 3.0);
+    }
+    if (rs >= m) return;                              // keep the all-pass keys (0, 0)
+
+    for (int i = tid; i < 3 * 2 * 256; i += kSelThreads) (&hist[0][0][0])[i] = 0u;
+
+    // the sample, as keys in registers
+    uint32_t key[PER];
+    uint32_t valid = 0u;
+    if (n <= (uint32_t)kSampleMax) {
+#pragma unroll
+        for (int s = 0; s < PER; ++s) {
+            const uint32_t i = s * kSelThreads + tid;
+            const bool in = i < n;
+            const float a = d.R[in ? i : 0u] + d.dW[in ? i : 0u];
+            key[s] = key_of_bits(__float_as_uint(a));
+            if (in) valid |= 1u << s;
+        }
+    } else {
+        const unsigned long long slots = n / 64u;     // >= RUNS
+        const uint32_t lane = tid & 63u;
+#pragma unroll
+        for (int s = 0; s < PER; ++s) {
+            const uint32_t run = (uint32_t)s * (kSelThreads / 64) + (tid >> 6);   // 0..RUNS-1
+            const uint32_t h = mix32(run * 0x9E3779B9u + (uint32_t)t * 0x85EBCA6Bu + 1u);
+            const uint32_t s_lo = (uint32_t)(run * slots / RUNS), s_hi = (uint32_t)((run + 1u) * slots / RUNS);
+            const uint32_t i = (s_lo + h % (s_hi - s_lo)) * 64u + lane;
+            const float a = d.R[i] + d.dW[i];
+            key[s] = key_of_bits(__float_as_uint(a));
+        }
+        valid = 0xFFFFFFFFu;
+    }
+    __syncthreads();
+
+    // three bytes of the r-th largest key (positive side) and of the r-th largest complemented
+    // key (negative side)
+    uint32_t need[2] = {rs, rs};
+    bool active[2] = {true, true};
+    uint32_t prefix[2] = {0u, 0u};
+#pragma unroll
+    for (int pass = 0; pass < 3; ++pass) {
+        const int shift = 24 - 8 * pass;
+#pragma unroll
+        for (int s = 0; s < PER; ++s) {
+            if (valid & (1u << s)) {
+                const uint32_t kp = key[s], kn = ~key[s];
+                if (pass == 0 || (kp >> (shift + 8)) == prefix[0]) atomicAdd(&hist[pass][0][(kp >> shift) & 255u], 1u);
+                if (pass == 0 || (kn >> (shift + 8)) == prefix[1]) atomicAdd(&hist[pass][1][(kn >> shift) & 255u], 1u);
+            }
+        }
+        __syncthreads();
+        const BytePick pk = pick_byte_both<kSelThreads>(hist[pass], need, active, res, scratch);
+        if (!pk.found[0] || !pk.found[1]) return;     // uniform; cannot happen; all-pass keys stay
+        prefix[0] = (prefix[0] << 8) | pk.byte[0];
+        prefix[1] = (prefix[1] << 8) | pk.byte[1];
+    }
+    if (tid == 0) {
+        st[t].lo_key[0] = prefix[0] << 8;             // lower edge of the 24-bit bucket
+        st[t].lo_key[1] = prefix[1] << 8;             // same, in the complemented key space
+    }
+}
+
+// --------------------------------------------------------------------------
+// Appends flagged entries of one chunk to the two candidate lists of its tensor with a block
+// scan: used by the histogram path and as the second try of a chunk whose LDS queue
+// overflowed.  key[s] is the plain key of the thread's s-th entry (entry s*NT + tid of the
+// chunk); bit s of mp / mn flags it for the positive / negative list; the negative list stores
+// complemented keys.  Contains barriers; every thread of the workgroup must call it.
+// --------------------------------------------------------------------------
+template <int PER>
+__device__ __forceinline__ void append_candidates(const uint32_t (&key)[PER], uint32_t mp, uint32_t mn,
+                                                  uint32_t e_first, const TensorDesc& d, TensorState* __restrict__ st_t,
+                                                  uint2* __restrict__ cand, ResultBlock* __restrict__ result,
+                                                  uint32_t* scratch, uint32_t* base) {
+    const int tid = threadIdx.x;
+    const uint32_t packed = __popc(mp) | (__popc(mn) << 16);
+    uint32_t total;
+    const uint32_t ex = block_excl_sum<uint32_t, kStreamThreads>(packed, &total, scratch);
+    if (total == 0u) return;                          // uniform
+    if (tid == 0) {
+        const uint32_t tp = total & 0xFFFFu, tn = total >> 16;
+        base[0] = tp ? atomicAdd(&st_t->cand_cnt[0], tp) : 0u;
+        base[1] = tn ? atomicAdd(&st_t->cand_cnt[1], tn) : 0u;
+    }
+    __syncthreads();
+    uint32_t op = base[0] + (ex & 0xFFFFu);
+    uint32_t on = base[1] + (ex >> 16);
+    __syncthreads();                                  // base may be rewritten by the next call
+    if (op + __popc(mp) > d.n || on + __popc(mn) > d.n) {   // cannot happen: a list holds at most n
+        atomicOr(&result->err, kErrInternal);
+        return;
+    }
+    uint2* __restrict__ cp = cand + d.cand_off;
+    uint2* __restrict__ cn = cand + d.cand_off + d.n;
+#pragma unroll
+    for (int s = 0; s < PER; ++s) {
+        const uint32_t idx = e_first + s * kStreamThreads + tid;
+        if (mp & (1u << s)) cp[op++] = make_uint2(key[s], idx);
+        if (mn & (1u << s)) cn[on++] = make_uint2(~key[s], idx);
+    }
+}
+
+// --------------------------------------------------------------------------
+// Residual accumulation fused with the prefilter.  One workgroup per chunk of 8192 entries:
+// 8 x 16-byte loads of each operand in flight per thread, A stored over R, and the few
+// entries at or beyond a side's filter key queued in LDS, then appended to the tensor's
+// candidate list with one atomic per side.  A chunk with more candidates than the queue
+// holds (tie-heavy or constant data) appends them again from a second read of its entries.
+// Chunks of tensors that are encoded from the bitmap also clear their bitmap words and their
+// share of the tensor's staging words.
+// --------------------------------------------------------------------------
+struct FilterShared {
+    uint2 queue[2][kFilterQueue];
+    uint32_t qcnt[2];
+    uint32_t base[2];
+    uint32_t scratch[kStreamThreads / 64];
+};
+
+__device__ __forceinline__ void filter_entry(float a, uint32_t idx, uint32_t lo_p, uint32_t lo_n,
+                                             FilterShared& sh, uint32_t& bad) {
+    const uint32_t u = __float_as_uint(a);
+    if ((u & 0x7F800000u) == 0x7F800000u) bad = 1u;
+    const uint32_t kk = key_of_bits(u);
+    if (kk >= lo_p) {
+        const uint32_t s = atomicAdd(&sh.qcnt[0], 1u);
+        if (s < (uint32_t)kFilterQueue) sh.queue[0][s] = make_uint2(kk, idx);
+    }
+    if (~kk >= lo_n) {
+        const uint32_t s = atomicAdd(&sh.qcnt[1], 1u);
+        if (s < (uint32_t)kFilterQueue) sh.queue[1][s] = make_uint2(~kk, idx);
+    }
+}
+
+__global__ __launch_bounds__(kStreamThreads) void k_accumulate_filter(
+        const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ chunk_tensor,
+        TensorState* __restrict__ st, uint2* __restrict__ cand, uint32_t* __restrict__ bitmap,
+        uint32_t* __restrict__ stage, ResultBlock* __restrict__ result) {
+    __shared__ FilterShared sh;
+    const int tid = threadIdx.x;
+    const uint32_t c = blockIdx.x;
+    const int t = (int)chunk_tensor[c];
+    const TensorDesc d = desc[t];
+    const uint32_t lo_p = st[t].lo_key[0], lo_n = st[t].lo_key[1];
+    const uint32_t cc = c - d.chunk0;
+    const uint32_t e0 = cc * (uint32_t)kChunk;
+    const uint32_t cnt = min((uint32_t)kChunk, d.n - e0);
+    if (tid < 2) sh.qcnt[tid] = 0u;
+
+    if (!(d.flags & kDescFused)) {
+        bitmap[(uint64_t)c * kChunkWords + tid] = 0u;
+        const uint32_t per = (d.bound_words + d.nchunks - 1u) / d.nchunks;
+        const uint32_t lo = per * cc;
+        const uint32_t hi = (lo + per < d.bound_words) ? lo + per : d.bound_words;
+        for (uint32_t w = lo + tid; w < hi; w += kStreamThreads) stage[d.stage_off + w] = 0u;
+    }
+    __syncthreads();
+
+    const float* __restrict__ dw = d.dW + e0;
+    float* __restrict__ r = d.R + e0;
+    uint32_t bad = 0u;
+    const bool vec = (cnt == (uint32_t)kChunk) && ((((uintptr_t)dw | (uintptr_t)r) & 15u) == 0u);
+    if (vec) {
+        const float4* __restrict__ dw4 = reinterpret_cast<const float4*>(dw);
+        float4* __restrict__ r4 = reinterpret_cast<float4*>(r);
+        constexpr int IT = kChunk / 4 / kStreamThreads;   // 8
+        float4 dv[IT], rv[IT];
+#pragma unroll
+        for (int i = 0; i < IT; ++i) {
+            dv[i] = dw4[i * kStreamThreads + tid];
+            rv[i] = r4[i * kStreamThreads + tid];
+        }
+#pragma unroll
+        for (int i = 0; i < IT; ++i) {
+            float4 a;
+            a.x = rv[i].x + dv[i].x;
+            a.y = rv[i].y + dv[i].y;
+            a.z = rv[i].z + dv[i].z;
+            a.w = rv[i].w + dv[i].w;
+            r4[i * kStreamThreads + tid] = a;
+            const uint32_t idx = e0 + (i * kStreamThreads + tid) * 4;
+            filter_entry(a.x, idx + 0, lo_p, lo_n, sh, bad);
+            filter_entry(a.y, idx + 1, lo_p, lo_n, sh, bad);
+            filter_entry(a.z, idx + 2, lo_p, lo_n, sh, bad);
+            filter_entry(a.w, idx + 3, lo_p, lo_n, sh, bad);
+        }
+    } else {
+        for (uint32_t i = tid; i < cnt; i += kStreamThreads) {
+            const float a = r[i] + dw[i];
+            r[i] = a;
+            filter_entry(a, e0 + i, lo_p, lo_n, sh, bad);
+        }
+    }
+    if (bad) atomicOr(&result->err, kErrNonFinite);
+    __syncthreads();
+    const uint32_t qp = sh.qcnt[0], qn = sh.qcnt[1];
+    if (qp <= (uint32_t)kFilterQueue && qn <= (uint32_t)kFilterQueue) {
+        if (qp + qn == 0u) return;
+        if (tid == 0) {
+            sh.base[0] = qp ? atomicAdd(&st[t].cand_cnt[0], qp) : 0u;
+            sh.base[1] = qn ? atomicAdd(&st[t].cand_cnt[1], qn) : 0u;
+        }
+        __syncthreads();
+        if ((uint64_t)sh.base[0] + qp > d.n || (uint64_t)sh.base[1] + qn > d.n) {   // cannot happen
+            if (tid == 0) atomicOr(&result->err, kErrInternal);
+            return;
+        }
+        uint2* __restrict__ cp = cand + d.cand_off + sh.base[0];
+        uint2* __restrict__ cn = cand + d.cand_off + d.n + sh.base[1];
+        for (uint32_t i = tid; i < qp; i += kStreamThreads) cp[i] = sh.queue[0][i];
+        for (uint32_t i = tid; i < qn; i += kStreamThreads) cn[i] = sh.queue[1][i];
+        return;
+    }
+    // queue overflow: append this chunk's candidates from a second read of A, 1024 entries at a time
+    for (uint32_t off = 0; off < cnt; off += 4 * kStreamThreads) {
+        uint32_t key[4];
+        uint32_t mp = 0u, mn = 0u;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const uint32_t i = off + s * kStreamThreads + tid;
+            const bool in = i < cnt;
+            key[s] = key_of_bits(__float_as_uint(r[in ? i : 0u]));
+            if (in && key[s] >= lo_p) mp |= 1u << s;
+            if (in && ~key[s] >= lo_n) mn |= 1u << s;
+        }
+        append_candidates<4>(key, mp, mn, e0 + off, d, &st[t], cand, result, sh.scratch, sh.base);
+    }
+}
+
+// --------------------------------------------------------------------------
+// Histogram path, used only for tensors whose prefilter failed (kStFailed).
+// k_hist_flagged: per chunk, first-digit histogram of A (already stored in R).
+// --------------------------------------------------------------------------
+__global__ __launch_bounds__(kStreamThreads) void k_hist_flagged(
+        const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ chunk_tensor,
+        const TensorState* __restrict__ st, uint32_t* __restrict__ hist) {
+    __shared__ uint32_t lh[kL1Bins];
+    const int tid = threadIdx.x;
+    const uint32_t c = blockIdx.x;
+    const int t = (int)chunk_tensor[c];
+    if (!(st[t].flags & kStFailed)) return;
+    const TensorDesc d = desc[t];
+    const uint32_t e0 = (c - d.chunk0) * (uint32_t)kChunk;
+    const uint32_t cnt = min((uint32_t)kChunk, d.n - e0);
+    for (int i = tid; i < kL1Bins; i += kStreamThreads) lh[i] = 0u;
+    __syncthreads();
+    const float* __restrict__ a = d.R + e0;
+    uint32_t zeros = 0u;
+    for (uint32_t i = tid; i < cnt; i += kStreamThreads) {
+        const uint32_t u = __float_as_uint(a[i]);
+        if ((u << 1) == 0u) ++zeros;
+        else atomicAdd(&lh[key_of_bits(u) >> kL1Shift], 1u);
+    }
+    if (zeros) atomicAdd(&lh[0x80000000u >> kL1Shift], zeros);
+    __syncthreads();
+    uint32_t* __restrict__ gh = hist + (size_t)t * kL1Bins;
+    for (int i = tid; i < kL1Bins; i += kStreamThreads) {
+        const uint32_t v = lh[i];
+        if (v) atomicAdd(&gh[i], v);
+    }
+}
+
+// k_pick_bins: per flagged tensor, the bins that hold the k-th largest and k-th smallest
+// entry; the tensor's candidate lists restart empty and it is handed to the exact pass.
+__global__ __launch_bounds__(256) void k_pick_bins(const TensorDesc* __restrict__ desc,
+                                                   const uint32_t* __restrict__ hist,
+                                                   TensorState* __restrict__ st,
+                                                   ResultBlock* __restrict__ result) {
+    __shared__ uint32_t h[kL1Bins];
+    __shared__ uint32_t res[2];
+    __shared__ uint32_t scratch[4];
+    const int t = blockIdx.x, tid = threadIdx.x;
+    if (!(st[t].flags & kStFailed)) return;
+    const uint32_t k = desc[t].k;
+    for (int i = tid; i < kL1Bins; i += 256) h[i] = hist[(size_t)t * kL1Bins + i];
+    __syncthreads();
+    find_from_top<kL1Bins, 256, false>(h, k, res, scratch);
+    const uint32_t bp = res[0];
+    __syncthreads();
+    find_from_top<kL1Bins, 256, true>(h, k, res, scratch);
+    const uint32_t bn = res[0];
+    if (tid == 0) {
+        if (bp == 0xFFFFFFFFu || bn == 0xFFFFFFFFu) atomicOr(&result->err, kErrInternal);
+        st[t].bin[0] = bp;
+        st[t].bin[1] = bn;                            // complemented-key numbering
+        st[t].cand_cnt[0] = 0u; st[t].cand_cnt[1] = 0u;
+        st[t].flags = kStExact;
+    }
+}
+
+// k_extract: per chunk of a tensor in the exact pass, every entry whose first digit lies in or
+// beyond a side's threshold bin becomes a candidate of that side.
+__global__ __launch_bounds__(kStreamThreads) void k_extract(
+        const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ chunk_tensor,
+        TensorState* __restrict__ st, uint2* __restrict__ cand, ResultBlock* __restrict__ result) {
+    constexpr int PER = kChunk / kStreamThreads;
+    __shared__ uint32_t scratch[kStreamThreads / 64];
+    __shared__ uint32_t base[2];
+    const int tid = threadIdx.x;
+    const uint32_t c = blockIdx.x;
+    const int t = (int)chunk_tensor[c];
+    if (!(st[t].flags & kStExact)) return;
+    const TensorDesc d = desc[t];
+    const uint32_t e0 = (c - d.chunk0) * (uint32_t)kChunk;
+    const uint32_t cnt = min((uint32_t)kChunk, d.n - e0);
+    const uint32_t bin_p = st[t].bin[0];
+    const uint32_t bin_n = (uint32_t)(kL1Bins - 1) - st[t].bin[1];  // in the plain key space
+    const float* __restrict__ a = d.R + e0;
+    uint32_t key[PER];
+    uint32_t mp = 0u, mn = 0u;
+#pragma unroll
+    for (int s = 0; s < PER; ++s) {
+        const uint32_t i = s * kStreamThreads + tid;
+        const bool in = i < cnt;
+        key[s] = key_of_bits(__float_as_uint(a[in ? i : 0u]));
+        const uint32_t bin = key[s] >> kL1Shift;
+        if (in && bin >= bin_p) mp |= 1u << s;
+        if (in && bin <= bin_n) mn |= 1u << s;
+    }
+    append_candidates<PER>(key, mp, mn, e0, d, &st[t], cand, result, scratch, base);
+}
+
+}  // namespace sbc

@@ -27,15 +27,15 @@ struct DecDesc {
     uint32_t pad;
 };
 
-// b bits of the stream starting at bit `pos` (MSB first), 0 <= b <= 30; words past n_words read as 0.
-__device__ __forceinline__ uint32_t read_bits(const uint32_t* __restrict__ words, unsigned long long n_words,
-                                              unsigned long long pos, int b) {
+constexpr int kTileWords = 2 * kDecThreads;   // stream words covered by one tile of segments
+constexpr int kTileSlack = 2;                 // a remainder may reach this many words past the tile
+
+// b bits (MSB first, 0 <= b <= 30) starting at bit `pos` of the tile staged in LDS.
+__device__ __forceinline__ uint32_t read_bits(const uint32_t* tile, uint32_t pos, int b) {
     if (b == 0) return 0u;
-    const unsigned long long w = pos >> 5;
-    const int off = (int)(pos & 31ull);
-    const unsigned long long hi = (w < n_words) ? words[w] : 0u;
-    const unsigned long long lo = (w + 1 < n_words) ? words[w + 1] : 0u;
-    const unsigned long long v = (hi << 32) | lo;
+    const uint32_t w = pos >> 5;
+    const int off = (int)(pos & 31u);
+    const unsigned long long v = ((unsigned long long)tile[w] << 32) | tile[w + 1];
     return (uint32_t)((v >> (64 - off - b)) & ((1ull << b) - 1ull));
 }
 
@@ -51,6 +51,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
     __shared__ uint8_t fn[2][kStates][kDecThreads];       // transition functions, [state][segment]
     __shared__ unsigned long long scratch64[kDecThreads / 64];
     __shared__ uint32_t s_state;
+    __shared__ uint32_t tile[kTileWords + kTileSlack];   // words past the stream read as ones
 
     const int tid = threadIdx.x;
     const int t = blockIdx.x;
@@ -100,15 +101,20 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
 
     for (unsigned long long seg0 = 0; seg0 < n_seg; seg0 += kDecThreads) {
         const unsigned long long seg = seg0 + tid;
-        // the segment's 64 bits; bits at or past bit_len read as ones (never a terminator)
-        unsigned long long w64 = ~0ull;
-        if (seg < n_seg) {
-            const unsigned long long hi = words[2 * seg];
-            const unsigned long long lo = (2 * seg + 1 < n_words) ? words[2 * seg + 1] : 0xFFFFFFFFull;
-            w64 = (hi << 32) | lo;
-            const unsigned long long valid = bit_len - seg * 64ull;
-            if (valid < 64ull) w64 |= (~0ull >> valid);
+        // stage the tile's words in LDS; bits at or past bit_len read as ones (never a terminator)
+        __syncthreads();
+        for (int i = tid; i < kTileWords + kTileSlack; i += kDecThreads) {
+            const unsigned long long w = 2ull * seg0 + (unsigned)i;
+            uint32_t v = 0xFFFFFFFFu;
+            if (w < n_words) {
+                v = words[w];
+                const unsigned long long valid = bit_len - 32ull * w;
+                if (valid < 32ull) v |= (0xFFFFFFFFu >> valid);
+            }
+            tile[i] = v;
         }
+        __syncthreads();
+        const unsigned long long w64 = ((unsigned long long)tile[2 * tid] << 32) | tile[2 * tid + 1];
 
         // ---- exit state for every entry state ----
         for (int s = 0; s < S; ++s) {
@@ -153,7 +159,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
                 const unsigned long long zpos = seg * 64ull + (unsigned)z;
                 if (zpos + 1ull + (unsigned)b > bit_len) { bad = true; break; }
                 ++nT;
-                sR += read_bits(words, n_words, zpos + 1ull, b);
+                sR += read_bits(tile, (uint32_t)(tid * 64 + z + 1), b);
                 x = z + b + 1;
             }
         }
@@ -166,19 +172,28 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
         if (seg < n_seg && !bad) {
             unsigned long long U = carry_U + exU, Tn = carry_T + exT, R = carry_R + exR;
             int x = entry;
+            uint32_t pend[4];                // positions are distinct: update them four at a time
+            int np = 0;
             while (x < 64) {
                 const int z = first_zero_from(w64, x);
                 U += (unsigned)(z - x);
                 if (z == 64) break;
                 const unsigned long long zpos = seg * 64ull + (unsigned)z;
-                R += read_bits(words, n_words, zpos + 1ull, b);
+                R += read_bits(tile, (uint32_t)(tid * 64 + z + 1), b);
                 const unsigned long long pos = (U << b) + R + Tn;
                 if (pos >= n || Tn >= nnz) { bad = true; break; }
                 if (Tn == (unsigned long long)nnz - 1ull && zpos + 1ull + (unsigned)b != bit_len) bad = true;
-                out[pos] += addend;          // positions of one stream are distinct
+                pend[np++] = (uint32_t)pos;
+                if (np == 4) {
+                    const float v0 = out[pend[0]], v1 = out[pend[1]], v2 = out[pend[2]], v3 = out[pend[3]];
+                    out[pend[0]] = v0 + addend; out[pend[1]] = v1 + addend;
+                    out[pend[2]] = v2 + addend; out[pend[3]] = v3 + addend;
+                    np = 0;
+                }
                 ++Tn;
                 x = z + b + 1;
             }
+            for (int i = 0; i < np; ++i) out[pend[i]] += addend;
         }
         carry_U += tile_U; carry_T += tile_T; carry_R += tile_R;
     }

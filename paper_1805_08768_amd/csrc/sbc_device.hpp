@@ -1,6 +1,6 @@
-// Device-side building blocks shared by the SBC kernels: the order-preserving
-// key of an fp32 value, wavefront/block scans for 64-wide wavefronts, and the
-// "find the digit that holds the need-th largest entry" step of a radix select.
+// Device-side building blocks shared by the SBC kernels: the order-preserving key of an
+// fp32 value, wavefront/block scans for 64-wide wavefronts, and the byte-wise radix-select
+// step that serves two independent selections (the two sign sides) at once.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -10,44 +10,65 @@ namespace sbc {
 
 // ---------------------------------------------------------------- layout ----
 
-constexpr int kChunk = 8192;            // entries of one tensor handled by one workgroup
+constexpr int kChunk = 8192;             // entries of one tensor handled by one workgroup
 constexpr int kChunkWords = kChunk / 32; // bitmap words per chunk (= threads of a chunk kernel)
-constexpr int kStreamThreads = 256;     // workgroup size of the streaming kernels
-constexpr int kL1Bits = 10;             // first radix digit: sign, exponent, top mantissa bit
+constexpr int kStreamThreads = 256;      // workgroup size of the streaming kernels
+constexpr int kSelThreads = 512;         // workgroup size of the sample and select kernels
+constexpr int kSelRegs = 32;             // entries per thread held in registers by those kernels
+constexpr uint32_t kSelCache = kSelRegs * kSelThreads;   // 16384
+constexpr int kSampleMax = (int)kSelCache;               // entries sampled per tensor for the prefilter
+
+// first digit of the histogram path: sign, exponent, top three mantissa bits
+constexpr int kL1Bits = 12;
 constexpr int kL1Bins = 1 << kL1Bits;
 constexpr int kL1Shift = 32 - kL1Bits;
-constexpr int kSelThreads = 1024;       // workgroup size of the per-tensor select kernel
-constexpr int kDigBits = 11;            // later digits
-constexpr int kDigBins = 1 << kDigBits;
+
+constexpr int kBucketBits = 11;          // index sort of the fused encoder: buckets by leading index bits
+constexpr int kBuckets = 1 << kBucketBits;
+constexpr uint32_t kFusedMaxK = 6144;    // a tensor with k up to this, and a stream bound of up to
+constexpr uint32_t kFusedMaxWords = 4096; // this many words, is sorted and encoded inside the select kernel
+constexpr int kFilterQueue = 1024;       // candidates per side a chunk can queue in LDS
 
 // error bits raised by kernels (word 0 of the result block)
 constexpr uint32_t kErrNonFinite = 1u;
 constexpr uint32_t kErrInternal = 2u;
 constexpr uint32_t kErrCorrupt = 4u;
+constexpr uint32_t kErrPrefilter = 8u;   // not an error: some tensor needs the histogram path
+
+// TensorDesc::flags
+constexpr uint32_t kDescFused = 1u;      // sorted and encoded inside the select kernel
+// TensorState::flags
+constexpr uint32_t kStFailed = 1u;       // prefilter kept fewer than k candidates on a side
+constexpr uint32_t kStExact = 2u;        // taken over by the histogram path
 
 // One tensor of the call, built on the host.
 struct TensorDesc {
     const float* dW;
-    float* R;           // residual in/out (compress) or accumulator (decode)
-    uint32_t n;         // entries
-    uint32_t k;         // entries kept per side
-    uint32_t chunk0;    // first chunk of this tensor in the call-wide chunk numbering
+    float* R;             // residual, in/out
+    uint32_t n;           // entries
+    uint32_t k;           // entries kept per side
+    uint32_t chunk0;      // first chunk of this tensor in the call-wide chunk numbering
     uint32_t nchunks;
-    uint64_t cand_off;  // candidate list of the positive side starts here; negative side at +n
+    uint64_t cand_off;    // candidate list of the positive side starts here; negative side at +n
+    uint64_t stage_off;   // first word of this tensor's stream in the staging area
+    uint32_t bound_words; // worst-case stream length in words
+    uint32_t kept_off;    // first entry of this tensor in the kept-index scratch
+    uint32_t flags;
+    uint32_t pad;
 };
 
-// Per-tensor results of the select stages, written on the device.
+// Per-tensor results, written on the device.
 struct TensorState {
+    uint32_t lo_key[2];    // prefilter: side keys at or above these become candidates
     uint32_t cand_cnt[2];  // candidates appended per side
-    uint32_t bin[2];       // first-digit bin holding the k-th entry of each side (side key space)
-    uint32_t above[2];     // entries in bins strictly above it
-    uint32_t tau[2];       // full 32-bit threshold key per side
+    uint32_t bin[2];       // histogram path: first-digit bin holding the k-th entry of each side
+    uint32_t tau[2];       // full 32-bit threshold key per side (side key space)
     uint32_t itau[2];      // ties at tau are kept up to this index
     double S[2];           // sum of the k kept values per side (negated on the negative side)
     int32_t side;          // +1 / -1
     float mu_signed;
     uint32_t nnz;
-    uint32_t pad;
+    uint32_t flags;
     uint64_t bit_len;
 };
 
@@ -142,12 +163,12 @@ __device__ __forceinline__ T block_excl_max(T v, T* total, T* smem) {
     return prev > base ? prev : base;
 }
 
-// Radix-select step.  hist (LDS, NB bins) counts entries per digit value; walking the digits
-// from the top (REV = false) or from the bottom (REV = true), find the digit at which the
-// running count first reaches `need` (1 <= need <= sum of hist).  res[0] receives that digit
-// expressed in "top is largest" order (NB-1-digit when REV), res[1] the count strictly
-// before it in walking order.  res[0] stays 0xFFFFFFFF if need exceeds the total.
-// scratch: NT/64 words.  Contains barriers; every thread must call it.
+// Radix-select step over a wide digit (histogram path).  hist (LDS, NB bins) counts entries
+// per digit value; walking the digits from the top (REV = false) or from the bottom
+// (REV = true), find the digit at which the running count first reaches `need`
+// (1 <= need <= sum of hist).  res[0] receives that digit expressed in "top is largest" order
+// (NB-1-digit when REV), res[1] the count strictly before it in walking order.  res[0] stays
+// 0xFFFFFFFF if need exceeds the total.  scratch: NT/64 words.  Contains barriers.
 template <int NB, int NT, bool REV>
 __device__ __forceinline__ void find_from_top(const uint32_t* hist, uint32_t need, uint32_t* res,
                                               uint32_t* scratch) {
@@ -177,14 +198,51 @@ __device__ __forceinline__ void find_from_top(const uint32_t* hist, uint32_t nee
     __syncthreads();
 }
 
-// Which tensor does call-wide chunk c belong to?  chunk_start has T+1 ascending entries.
-__device__ __forceinline__ int tensor_of_chunk(const uint32_t* __restrict__ chunk_start, int T, uint32_t c) {
-    int lo = 0, hi = T;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (chunk_start[mid] <= c) lo = mid; else hi = mid;
+// ------------------------------------------- byte-wise select, two at once ----
+//
+// The select and sample kernels look for the need-th largest 32-bit value of two independent
+// collections (one per sign side) by fixing one byte per pass, most significant first.  For
+// each pass the caller has filled hist[s][0..255] (LDS) with the counts of byte values among
+// the entries of collection s that match the bytes fixed so far.  pick_byte_both finds, for
+// both collections in one block scan, the byte value at which the count from the top reaches
+// need[s]; it lowers need[s] by the count strictly above that byte and returns the byte and
+// the number of entries holding it.  A collection that is not `active` is left alone.  If a
+// need exceeds the total, found[s] stays false.  res: 8 words, scratch: NT/64 u64 (LDS).
+// Contains barriers; every thread must call it.
+struct BytePick {
+    uint32_t byte[2];
+    uint32_t count[2];
+    bool found[2];
+};
+
+template <int NT>
+__device__ __forceinline__ BytePick pick_byte_both(const uint32_t (*hist)[256], uint32_t (&need)[2],
+                                                   const bool (&active)[2], uint32_t* res,
+                                                   unsigned long long* scratch) {
+    static_assert(NT >= 256, "one thread per byte value");
+    const int t = threadIdx.x;
+    if (t < 8) res[t] = (t & 3) == 0 ? 0xFFFFFFFFu : 0u;       // res[4*s + {0: byte, 1: above, 2: count}]
+    uint32_t h0 = 0u, h1 = 0u;
+    if (t < 256) { h0 = active[0] ? hist[0][255 - t] : 0u; h1 = active[1] ? hist[1][255 - t] : 0u; }
+    unsigned long long total;
+    const unsigned long long ex =
+        block_excl_sum<unsigned long long, NT>((unsigned long long)h0 | ((unsigned long long)h1 << 32), &total, scratch);
+    const uint32_t ex0 = (uint32_t)ex, ex1 = (uint32_t)(ex >> 32);
+    if (t < 256) {
+        if (active[0] && ex0 < need[0] && need[0] <= ex0 + h0) { res[0] = 255u - t; res[1] = ex0; res[2] = h0; }
+        if (active[1] && ex1 < need[1] && need[1] <= ex1 + h1) { res[4] = 255u - t; res[5] = ex1; res[6] = h1; }
     }
-    return lo;
+    __syncthreads();
+    BytePick p;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        p.byte[s] = res[4 * s]; p.count[s] = res[4 * s + 2];
+        p.found[s] = active[s] && p.byte[s] != 0xFFFFFFFFu;
+        if (p.found[s]) need[s] -= res[4 * s + 1];
+        p.byte[s] &= 255u;
+    }
+    __syncthreads();                                  // res may be rewritten by the next call
+    return p;
 }
 
 }  // namespace sbc

@@ -5,23 +5,28 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <numeric>
 #include <vector>
 
-#include "sbc_compress_kernels.hpp"
+#include "sbc_accumulate_kernels.hpp"
+#include "sbc_select_kernels.hpp"
+#include "sbc_encode_kernels.hpp"
 #include "sbc_decode_kernels.hpp"
 
 using namespace sbc;
 
 namespace {
-enum Stage { kStReset = 0, kStAccumulate, kStPickBins, kStExtract, kStSelectApply, kStChunkSummary,
-             kStTensorScan, kStPack, kNumStages };
+// kernels of sbc_compress in launch order (the histogram path repeats some of them)
+enum Stage { kStSample = 0, kStAccumulate, kStSelect, kStChunkSummary, kStTensorScan, kStPack, kStGather,
+             kNumStages };
 const char* const kStageNames[kNumStages] = {
-    "k_reset", "k_accumulate_hist", "k_pick_bins", "k_extract", "k_select_apply",
-    "k_chunk_summary", "k_tensor_scan", "k_pack"};
+    "k_sample_thresholds", "k_accumulate_filter", "k_select", "k_chunk_summary", "k_tensor_scan",
+    "k_pack", "k_gather"};
 }  // namespace
 
 struct sbc_ctx {
@@ -29,14 +34,19 @@ struct sbc_ctx {
     int64_t max_elems = 0;
     int max_tensors = 0;
     uint64_t max_chunks = 0;
+    uint64_t kept_cap = 0;
+    uint64_t stage_cap = 0;
 
     // device scratch
     TensorDesc* d_desc = nullptr;
-    uint32_t* d_chunk_start = nullptr;
+    uint32_t* d_chunk_tensor = nullptr;
+    uint32_t* d_order = nullptr;
     uint32_t* d_hist = nullptr;
     TensorState* d_state = nullptr;
     uint2* d_cand = nullptr;
     uint32_t* d_bitmap = nullptr;
+    uint32_t* d_stage = nullptr;
+    uint32_t* d_kept = nullptr;
     ChunkSummary* d_sum = nullptr;
     uint32_t* d_prev_end = nullptr;
     uint64_t* d_bitoff = nullptr;
@@ -45,7 +55,8 @@ struct sbc_ctx {
 
     // pinned host staging
     TensorDesc* h_desc = nullptr;
-    uint32_t* h_chunk_start = nullptr;
+    uint32_t* h_chunk_tensor = nullptr;
+    uint32_t* h_order = nullptr;
     ResultBlock* h_result = nullptr;
     DecDesc* h_dec = nullptr;
     TensorState* h_state = nullptr;
@@ -56,9 +67,12 @@ struct sbc_ctx {
     int dev_dec_T = 0;
     bool dev_dec_valid = false;
 
+    // options
+    int force_exact = 0;
+
     // optional per-kernel timing with HIP events on the caller's stream
     int profile_level = 0;
-    hipEvent_t ev[kNumStages + 1] = {};
+    hipEvent_t ev[2 * kNumStages] = {};
     bool ev_ok = false;
     double stage_ms[kNumStages] = {};
     int64_t stage_calls[kNumStages] = {};
@@ -66,7 +80,9 @@ struct sbc_ctx {
     // last compress call, for the inspection entry points
     int last_T = 0;
     bool last_ok = false;
-    std::vector<TensorDesc> last_desc;
+    bool last_used_exact_path = false;
+    std::vector<TensorDesc> plan;
+    std::vector<uint32_t> plan_order;
 };
 
 namespace {
@@ -108,12 +124,13 @@ template <typename T>
 hipError_t host_alloc(T** p, size_t count) { return hipHostMalloc(reinterpret_cast<void**>(p), count * sizeof(T), hipHostMallocDefault); }
 
 void free_all(sbc_ctx* c) {
-    (void)hipFree(c->d_desc); (void)hipFree(c->d_chunk_start); (void)hipFree(c->d_hist);
-    (void)hipFree(c->d_state); (void)hipFree(c->d_cand); (void)hipFree(c->d_bitmap);
-    (void)hipFree(c->d_sum); (void)hipFree(c->d_prev_end); (void)hipFree(c->d_bitoff);
+    (void)hipFree(c->d_desc); (void)hipFree(c->d_chunk_tensor); (void)hipFree(c->d_order); (void)hipFree(c->d_hist);
+    (void)hipFree(c->d_state); (void)hipFree(c->d_cand); (void)hipFree(c->d_bitmap); (void)hipFree(c->d_stage);
+    (void)hipFree(c->d_kept); (void)hipFree(c->d_sum); (void)hipFree(c->d_prev_end); (void)hipFree(c->d_bitoff);
     (void)hipFree(c->d_result); (void)hipFree(c->d_dec);
     if (c->h_desc) (void)hipHostFree(c->h_desc);
-    if (c->h_chunk_start) (void)hipHostFree(c->h_chunk_start);
+    if (c->h_chunk_tensor) (void)hipHostFree(c->h_chunk_tensor);
+    if (c->h_order) (void)hipHostFree(c->h_order);
     if (c->h_result) (void)hipHostFree(c->h_result);
     if (c->h_dec) (void)hipHostFree(c->h_dec);
     if (c->h_state) (void)hipHostFree(c->h_state);
@@ -179,30 +196,39 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     c->max_elems = max_total_elems;
     c->max_tensors = max_tensors;
     c->max_chunks = (uint64_t)max_total_elems / kChunk + (uint64_t)max_tensors;
+    c->kept_cap = std::min<uint64_t>((uint64_t)max_total_elems, (uint64_t)kFusedMaxK * (uint64_t)max_tensors);
+    // A tensor's stream is at most k(1+b*) + (n-k)/2^b* bits, which stays below 1.3 n for every p
+    // (b* shrinks as p grows); n/16 words plus rounding per tensor is ample, and sbc_compress
+    // checks the actual need against this capacity.
+    c->stage_cap = (uint64_t)max_total_elems / 16 + 2ull * (uint64_t)max_tensors + 64ull;
     DeviceGuard guard(device);
     const size_t T = (size_t)max_tensors;
     bool ok = true;
     ok = ok && dev_alloc(&c->d_desc, T) == hipSuccess;
-    ok = ok && dev_alloc(&c->d_chunk_start, T + 1) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_chunk_tensor, (size_t)c->max_chunks) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_order, T) == hipSuccess;
     ok = ok && dev_alloc(&c->d_hist, T * kL1Bins) == hipSuccess;
     ok = ok && dev_alloc(&c->d_state, T) == hipSuccess;
     ok = ok && dev_alloc(&c->d_cand, 2 * (size_t)max_total_elems) == hipSuccess;
     ok = ok && dev_alloc(&c->d_bitmap, (size_t)c->max_chunks * kChunkWords) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_stage, (size_t)c->stage_cap) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_kept, (size_t)c->kept_cap) == hipSuccess;
     ok = ok && dev_alloc(&c->d_sum, (size_t)c->max_chunks) == hipSuccess;
     ok = ok && dev_alloc(&c->d_prev_end, (size_t)c->max_chunks) == hipSuccess;
     ok = ok && dev_alloc(&c->d_bitoff, (size_t)c->max_chunks) == hipSuccess;
     ok = ok && dev_alloc(&c->d_result, 1) == hipSuccess;
     ok = ok && dev_alloc(&c->d_dec, T) == hipSuccess;
     ok = ok && host_alloc(&c->h_desc, T) == hipSuccess;
-    ok = ok && host_alloc(&c->h_chunk_start, T + 1) == hipSuccess;
+    ok = ok && host_alloc(&c->h_chunk_tensor, (size_t)c->max_chunks) == hipSuccess;
+    ok = ok && host_alloc(&c->h_order, T) == hipSuccess;
     ok = ok && host_alloc(&c->h_result, 1) == hipSuccess;
     ok = ok && host_alloc(&c->h_dec, T) == hipSuccess;
     ok = ok && host_alloc(&c->h_state, T) == hipSuccess;
     if (ok) {
         int made = 0;
-        for (; made <= kNumStages; ++made)
+        for (; made < 2 * kNumStages; ++made)
             if (hipEventCreate(&c->ev[made]) != hipSuccess) break;
-        if (made <= kNumStages) {
+        if (made < 2 * kNumStages) {
             for (int i = 0; i < made; ++i) (void)hipEventDestroy(c->ev[i]);
             ok = false;
         } else {
@@ -226,6 +252,14 @@ void sbc_destroy(sbc_ctx* c) {
     delete c;
 }
 
+int sbc_set_option(sbc_ctx* c, int option, int value) {
+    if (!c) return SBC_EINVAL;
+    switch (option) {
+        case SBC_OPT_FORCE_EXACT_PATH: c->force_exact = value ? 1 : 0; return SBC_OK;
+        default: return SBC_EINVAL;
+    }
+}
+
 int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* const* residual,
                  const int64_t* numel, int n_tensors, double p, void* msg, size_t msg_capacity,
                  size_t* msg_bytes) {
@@ -238,9 +272,11 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
     if (b > kMaxB) return SBC_EINVAL;
     c->last_ok = false;
 
-    // ---- plan: tensor table and chunk numbering ----
-    uint64_t total = 0, chunks = 0, zero_words = 0;
+    // ---- plan: tensor table, chunk numbering, staging layout ----
+    uint64_t total = 0, chunks = 0, stage_words = 0, kept_total = 0, max_bound = 0;
     bool same = c->dev_desc_valid && c->dev_T == T;
+    bool any_bitmap = false;
+    if (c->plan.size() < (size_t)T) c->plan.resize(T);
     for (int t = 0; t < T; ++t) {
         const int64_t n = numel[t];
         if (n < 1 || n >= (int64_t)1 << 32) return SBC_EINVAL;
@@ -258,31 +294,45 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
         d.chunk0 = (uint32_t)chunks;
         d.nchunks = (uint32_t)((n + kChunk - 1) / kChunk);
         d.cand_off = 2 * total;
+        d.stage_off = stage_words;
+        const uint64_t bw = bound_words_of(n, d.k, b);
+        if (bw >= (1ull << 32)) return SBC_ECAPACITY;
+        d.bound_words = (uint32_t)bw;
+        const bool fused = d.k <= kFusedMaxK && bw <= kFusedMaxWords;
+        d.flags = fused ? kDescFused : 0u;
+        d.kept_off = (uint32_t)kept_total;
+        if (fused) kept_total += d.k; else any_bitmap = true;
         if (same && std::memcmp(&d, &c->h_desc[t], sizeof(d)) != 0) same = false;
-        if (!same) { /* keep scanning: validation must see every tensor */ }
         total += (uint64_t)n;
         chunks += d.nchunks;
-        zero_words += bound_words_of(n, d.k, b);
-        if (total > (uint64_t)c->max_elems || chunks > c->max_chunks) return SBC_ECAPACITY;
-        // stage into a scratch copy first: h_desc may still equal the device copy
-        if (c->last_desc.size() < (size_t)T) c->last_desc.resize(T);
-        c->last_desc[t] = d;
+        stage_words += bw;
+        max_bound = std::max<uint64_t>(max_bound, bw);
+        if (total > (uint64_t)c->max_elems || chunks > c->max_chunks || kept_total > c->kept_cap ||
+            stage_words > c->stage_cap)
+            return SBC_ECAPACITY;
+        c->plan[t] = d;                               // h_desc may still mirror the device copy
     }
     if (chunks >= (1ull << 31)) return SBC_ECAPACITY;
-    const size_t need = (size_t)(32 + 24ull * (unsigned)T + 4ull * zero_words);
+    const size_t need = (size_t)(32 + 24ull * (unsigned)T + 4ull * stage_words);
     if (msg_capacity < need) return SBC_ECAPACITY;
 
     DeviceGuard guard(c->device);
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     if (!same) {
+        c->plan_order.resize(T);
+        std::iota(c->plan_order.begin(), c->plan_order.end(), 0u);
+        std::stable_sort(c->plan_order.begin(), c->plan_order.end(),
+                         [&](uint32_t x, uint32_t y) { return c->plan[x].n > c->plan[y].n; });
         for (int t = 0; t < T; ++t) {
-            c->h_desc[t] = c->last_desc[t];
-            c->h_chunk_start[t] = c->last_desc[t].chunk0;
+            c->h_desc[t] = c->plan[t];
+            c->h_order[t] = c->plan_order[t];
+            uint32_t* ct = c->h_chunk_tensor + c->plan[t].chunk0;
+            for (uint32_t j = 0; j < c->plan[t].nchunks; ++j) ct[j] = (uint32_t)t;
         }
-        c->h_chunk_start[T] = (uint32_t)chunks;
         c->dev_desc_valid = false;
         if (hipMemcpyAsync(c->d_desc, c->h_desc, sizeof(TensorDesc) * T, hipMemcpyHostToDevice, stream) != hipSuccess ||
-            hipMemcpyAsync(c->d_chunk_start, c->h_chunk_start, sizeof(uint32_t) * (T + 1), hipMemcpyHostToDevice, stream) != hipSuccess) {
+            hipMemcpyAsync(c->d_order, c->h_order, sizeof(uint32_t) * T, hipMemcpyHostToDevice, stream) != hipSuccess ||
+            hipMemcpyAsync(c->d_chunk_tensor, c->h_chunk_tensor, sizeof(uint32_t) * chunks, hipMemcpyHostToDevice, stream) != hipSuccess) {
             (void)hipGetLastError();
             return SBC_EHIP;
         }
@@ -290,61 +340,100 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
     }
 
     uint8_t* msg8 = static_cast<uint8_t*>(msg);
-    uint32_t* payload = reinterpret_cast<uint32_t*>(msg8 + 32 + 24ull * (unsigned)T);
     const uint32_t n_chunks = (uint32_t)chunks;
-    const uint32_t hist_words = (uint32_t)T * kL1Bins;
-    const uint32_t state_words = (uint32_t)(T * sizeof(TensorState) / 4);
-    const int reset_blocks = (int)((hist_words + 256 * 8 - 1) / (256 * 8));
+    const unsigned gather_y = (unsigned)std::min<uint64_t>(64, std::max<uint64_t>(1, (max_bound + 1023) / 1024));
 
-    // stage boundaries are timed with events only when profiling was asked for
+    // stage boundaries are timed with events only when profiling was asked for:
+    // event 2s is recorded before stage s, event 2s+1 after it
     const int lvl = c->profile_level;
-    auto mark = [&](int stage_begun) {   // called before the kernel of `stage_begun` (kNumStages: after the last)
-        if (lvl >= 2 || (lvl == 1 && (stage_begun == kStAccumulate || stage_begun == kStAccumulate + 1)))
-            (void)hipEventRecord(c->ev[stage_begun], stream);
+    bool timed[kNumStages] = {};
+    auto mark = [&](int stage, bool begin) {
+        if (lvl >= 2 || (lvl == 1 && stage == kStAccumulate)) {
+            (void)hipEventRecord(c->ev[2 * stage + (begin ? 0 : 1)], stream);
+            if (!begin) timed[stage] = true;
+        }
     };
-    mark(kStReset);
-    hipLaunchKernelGGL(k_reset, dim3(reset_blocks), dim3(256), 0, stream, c->d_hist, hist_words,
-                       reinterpret_cast<uint32_t*>(c->d_state), state_words, c->d_result);
-    mark(kStAccumulate);
-    hipLaunchKernelGGL(k_accumulate_hist, dim3(n_chunks), dim3(kStreamThreads), 0, stream, c->d_desc,
-                       c->d_chunk_start, T, c->d_hist, c->d_bitmap, payload, (uint64_t)zero_words, c->d_result);
-    mark(kStPickBins);
-    hipLaunchKernelGGL(k_pick_bins, dim3(T), dim3(256), 0, stream, c->d_desc, c->d_hist, c->d_state, c->d_result);
-    mark(kStExtract);
-    hipLaunchKernelGGL(k_extract, dim3(n_chunks), dim3(kStreamThreads), 0, stream, c->d_desc,
-                       c->d_chunk_start, T, c->d_state, c->d_cand, 1, c->d_result);
-    mark(kStSelectApply);
-    hipLaunchKernelGGL(k_select_apply, dim3(T), dim3(kSelThreads), 0, stream, c->d_desc, c->d_state,
-                       c->d_cand, c->d_bitmap, c->d_result);
-    mark(kStChunkSummary);
-    hipLaunchKernelGGL(k_chunk_summary, dim3(n_chunks), dim3(kChunkWords), 0, stream, c->d_bitmap, c->d_sum, b);
-    mark(kStTensorScan);
-    hipLaunchKernelGGL(k_tensor_scan, dim3(T), dim3(256), 0, stream, c->d_desc, c->d_sum, c->d_prev_end,
-                       c->d_bitoff, c->d_state, b);
-    mark(kStPack);
-    hipLaunchKernelGGL(k_pack, dim3(n_chunks), dim3(kChunkWords), 0, stream, c->d_desc, c->d_chunk_start, T,
-                       c->d_bitmap, c->d_sum, c->d_prev_end, c->d_bitoff, c->d_state, b, msg8,
-                       (uint64_t)zero_words, c->d_result);
-    mark(kNumStages);
-    if (hipGetLastError() != hipSuccess) return SBC_EHIP;
-    if (hipMemcpyAsync(c->h_result, c->d_result, sizeof(ResultBlock), hipMemcpyDeviceToHost, stream) != hipSuccess ||
-        hipStreamSynchronize(stream) != hipSuccess) {
-        (void)hipGetLastError();
-        return SBC_EHIP;
-    }
+    auto encode_and_gather = [&](bool profile) {
+        if (any_bitmap) {
+            if (profile) mark(kStChunkSummary, true);
+            hipLaunchKernelGGL(k_chunk_summary, dim3(n_chunks), dim3(kChunkWords), 0, stream, c->d_desc,
+                               c->d_chunk_tensor, c->d_bitmap, c->d_sum, b);
+            if (profile) { mark(kStChunkSummary, false); mark(kStTensorScan, true); }
+            hipLaunchKernelGGL(k_tensor_scan, dim3(T), dim3(256), 0, stream, c->d_desc, c->d_sum, c->d_prev_end,
+                               c->d_bitoff, c->d_state, b);
+            if (profile) { mark(kStTensorScan, false); mark(kStPack, true); }
+            hipLaunchKernelGGL(k_pack, dim3(n_chunks), dim3(kChunkWords), 0, stream, c->d_desc, c->d_chunk_tensor,
+                               c->d_bitmap, c->d_sum, c->d_prev_end, c->d_bitoff, b, c->d_stage, c->d_result);
+            if (profile) mark(kStPack, false);
+        }
+        if (profile) mark(kStGather, true);
+        hipLaunchKernelGGL(k_gather, dim3(T, gather_y), dim3(256), 0, stream, c->d_desc, c->d_state, T, b,
+                           c->d_stage, msg8, (uint64_t)msg_capacity, c->d_result);
+        if (profile) mark(kStGather, false);
+    };
+    auto finish = [&]() -> int {                      // copy the result block back and wait
+        if (hipGetLastError() != hipSuccess) return SBC_EHIP;
+        if (hipMemcpyAsync(c->h_result, c->d_result, sizeof(ResultBlock), hipMemcpyDeviceToHost, stream) != hipSuccess ||
+            hipStreamSynchronize(stream) != hipSuccess) {
+            (void)hipGetLastError();
+            return SBC_EHIP;
+        }
+        return SBC_OK;
+    };
+
+    // ---- fast path: sample -> accumulate + filter -> select (+ fused encode) -> gather ----
+    mark(kStSample, true);
+    hipLaunchKernelGGL(k_sample_thresholds, dim3(T), dim3(kSelThreads), 0, stream, c->d_desc, c->d_state,
+                       c->d_result, c->force_exact);
+    mark(kStSample, false);
+    mark(kStAccumulate, true);
+    hipLaunchKernelGGL(k_accumulate_filter, dim3(n_chunks), dim3(kStreamThreads), 0, stream, c->d_desc,
+                       c->d_chunk_tensor, c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_result);
+    mark(kStAccumulate, false);
+    mark(kStSelect, true);
+    hipLaunchKernelGGL(k_select, dim3(T), dim3(kSelThreads), 0, stream, c->d_desc, c->d_order,
+                       c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 0, c->d_result);
+    mark(kStSelect, false);
+    encode_and_gather(true);
+    int rc = finish();
+    if (rc != SBC_OK) return rc;
     c->dev_desc_valid = true;
     c->last_T = T;
-    for (int st = 0; st < kNumStages && lvl > 0; ++st) {
-        if (lvl == 1 && st != kStAccumulate) continue;
+    for (int st = 0; st < kNumStages; ++st) {
+        if (!timed[st]) continue;
         float ms = 0.f;
-        if (hipEventElapsedTime(&ms, c->ev[st], c->ev[st + 1]) == hipSuccess) {
+        if (hipEventElapsedTime(&ms, c->ev[2 * st], c->ev[2 * st + 1]) == hipSuccess) {
             c->stage_ms[st] += (double)ms;
             c->stage_calls[st] += 1;
         } else {
             (void)hipGetLastError();
         }
     }
-    const int status = status_of_err(c->h_result->err);
+    uint32_t err = c->h_result->err;
+    c->last_used_exact_path = false;
+
+    // ---- histogram path for the tensors whose filter kept fewer than k candidates ----
+    if ((err & kErrPrefilter) && !(err & (kErrInternal | kErrNonFinite))) {
+        c->last_used_exact_path = true;
+        const uint32_t hist_words = (uint32_t)T * kL1Bins;
+        hipLaunchKernelGGL(k_zero_words, dim3((hist_words + 2047) / 2048), dim3(256), 0, stream, c->d_hist,
+                           (uint64_t)hist_words);
+        hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(c->d_result),
+                           (uint64_t)(sizeof(ResultBlock) / 4));
+        hipLaunchKernelGGL(k_hist_flagged, dim3(n_chunks), dim3(kStreamThreads), 0, stream, c->d_desc,
+                           c->d_chunk_tensor, c->d_state, c->d_hist);
+        hipLaunchKernelGGL(k_pick_bins, dim3(T), dim3(256), 0, stream, c->d_desc, c->d_hist, c->d_state, c->d_result);
+        hipLaunchKernelGGL(k_extract, dim3(n_chunks), dim3(kStreamThreads), 0, stream, c->d_desc,
+                           c->d_chunk_tensor, c->d_state, c->d_cand, c->d_result);
+        hipLaunchKernelGGL(k_select, dim3(T), dim3(kSelThreads), 0, stream, c->d_desc, c->d_order,
+                           c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 1, c->d_result);
+        encode_and_gather(false);
+        rc = finish();
+        if (rc != SBC_OK) return rc;
+        err = c->h_result->err;
+        if (err & kErrPrefilter) return SBC_EINTERNAL;
+    }
+    const int status = status_of_err(err);
     if (status != SBC_OK) return status;
     if (c->h_result->msg_bytes > need) return SBC_EINTERNAL;
     *msg_bytes = (size_t)c->h_result->msg_bytes;
@@ -378,7 +467,8 @@ int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, siz
         }
         c->dev_dec_T = T;
     }
-    hipLaunchKernelGGL(k_reset, dim3(1), dim3(64), 0, stream, (uint32_t*)nullptr, 0u, (uint32_t*)nullptr, 0u, c->d_result);
+    hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(c->d_result),
+                       (uint64_t)(sizeof(ResultBlock) / 4));
     hipLaunchKernelGGL(k_decode_accumulate, dim3(T), dim3(kDecThreads), 0, stream,
                        static_cast<const uint8_t*>(msg), (unsigned long long)msg_bytes, c->d_dec, T, b, scale,
                        c->d_result);
@@ -427,7 +517,7 @@ int sbc_last_tensor_stats(sbc_ctx* c, int tensor, double* mu_pos, double* mu_neg
         return SBC_EHIP;
     }
     const TensorState& s = c->h_state[0];
-    const double k = (double)c->last_desc[tensor].k;
+    const double k = (double)c->plan[tensor].k;
     if (mu_pos) *mu_pos = s.S[0] / k;
     if (mu_neg) *mu_neg = s.S[1] / k;
     if (side) *side = s.side;
@@ -438,14 +528,33 @@ int sbc_last_tensor_stats(sbc_ctx* c, int tensor, double* mu_pos, double* mu_neg
 
 int sbc_last_mask(sbc_ctx* c, int tensor, uint32_t* mask_words, size_t n_words) {
     if (!c || !c->last_ok || !mask_words || tensor < 0 || tensor >= c->last_T) return SBC_EINVAL;
-    const TensorDesc& d = c->last_desc[tensor];
+    const TensorDesc& d = c->plan[tensor];
     if (n_words != ((size_t)d.n + 31) / 32) return SBC_EINVAL;
     DeviceGuard guard(c->device);
+    if (d.flags & kDescFused) {
+        // the select kernel left the sorted kept indices in scratch
+        std::vector<uint32_t> idx(d.k);
+        if (hipMemcpy(idx.data(), c->d_kept + d.kept_off, (size_t)d.k * 4, hipMemcpyDeviceToHost) != hipSuccess) {
+            (void)hipGetLastError();
+            return SBC_EHIP;
+        }
+        std::memset(mask_words, 0, n_words * 4);
+        for (uint32_t j : idx) {
+            if (j >= d.n) return SBC_EINTERNAL;
+            mask_words[j >> 5] |= 1u << (j & 31u);
+        }
+        return SBC_OK;
+    }
     if (hipMemcpy(mask_words, c->d_bitmap + (size_t)d.chunk0 * kChunkWords, n_words * 4, hipMemcpyDeviceToHost) != hipSuccess) {
         (void)hipGetLastError();
         return SBC_EHIP;
     }
     return SBC_OK;
+}
+
+int sbc_last_used_exact_path(sbc_ctx* c) {
+    if (!c || !c->last_ok) return SBC_EINVAL;
+    return c->last_used_exact_path ? 1 : 0;
 }
 
 }  // extern "C"

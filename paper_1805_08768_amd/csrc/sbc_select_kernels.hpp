@@ -1,0 +1,350 @@
+// Alg. 2 in full, Alg. 1's residual line, and (for tensors of ordinary size) Alg. 3.
+//
+// k_select runs one workgroup per tensor and works on both sign sides together:
+//   * a byte-wise radix select (four passes) over each side's candidate list finds the exact
+//     k-th most extreme key tau and the number r of entries equal to tau that are kept; if
+//     fewer than all ties are kept, a second radix select over the tied indices finds the r
+//     lowest (equal values go to the lowest index);
+//   * S, the sum of the k kept values of a side, is accumulated as exact integers per fp32
+//     exponent (independent of the order of the list) and combined in a fixed order in fp64.
+// It then decides the side (positive iff mu+ >= mu-, which for equal counts is S+ >= S-)
+// and applies it:
+//   * residual update R[j] = A[j] - mu_signed at the k kept entries;
+//   * tensors flagged kDescFused: the kept indices are sorted in LDS (bucket by leading
+//     index bits, rank inside the bucket), their gaps Golomb-coded into LDS words and the
+//     stream written to the tensor's staging words;
+//   * other tensors: bit j of the kept-position bitmap is set, and the bitmap kernels encode.
+// Lists of up to kSelCache candidates are held in registers for all passes.
+#pragma once
+
+#include "sbc_device.hpp"
+
+namespace sbc {
+
+__device__ __forceinline__ uint32_t golomb_len(uint32_t gap, int b) { return (gap >> b) + 1u + (uint32_t)b; }
+
+// val (< 2^nb, 1 <= nb <= 32) written MSB-first at bit `pos` of a zero-initialised word array.
+__device__ __forceinline__ void put_bits(uint32_t* words, unsigned long long pos, uint32_t val, int nb) {
+    const unsigned long long w = pos >> 5;
+    const int off = (int)(pos & 31ull);
+    const unsigned long long v = (unsigned long long)val << (64 - off - nb);
+    const uint32_t hi = (uint32_t)(v >> 32), lo = (uint32_t)v;
+    if (hi) atomicOr(&words[w], hi);
+    if (lo) atomicOr(&words[w + 1], lo);
+}
+
+// q one-bits starting at bit `pos`.
+__device__ __forceinline__ void put_ones(uint32_t* words, unsigned long long pos, unsigned long long q) {
+    while (q) {
+        const unsigned long long w = pos >> 5;
+        const uint32_t room = 32u - (uint32_t)(pos & 31ull);
+        const uint32_t take = q < room ? (uint32_t)q : room;
+        if (take == 32u) words[w] = 0xFFFFFFFFu;        // the whole word belongs to this run
+        else atomicOr(&words[w], ((1u << take) - 1u) << (room - take));
+        pos += take;
+        q -= take;
+    }
+}
+
+struct SelectShared {
+    uint32_t hist[2][256];                               // byte histograms of the two sides
+    long long acc[2][256];                               // per-exponent integer sums
+    uint32_t bucket_cnt[kBuckets];                       // index sort: entries per bucket, then offsets
+    uint32_t bucket_fill[kBuckets];
+    uint32_t grp[kFusedMaxK];                            // kept indices grouped by bucket; later stream words
+    uint32_t sorted[kFusedMaxK];                         // kept indices ascending
+    uint32_t res[8];
+    uint32_t scratch[kSelThreads / 64];
+    unsigned long long scratch64[kSelThreads / 64];
+    double S[2];
+};
+static_assert(kFusedMaxWords <= kFusedMaxK, "stream words reuse the grouping array");
+
+// One side's candidate list: (side key, index) pairs, in registers when it fits.
+struct CandView {
+    const uint2* __restrict__ cl;
+    uint32_t cnt;
+    bool cached;
+    uint2 reg[kSelRegs];
+
+    __device__ __forceinline__ void init(const uint2* __restrict__ list, uint32_t count) {
+        cl = list; cnt = count; cached = count <= kSelCache;
+        if (cached) {
+#pragma unroll
+            for (int j = 0; j < kSelRegs; ++j) {
+                const uint32_t i = j * kSelThreads + threadIdx.x;
+                reg[j] = cl[i < cnt ? i : 0u];          // clamped: unconditional loads stay in flight together
+            }
+        }
+    }
+    template <typename F>
+    __device__ __forceinline__ void for_each(F f) const {
+        if (cached) {
+#pragma unroll
+            for (int j = 0; j < kSelRegs; ++j)
+                if (j * kSelThreads + threadIdx.x < cnt) f(reg[j]);
+        } else {
+            for (uint32_t i0 = 0; i0 < cnt; i0 += 8 * kSelThreads) {
+                uint2 e[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t i = i0 + j * kSelThreads + threadIdx.x;
+                    e[j] = cl[i < cnt ? i : cnt - 1u];
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (i0 + j * kSelThreads + threadIdx.x < cnt) f(e[j]);
+            }
+        }
+    }
+};
+
+__device__ __forceinline__ bool cand_kept(uint32_t key, uint32_t idx, uint32_t tau, uint32_t itau) {
+    return key > tau || (key == tau && idx <= itau);
+}
+
+// The need[s]-th largest value of Q(e) over the entries e of side s that pass F(s, e), for both
+// sides at once, one byte per pass.  Returns the values in out[s]; last[s] is the number of
+// entries equal to out[s], need[s] ends as the rank of the wanted entry among those equals.
+// A side that is not active is skipped.  Returns false if a need exceeded a side's population.
+template <typename Q, typename F>
+__device__ __forceinline__ bool select_both(SelectShared& sh, const CandView& cp, const CandView& cn,
+                                            uint32_t (&need)[2], const bool (&active)[2], Q q, F f,
+                                            uint32_t (&out)[2], uint32_t (&last)[2]) {
+    uint32_t prefix[2] = {0u, 0u};
+    bool ok = true;
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        for (int i = threadIdx.x; i < 512; i += kSelThreads) (&sh.hist[0][0])[i] = 0u;
+        __syncthreads();
+        if (active[0]) cp.for_each([&](const uint2& e) {
+            const uint32_t v = q(e);
+            if (f(0, e) && (pass == 0 || (v >> (shift + 8)) == prefix[0])) atomicAdd(&sh.hist[0][(v >> shift) & 255u], 1u);
+        });
+        if (active[1]) cn.for_each([&](const uint2& e) {
+            const uint32_t v = q(e);
+            if (f(1, e) && (pass == 0 || (v >> (shift + 8)) == prefix[1])) atomicAdd(&sh.hist[1][(v >> shift) & 255u], 1u);
+        });
+        __syncthreads();
+        const BytePick pk = pick_byte_both<kSelThreads>(sh.hist, need, active, sh.res, sh.scratch64);
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            if (active[s] && !pk.found[s]) ok = false;
+            prefix[s] = (prefix[s] << 8) | pk.byte[s];
+            last[s] = pk.count[s];
+        }
+    }
+    out[0] = prefix[0]; out[1] = prefix[1];
+    return ok;
+}
+
+// One workgroup per tensor; `order` lists the tensors by decreasing size so that the
+// long-running workgroups start first.  pass 0: every tensor; pass 1: only tensors handed to
+// the histogram path (kStExact).
+__global__ __launch_bounds__(kSelThreads) void k_select(
+        const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ order,
+        TensorState* __restrict__ st, const uint2* __restrict__ cand, uint32_t* __restrict__ bitmap,
+        uint32_t* __restrict__ stage, uint32_t* __restrict__ kept_idx, int b, int pass,
+        ResultBlock* __restrict__ result) {
+    __shared__ SelectShared sh;
+    const int t = (int)order[blockIdx.x], tid = threadIdx.x;
+    if (pass == 1 && !(st[t].flags & kStExact)) return;
+    const TensorDesc d = desc[t];
+    const uint32_t k = d.k, n = d.n;
+    const uint32_t cnt_p = st[t].cand_cnt[0], cnt_n = st[t].cand_cnt[1];
+    if (cnt_p > n || cnt_n > n) {
+        if (tid == 0) atomicOr(&result->err, kErrInternal);
+        return;
+    }
+    if (cnt_p < k || cnt_n < k) {
+        // the filter kept too few entries on a side: the histogram path redoes this tensor
+        if (tid == 0) {
+            st[t].flags = kStFailed;
+            atomicOr(&result->err, pass == 0 ? kErrPrefilter : kErrInternal);
+        }
+        return;
+    }
+    CandView cp, cn;
+    cp.init(cand + d.cand_off, cnt_p);
+    cn.init(cand + d.cand_off + n, cnt_n);
+
+    // exact k-th most extreme key of each side
+    uint32_t need[2] = {k, k}, tau[2], ties[2];
+    const bool both[2] = {true, true};
+    bool ok = select_both(sh, cp, cn, need, both, [](const uint2& e) { return e.x; },
+                          [](int, const uint2&) { return true; }, tau, ties);
+    // need[s] is now the number r of entries equal to tau[s] that are kept (1 <= r <= ties[s])
+    uint32_t itau[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};
+    bool tie_break[2] = {ok && need[0] < ties[0], ok && need[1] < ties[1]};
+    if (tie_break[0] || tie_break[1]) {
+        // the r lowest indices among the ties: the r-th largest complemented index
+        uint32_t rneed[2] = {need[0], need[1]}, ridx[2], one[2];
+        const uint32_t tp = tau[0], tn = tau[1];
+        ok = select_both(sh, cp, cn, rneed, tie_break, [](const uint2& e) { return ~e.y; },
+                         [tp, tn](int s, const uint2& e) { return e.x == (s ? tn : tp); }, ridx, one) && ok;
+        if (tie_break[0]) itau[0] = ~ridx[0];
+        if (tie_break[1]) itau[1] = ~ridx[1];
+    }
+
+    // S+ and S-: exact integer accumulation per fp32 exponent; a thread first adds up runs of
+    // equal exponent in a register
+    for (int i = tid; i < 512; i += kSelThreads) (&sh.acc[0][0])[i] = 0ll;
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const CandView& cv = s ? cn : cp;
+        const uint32_t tk = tau[s], ti = itau[s];
+        uint32_t cur_ex = 0u;
+        long long cur = 0ll;
+        cv.for_each([&](const uint2& e) {
+            if (cand_kept(e.x, e.y, tk, ti)) {
+                const uint32_t u = bits_of_key(s ? ~e.x : e.x);
+                uint32_t ex = (u >> 23) & 0xFFu;
+                long long m = (long long)(ex ? ((u & 0x7FFFFFu) | 0x800000u) : (u & 0x7FFFFFu));
+                if (ex == 0u) ex = 1u;
+                if (((u >> 31) != 0u) != (s != 0)) m = -m;       // the negative side sums -A
+                if (ex != cur_ex) {
+                    if (cur != 0ll) atomicAdd(reinterpret_cast<unsigned long long*>(&sh.acc[s][cur_ex]), (unsigned long long)cur);
+                    cur_ex = ex; cur = 0ll;
+                }
+                cur += m;
+            }
+        });
+        if (cur != 0ll) atomicAdd(reinterpret_cast<unsigned long long*>(&sh.acc[s][cur_ex]), (unsigned long long)cur);
+    }
+    __syncthreads();
+    if (tid < 128) {
+        // fixed order: lane l of wavefront s adds exponents 4l..4l+3 ascending, then a fixed shuffle tree
+        const int s = tid >> 6, lane = tid & 63;
+        double v = 0.0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int ex = 4 * lane + j;
+            v += ldexp((double)sh.acc[s][ex], ex - 150);
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
+        if (lane == 0) sh.S[s] = v;
+    }
+    __syncthreads();
+    const double Sp = sh.S[0], Sn = sh.S[1];
+    const int chosen = (Sp >= Sn) ? 0 : 1;            // mu+ >= mu-  <=>  S+ >= S-  (equal counts)
+    const float mu32 = (float)((chosen ? Sn : Sp) / (double)k);
+    const float mu_signed = chosen ? -mu32 : mu32;
+    if (tid == 0) {
+        st[t].tau[0] = tau[0]; st[t].tau[1] = tau[1];
+        st[t].itau[0] = itau[0]; st[t].itau[1] = itau[1];
+        st[t].S[0] = Sp; st[t].S[1] = Sn;
+        st[t].side = chosen ? -1 : 1;
+        st[t].mu_signed = mu_signed;
+        if (!ok) atomicOr(&result->err, kErrInternal);
+    }
+    if (!ok) return;
+
+    const CandView& cv = chosen ? cn : cp;
+    const uint32_t ktau = tau[chosen], kitau = itau[chosen];
+    float* __restrict__ R = d.R;
+
+    if (!(d.flags & kDescFused)) {
+        // residual update; positions go to the bitmap
+        uint32_t* __restrict__ bm = bitmap + (uint64_t)d.chunk0 * kChunkWords;
+        cv.for_each([&](const uint2& e) {
+            if (cand_kept(e.x, e.y, ktau, kitau)) {
+                if (e.y >= n) { atomicOr(&result->err, kErrInternal); return; }
+                const float a = __uint_as_float(bits_of_key(chosen ? ~e.x : e.x));
+                R[e.y] = a - mu_signed;
+                atomicOr(&bm[e.y >> 5], 1u << (e.y & 31u));
+            }
+        });
+        return;
+    }
+
+    // ---- fused: sort the k kept indices, encode their gaps (Alg. 3), write the stream ----
+    int shift = 32 - __clz((int)(n - 1u | 1u)) - kBucketBits;  // bucket = idx >> shift, below kBuckets
+    if (shift < 0) shift = 0;
+    for (int i = tid; i < kBuckets; i += kSelThreads) { sh.bucket_cnt[i] = 0u; sh.bucket_fill[i] = 0u; }
+    __syncthreads();
+    cv.for_each([&](const uint2& e) {
+        if (cand_kept(e.x, e.y, ktau, kitau) && e.y < n) atomicAdd(&sh.bucket_cnt[e.y >> shift], 1u);
+    });
+    __syncthreads();
+    {   // exclusive scan of the bucket counts, in place: consecutive buckets per thread
+        constexpr int PB = kBuckets / kSelThreads;
+        uint32_t loc[PB], sum = 0u;
+#pragma unroll
+        for (int j = 0; j < PB; ++j) { loc[j] = sh.bucket_cnt[tid * PB + j]; sum += loc[j]; }
+        uint32_t total;
+        uint32_t ex = block_excl_sum<uint32_t, kSelThreads>(sum, &total, sh.scratch);
+#pragma unroll
+        for (int j = 0; j < PB; ++j) { sh.bucket_cnt[tid * PB + j] = ex; ex += loc[j]; }
+        if (total != k) {                             // uniform: every thread sees the same total
+            if (tid == 0) atomicOr(&result->err, kErrInternal);
+            return;
+        }
+    }
+    __syncthreads();
+    cv.for_each([&](const uint2& e) {
+        if (cand_kept(e.x, e.y, ktau, kitau) && e.y < n) {
+            const uint32_t bk = e.y >> shift;
+            sh.grp[sh.bucket_cnt[bk] + atomicAdd(&sh.bucket_fill[bk], 1u)] = e.y;
+            const float a = __uint_as_float(bits_of_key(chosen ? ~e.x : e.x));
+            R[e.y] = a - mu_signed;                   // Alg. 1: R <- dW - dW*
+        }
+    });
+    __syncthreads();
+    for (uint32_t i = tid; i < k; i += kSelThreads) {
+        const uint32_t v = sh.grp[i];
+        const uint32_t bk = v >> shift;
+        const uint32_t lo = sh.bucket_cnt[bk], hi = lo + sh.bucket_fill[bk];
+        uint32_t rank = 0u;
+        for (uint32_t j = lo; j < hi; ++j) rank += (sh.grp[j] < v) ? 1u : 0u;
+        sh.sorted[lo + rank] = v;
+    }
+    __syncthreads();
+
+    // Golomb code lengths of E consecutive entries per thread, then their bit offsets
+    const uint32_t E = (k + kSelThreads - 1) / kSelThreads;
+    const uint32_t i0 = tid * E < k ? tid * E : k;
+    const uint32_t i1 = i0 + E < k ? i0 + E : k;
+    unsigned long long bits = 0ull;
+    {
+        uint32_t pe = i0 ? sh.sorted[i0 - 1] + 1u : 0u;
+        for (uint32_t i = i0; i < i1; ++i) {
+            const uint32_t x = sh.sorted[i];
+            bits += golomb_len(x - pe, b);
+            pe = x + 1u;
+        }
+    }
+    unsigned long long total_bits;
+    unsigned long long pos = block_excl_sum<unsigned long long, kSelThreads>(bits, &total_bits, sh.scratch64);
+    const uint32_t n_words = (uint32_t)((total_bits + 31ull) >> 5);
+    if (n_words > d.bound_words || n_words > kFusedMaxWords) {   // uniform; cannot happen
+        if (tid == 0) atomicOr(&result->err, kErrInternal);
+        return;
+    }
+    uint32_t* words = sh.grp;                         // the grouping array is free again
+    for (uint32_t w = tid; w < n_words + 1u; w += kSelThreads) words[w] = 0u;
+    __syncthreads();
+    {
+        uint32_t pe = i0 ? sh.sorted[i0 - 1] + 1u : 0u;
+        for (uint32_t i = i0; i < i1; ++i) {
+            const uint32_t x = sh.sorted[i];
+            const uint32_t gap = x - pe;
+            const uint32_t q = gap >> b;
+            put_ones(words, pos, q);
+            pos += q;
+            put_bits(words, pos, gap & ((1u << b) - 1u), b + 1);   // the zero and the remainder
+            pos += (unsigned)b + 1u;
+            pe = x + 1u;
+        }
+    }
+    __syncthreads();
+    uint32_t* __restrict__ out = stage + d.stage_off;
+    for (uint32_t w = tid; w < n_words; w += kSelThreads) out[w] = words[w];
+    uint32_t* __restrict__ ki = kept_idx + d.kept_off;
+    for (uint32_t i = tid; i < k; i += kSelThreads) ki[i] = sh.sorted[i];
+    if (tid == 0) { st[t].bit_len = total_bits; st[t].nnz = k; }
+}
+
+}  // namespace sbc

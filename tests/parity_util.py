@@ -89,9 +89,7 @@ def check_round(run: DeviceRun, dWs: Sequence[np.ndarray], R_before: Sequence[np
     assert got_msg == want_msg, "message bytes differ"
     # the cleared-but-unused tail of the payload and the guard bytes behind the bound
     bound = sbc.sbc_msg_bound(run.sizes, p)
-    tail = msg[nbytes:bound].cpu().numpy()
-    assert not tail.any()
-    assert (msg[bound:].cpu().numpy() == 0xAB).all(), "wrote past sbc_msg_bound"
+    assert (msg[nbytes:].cpu().numpy() == 0xAB).all(), "wrote past the message"
 
     if check_decode:
         outs = [torch.zeros(n, dtype=torch.float32, device=run.device) for n in run.sizes]

@@ -94,6 +94,78 @@ def test_long_unary_runs():
     run_rounds([n], lambda r: [x], 1e-5)      # k = 30, b* = 16
 
 
+# ------------------------------------------- candidate search: both routes, all list sizes ----
+
+def test_histogram_path_forced():
+    """SBC_OPT_FORCE_EXACT_PATH sends every tensor through the histogram route; results must
+    be the same as with the sampled filter."""
+    sizes = [64, 1000, 8193, 40001, 300000, 5]
+    for p in (0.1, 0.001):
+        with DeviceRun(sizes) as run:
+            sbc.sbc_set_option(run.ctx, sbc.SBC_OPT_FORCE_EXACT_PATH, 1)
+            R = [np.zeros(n, np.float32) for n in sizes]
+            for r in range(2):
+                res = check_round(run, synth.small_model_update(sizes, round_=r), R, p)
+                assert sbc.sbc_last_used_exact_path(run.ctx)
+                R = [x.R_new for x in res]
+    dWs = [synth.palette_update(200000), np.zeros(70000, np.float32)]
+    with DeviceRun([200000, 70000]) as run:
+        sbc.sbc_set_option(run.ctx, sbc.SBC_OPT_FORCE_EXACT_PATH, 1)
+        check_round(run, dWs, [np.zeros_like(d) for d in dWs], 0.01)
+
+
+def _mix32(x):
+    x &= 0xFFFFFFFF
+    x ^= x >> 16; x = (x * 0x7FEB352D) & 0xFFFFFFFF
+    x ^= x >> 15; x = (x * 0x846CA68B) & 0xFFFFFFFF
+    x ^= x >> 16
+    return x
+
+
+def sampled_positions(n, tensor):
+    """Positions the threshold sampler reads for a tensor of more than 16384 entries: 256 runs of
+    64 entries, one per stratum (mirrors k_sample_thresholds; the test below checks that the
+    histogram route really ran, so a change of the layout shows)."""
+    slots = n // 64
+    pos = []
+    for run in range(256):
+        h = _mix32(run * 0x9E3779B9 + tensor * 0x85EBCA6B + 1)
+        lo, hi = run * slots // 256, (run + 1) * slots // 256
+        first = (lo + h % (hi - lo)) * 64
+        pos.extend(range(first, first + 64))
+    return np.array(pos)
+
+
+def test_misleading_sample_falls_back_per_tensor():
+    """Tensor 1 carries its few large entries exactly where the sampler looks, so the sampled
+    threshold lands above the true k-th entry and the filter keeps too few candidates; the
+    histogram route must redo that tensor only, and the message must still equal the oracle's."""
+    sizes = [50000, 400000, 3000]
+    dWs = synth.small_model_update(sizes, round_=4)
+    x = (np.abs(dWs[1]) * 1e-3).astype(np.float32)           # small noise everywhere
+    pos = sampled_positions(sizes[1], 1)
+    x[pos[::200]] = 5.0                                      # 82 large entries, all of them sampled
+    x[pos[1::200]] = -7.0
+    dWs[1] = x
+    with DeviceRun(sizes) as run:
+        R = [np.zeros(n, np.float32) for n in sizes]
+        res = check_round(run, dWs, R, 0.001)                # k = 400 for tensor 1
+        assert sbc.sbc_last_used_exact_path(run.ctx), "the sample was meant to mislead the filter"
+        # the residual still holds the planted entries, so the next round falls back again
+        check_round(run, synth.small_model_update(sizes, round_=5), [r.R_new for r in res], 0.001)
+    with DeviceRun(sizes) as run:                            # ordinary data: the fast route alone
+        check_round(run, synth.small_model_update(sizes, round_=5), [np.zeros(n, np.float32) for n in sizes], 0.001)
+        assert not sbc.sbc_last_used_exact_path(run.ctx)
+
+
+def test_candidate_lists_beyond_the_register_cache():
+    """Mostly-constant data: the filter cannot separate ties, so the lists hold tens of thousands
+    of candidates (streamed instead of cached) and ties decide the mask."""
+    x = np.zeros(500000, np.float32); x[::7] = 1e-3; x[3::11] = -2e-3
+    y = np.full(100000, 0.125, np.float32)
+    run_rounds([500000, 100000], lambda r: [x, y], 0.01, rounds=2)
+
+
 # ------------------------------------------------------------------- the configs ----
 
 def test_config1_gaussian_2p20():
