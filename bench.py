@@ -74,9 +74,10 @@ def main() -> int:
             off += n
         return out
 
-    dW_sets = [views(f) for f in flat_sets]
-    R = views(flat_R)
-    out = views(flat_out)
+    # pointer tables are marshalled once, as a training loop with persistent buffers would
+    dW_sets = [sbc.TensorList(views(f)) for f in flat_sets]
+    R = sbc.TensorList(views(flat_R))
+    out = sbc.TensorList(views(flat_out))
     bound = sbc.sbc_msg_bound(sizes, P)
     msg = torch.zeros(bound, dtype=torch.uint8, device=dev)
     ctx = sbc.sbc_create(0, N, T)

@@ -107,6 +107,26 @@ def _i64_array(values: Sequence[int]):
     return (ctypes.c_int64 * len(values))(*[int(v) for v in values])
 
 
+class TensorList:
+    """A list of contiguous fp32 device tensors marshalled once into the pointer and size arrays
+    the C ABI takes.  Keeps the tensors alive.  Pass it instead of a plain list when the same
+    buffers are used call after call (weights, residuals, accumulators): marshalling a few
+    hundred tensors in Python costs more than the kernels."""
+
+    def __init__(self, tensors: Sequence[torch.Tensor]):
+        self.tensors = list(tensors)
+        self.ptrs = _ptr_array(self.tensors, torch.float32)
+        self.numel = [t.numel() for t in self.tensors]
+        self.numel_arr = _i64_array(self.numel)
+
+    def __len__(self):
+        return len(self.tensors)
+
+
+def _as_list(x) -> "TensorList":
+    return x if isinstance(x, TensorList) else TensorList(x)
+
+
 def _stream_handle(stream) -> Optional[int]:
     if stream is None:
         stream = torch.cuda.current_stream()
@@ -145,22 +165,19 @@ def sbc_destroy(ctx: ctypes.c_void_p) -> None:
     load().sbc_destroy(ctx)
 
 
-def sbc_compress(ctx, dW: Sequence[torch.Tensor], residual: Sequence[torch.Tensor], p: float,
+def sbc_compress(ctx, dW, residual, p: float,
                  msg: torch.Tensor, stream=None) -> int:
-    """Runs the client step on the given fp32 device tensors; returns the message size in
-    bytes.  `residual` is updated in place, `msg` (uint8 device tensor) receives the message."""
-    if len(dW) != len(residual):
-        raise ValueError("dW and residual must list the same tensors")
-    numel = [t.numel() for t in dW]
-    for a, b in zip(dW, residual):
-        if a.numel() != b.numel():
-            raise ValueError("dW and residual sizes differ")
+    """Runs the client step on the given fp32 device tensors (lists of tensors or TensorList);
+    returns the message size in bytes.  `residual` is updated in place, `msg` (uint8 device
+    tensor) receives the message."""
+    dW, residual = _as_list(dW), _as_list(residual)
+    if dW.numel != residual.numel:
+        raise ValueError("dW and residual must list tensors of the same sizes")
     _check_device(msg)
     if msg.dtype != torch.uint8 or not msg.is_contiguous():
         raise ValueError("msg must be a contiguous uint8 tensor")
     out_bytes = ctypes.c_size_t(0)
-    rc = load().sbc_compress(ctx, _stream_handle(stream), _ptr_array(dW, torch.float32),
-                             _ptr_array(residual, torch.float32), _i64_array(numel), len(numel),
+    rc = load().sbc_compress(ctx, _stream_handle(stream), dW.ptrs, residual.ptrs, dW.numel_arr, len(dW),
                              float(p), ctypes.c_void_p(msg.data_ptr()), msg.numel(), ctypes.byref(out_bytes))
     if rc != SBC_OK:
         raise SbcError(rc, "sbc_compress")
@@ -168,15 +185,15 @@ def sbc_compress(ctx, dW: Sequence[torch.Tensor], residual: Sequence[torch.Tenso
 
 
 def sbc_decompress_accumulate(ctx, msg: torch.Tensor, msg_bytes: int, p: float, scale: float,
-                              out: Sequence[torch.Tensor], stream=None) -> None:
+                              out, stream=None) -> None:
     """Adds scale * (decoded sparse binary update) of one client message into `out`."""
     _check_device(msg)
     if msg.dtype != torch.uint8 or not msg.is_contiguous() or msg_bytes > msg.numel():
         raise ValueError("msg must be a contiguous uint8 tensor holding msg_bytes bytes")
-    numel = [t.numel() for t in out]
+    out = _as_list(out)
     rc = load().sbc_decompress_accumulate(ctx, _stream_handle(stream), ctypes.c_void_p(msg.data_ptr()),
-                                          int(msg_bytes), _i64_array(numel), len(numel), float(p),
-                                          ctypes.c_float(scale), _ptr_array(out, torch.float32))
+                                          int(msg_bytes), out.numel_arr, len(out), float(p),
+                                          ctypes.c_float(scale), out.ptrs)
     if rc != SBC_OK:
         raise SbcError(rc, "sbc_decompress_accumulate")
 

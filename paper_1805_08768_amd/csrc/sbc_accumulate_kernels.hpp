@@ -61,10 +61,12 @@ __device__ __forceinline__ uint32_t mix32(uint32_t x) {
 __global__ __launch_bounds__(kSelThreads) void k_sample_thresholds(
         const TensorDesc* __restrict__ desc, TensorState* __restrict__ st,
         ResultBlock* __restrict__ result, int force_exact) {
-    constexpr int PER = kSelRegs;                     // 32 sampled entries per thread
     constexpr int RUNS = kSampleMax / 64;             // 256
+    constexpr int COPIES = 16;
+    __shared__ uint32_t skey[kSampleMax];             // the sample, as keys (loops stay rolled: small code)
+    __shared__ uint32_t hist0[2][256][COPIES];        // first byte: lane-private copies, one bank each
     __shared__ uint32_t hist[3][2][256];
-    __shared__ uint32_t res[8];
+    __shared__ uint32_t res[3][8];
     __shared__ unsigned long long scratch[kSelThreads / 64];
     const int t = blockIdx.x, tid = threadIdx.x;
     const TensorDesc d = desc[t];
@@ -92,53 +94,66 @@ __global__ __launch_bounds__(kSelThreads) void k_sample_thresholds(
     if (rs >= m) return;                              // keep the all-pass keys (0, 0)
 
     for (int i = tid; i < 3 * 2 * 256; i += kSelThreads) (&hist[0][0][0])[i] = 0u;
-
-    // the sample, as keys in registers
-    uint32_t key[PER];
-    uint32_t valid = 0u;
+    for (int i = tid; i < 2 * 256 * COPIES; i += kSelThreads) (&hist0[0][0][0])[i] = 0u;
+    const float* __restrict__ R = d.R;
+    const float* __restrict__ dW = d.dW;
     if (n <= (uint32_t)kSampleMax) {
-#pragma unroll
-        for (int s = 0; s < PER; ++s) {
-            const uint32_t i = s * kSelThreads + tid;
-            const bool in = i < n;
-            const float a = d.R[in ? i : 0u] + d.dW[in ? i : 0u];
-            key[s] = key_of_bits(__float_as_uint(a));
-            if (in) valid |= 1u << s;
-        }
+#pragma unroll 8
+        for (uint32_t i = tid; i < m; i += kSelThreads)
+            skey[i] = key_of_bits(__float_as_uint(R[i] + dW[i]));
     } else {
         const unsigned long long slots = n / 64u;     // >= RUNS
         const uint32_t lane = tid & 63u;
-#pragma unroll
-        for (int s = 0; s < PER; ++s) {
-            const uint32_t run = (uint32_t)s * (kSelThreads / 64) + (tid >> 6);   // 0..RUNS-1
+#pragma unroll 16
+        for (uint32_t s = 0; s < (uint32_t)(kSampleMax / kSelThreads); ++s) {
+            const uint32_t run = s * (kSelThreads / 64) + (tid >> 6);             // 0..RUNS-1
             const uint32_t h = mix32(run * 0x9E3779B9u + (uint32_t)t * 0x85EBCA6Bu + 1u);
             const uint32_t s_lo = (uint32_t)(run * slots / RUNS), s_hi = (uint32_t)((run + 1u) * slots / RUNS);
             const uint32_t i = (s_lo + h % (s_hi - s_lo)) * 64u + lane;
-            const float a = d.R[i] + d.dW[i];
-            key[s] = key_of_bits(__float_as_uint(a));
+            skey[s * kSelThreads + tid] = key_of_bits(__float_as_uint(R[i] + dW[i]));
         }
-        valid = 0xFFFFFFFFu;
     }
     __syncthreads();
 
     // three bytes of the r-th largest key (positive side) and of the r-th largest complemented
     // key (negative side)
     uint32_t need[2] = {rs, rs};
-    bool active[2] = {true, true};
+    const bool active[2] = {true, true};
     uint32_t prefix[2] = {0u, 0u};
-#pragma unroll
-    for (int pass = 0; pass < 3; ++pass) {
-        const int shift = 24 - 8 * pass;
-#pragma unroll
-        for (int s = 0; s < PER; ++s) {
-            if (valid & (1u << s)) {
-                const uint32_t kp = key[s], kn = ~key[s];
-                if (pass == 0 || (kp >> (shift + 8)) == prefix[0]) atomicAdd(&hist[pass][0][(kp >> shift) & 255u], 1u);
-                if (pass == 0 || (kn >> (shift + 8)) == prefix[1]) atomicAdd(&hist[pass][1][(kn >> shift) & 255u], 1u);
-            }
+    {   // first byte: floating-point keys take only a handful of values here, so every lane group
+        // counts into its own copy and the copies are added up afterwards
+        const int copy = ((tid >> 6) & 1) * 8 + (tid & 7);
+#pragma unroll 8
+        for (uint32_t i = tid; i < m; i += kSelThreads) {
+            const uint32_t kp = skey[i];
+            atomicAdd(&hist0[0][kp >> 24][copy], 1u);
+            atomicAdd(&hist0[1][(~kp) >> 24][copy], 1u);
         }
         __syncthreads();
-        const BytePick pk = pick_byte_both<kSelThreads>(hist[pass], need, active, res, scratch);
+        {
+            uint32_t sum = 0u;
+#pragma unroll
+            for (int c = 0; c < COPIES; ++c) sum += (&hist0[0][0][0])[tid * COPIES + c];   // tid = side*256 + byte
+            (&hist[0][0][0])[tid] = sum;
+        }
+        __syncthreads();
+    }
+#pragma nounroll
+    for (int pass = 0; pass < 3; ++pass) {
+        const int shift = 24 - 8 * pass;
+        if (pass > 0) {
+            RunCounter rp, rn;
+#pragma unroll 8
+            for (uint32_t i = tid; i < m; i += kSelThreads) {
+                const uint32_t kp = skey[i], kn = ~kp;
+                if ((kp >> (shift + 8)) == prefix[0]) rp.add(hist[pass][0], (kp >> shift) & 255u);
+                if ((kn >> (shift + 8)) == prefix[1]) rn.add(hist[pass][1], (kn >> shift) & 255u);
+            }
+            rp.flush(hist[pass][0]);
+            rn.flush(hist[pass][1]);
+            __syncthreads();
+        }
+        const BytePick pk = pick_byte_both<kSelThreads>(hist[pass], need, active, res[pass], scratch);
         if (!pk.found[0] || !pk.found[1]) return;     // uniform; cannot happen; all-pass keys stay
         prefix[0] = (prefix[0] << 8) | pk.byte[0];
         prefix[1] = (prefix[1] << 8) | pk.byte[1];

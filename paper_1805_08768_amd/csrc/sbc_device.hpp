@@ -14,9 +14,7 @@ constexpr int kChunk = 8192;             // entries of one tensor handled by one
 constexpr int kChunkWords = kChunk / 32; // bitmap words per chunk (= threads of a chunk kernel)
 constexpr int kStreamThreads = 256;      // workgroup size of the streaming kernels
 constexpr int kSelThreads = 512;         // workgroup size of the sample and select kernels
-constexpr int kSelRegs = 32;             // entries per thread held in registers by those kernels
-constexpr uint32_t kSelCache = kSelRegs * kSelThreads;   // 16384
-constexpr int kSampleMax = (int)kSelCache;               // entries sampled per tensor for the prefilter
+constexpr int kSampleMax = 16384;        // entries sampled per tensor for the prefilter threshold
 
 // first digit of the histogram path: sign, exponent, top three mantissa bits
 constexpr int kL1Bits = 12;
@@ -198,6 +196,24 @@ __device__ __forceinline__ void find_from_top(const uint32_t* hist, uint32_t nee
     __syncthreads();
 }
 
+// Histogram update that first adds up runs of equal bins in a register: the leading bytes of
+// floating-point keys take very few distinct values, and same-address LDS atomics serialize.
+struct RunCounter {
+    uint32_t bin = 0xFFFFFFFFu;
+    uint32_t cnt = 0u;
+    __device__ __forceinline__ void add(uint32_t* hist, uint32_t b) {
+        if (b != bin) {
+            if (cnt) atomicAdd(&hist[bin], cnt);
+            bin = b; cnt = 0u;
+        }
+        ++cnt;
+    }
+    __device__ __forceinline__ void flush(uint32_t* hist) {
+        if (cnt) atomicAdd(&hist[bin], cnt);
+        cnt = 0u; bin = 0xFFFFFFFFu;
+    }
+};
+
 // ------------------------------------------- byte-wise select, two at once ----
 //
 // The select and sample kernels look for the need-th largest 32-bit value of two independent
@@ -207,8 +223,9 @@ __device__ __forceinline__ void find_from_top(const uint32_t* hist, uint32_t nee
 // both collections in one block scan, the byte value at which the count from the top reaches
 // need[s]; it lowers need[s] by the count strictly above that byte and returns the byte and
 // the number of entries holding it.  A collection that is not `active` is left alone.  If a
-// need exceeds the total, found[s] stays false.  res: 8 words, scratch: NT/64 u64 (LDS).
-// Contains barriers; every thread must call it.
+// need exceeds the total, found[s] stays false.  res: 8 words of LDS that nothing else touches
+// until the caller's next barrier, scratch: NT/64 u64 (LDS).  Contains barriers; every thread
+// must call it.
 struct BytePick {
     uint32_t byte[2];
     uint32_t count[2];
@@ -222,6 +239,7 @@ __device__ __forceinline__ BytePick pick_byte_both(const uint32_t (*hist)[256], 
     static_assert(NT >= 256, "one thread per byte value");
     const int t = threadIdx.x;
     if (t < 8) res[t] = (t & 3) == 0 ? 0xFFFFFFFFu : 0u;       // res[4*s + {0: byte, 1: above, 2: count}]
+    // (the finder threads write res only after the barriers of the scan below)
     uint32_t h0 = 0u, h1 = 0u;
     if (t < 256) { h0 = active[0] ? hist[0][255 - t] : 0u; h1 = active[1] ? hist[1][255 - t] : 0u; }
     unsigned long long total;
@@ -241,7 +259,6 @@ __device__ __forceinline__ BytePick pick_byte_both(const uint32_t (*hist)[256], 
         if (p.found[s]) need[s] -= res[4 * s + 1];
         p.byte[s] &= 255u;
     }
-    __syncthreads();                                  // res may be rewritten by the next call
     return p;
 }
 

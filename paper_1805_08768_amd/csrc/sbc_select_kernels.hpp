@@ -14,7 +14,7 @@
 //     index bits, rank inside the bucket), their gaps Golomb-coded into LDS words and the
 //     stream written to the tensor's staging words;
 //   * other tensors: bit j of the kept-position bitmap is set, and the bitmap kernels encode.
-// Lists of up to kSelCache candidates are held in registers for all passes.
+// Lists of up to kSelLds candidates per side are staged in LDS for all sweeps.
 #pragma once
 
 #include "sbc_device.hpp"
@@ -46,88 +46,87 @@ __device__ __forceinline__ void put_ones(uint32_t* words, unsigned long long pos
     }
 }
 
+constexpr uint32_t kSelLds = 8192;                       // candidates per side staged in LDS
+static_assert(2 * kFusedMaxK * 4 <= kSelLds * 8, "sort arrays reuse one side's candidate space");
+static_assert(kFusedMaxWords <= kFusedMaxK, "stream words reuse the grouping array");
+
 struct SelectShared {
-    uint32_t hist[2][256];                               // byte histograms of the two sides
-    long long acc[2][256];                               // per-exponent integer sums
-    uint32_t bucket_cnt[kBuckets];                       // index sort: entries per bucket, then offsets
-    uint32_t bucket_fill[kBuckets];
-    uint32_t grp[kFusedMaxK];                            // kept indices grouped by bucket; later stream words
-    uint32_t sorted[kFusedMaxK];                         // kept indices ascending
-    uint32_t res[8];
+    uint2 cand[2][kSelLds];                              // both sides' lists when they fit
+    union {
+        struct {
+            uint32_t hist[4][2][256];                    // byte histograms: [pass][side][byte]
+            long long acc[2][256];                       // per-exponent integer sums
+        };
+        struct {                                         // index sort, after the side is decided
+            uint32_t bucket_cnt[kBuckets];               // entries per bucket, then offsets
+            uint32_t bucket_fill[kBuckets];
+        };
+    };
+    uint32_t res[4][8];
     uint32_t scratch[kSelThreads / 64];
     unsigned long long scratch64[kSelThreads / 64];
     double S[2];
 };
-static_assert(kFusedMaxWords <= kFusedMaxK, "stream words reuse the grouping array");
 
-// One side's candidate list: (side key, index) pairs, in registers when it fits.
-struct CandView {
-    const uint2* __restrict__ cl;
-    uint32_t cnt;
-    bool cached;
-    uint2 reg[kSelRegs];
-
-    __device__ __forceinline__ void init(const uint2* __restrict__ list, uint32_t count) {
-        cl = list; cnt = count; cached = count <= kSelCache;
-        if (cached) {
-#pragma unroll
-            for (int j = 0; j < kSelRegs; ++j) {
-                const uint32_t i = j * kSelThreads + threadIdx.x;
-                reg[j] = cl[i < cnt ? i : 0u];          // clamped: unconditional loads stay in flight together
-            }
-        }
-    }
-    template <typename F>
-    __device__ __forceinline__ void for_each(F f) const {
-        if (cached) {
-#pragma unroll
-            for (int j = 0; j < kSelRegs; ++j)
-                if (j * kSelThreads + threadIdx.x < cnt) f(reg[j]);
-        } else {
-            for (uint32_t i0 = 0; i0 < cnt; i0 += 8 * kSelThreads) {
-                uint2 e[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const uint32_t i = i0 + j * kSelThreads + threadIdx.x;
-                    e[j] = cl[i < cnt ? i : cnt - 1u];
-                }
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (i0 + j * kSelThreads + threadIdx.x < cnt) f(e[j]);
-            }
-        }
-    }
+// The candidate lists of a tensor: (side key, index) pairs, staged in LDS when both sides fit,
+// else read from global memory in every sweep.  Sweeps are loops with a small unroll factor on
+// purpose: every workgroup executes this kernel's code only once, so the code must stay small
+// enough to stream through the instruction cache, while a few loads in flight hide latency.
+struct CandLists {
+    const uint2* g[2];
+    uint32_t cnt[2];
+    bool staged;
 };
+
+template <int S, typename F>
+__device__ __forceinline__ void sweep(const SelectShared& sh, const CandLists& l, F f) {
+    if (l.staged) {
+        const uint2* p = sh.cand[S];                    // LDS
+#pragma unroll 4
+        for (uint32_t i = threadIdx.x; i < l.cnt[S]; i += kSelThreads) f(p[i]);
+    } else {
+        const uint2* __restrict__ p = l.g[S];           // global
+#pragma unroll 8
+        for (uint32_t i = threadIdx.x; i < l.cnt[S]; i += kSelThreads) f(p[i]);
+    }
+}
 
 __device__ __forceinline__ bool cand_kept(uint32_t key, uint32_t idx, uint32_t tau, uint32_t itau) {
     return key > tau || (key == tau && idx <= itau);
 }
 
-// The need[s]-th largest value of Q(e) over the entries e of side s that pass F(s, e), for both
-// sides at once, one byte per pass.  Returns the values in out[s]; last[s] is the number of
-// entries equal to out[s], need[s] ends as the rank of the wanted entry among those equals.
-// A side that is not active is skipped.  Returns false if a need exceeded a side's population.
-template <typename Q, typename F>
-__device__ __forceinline__ bool select_both(SelectShared& sh, const CandView& cp, const CandView& cn,
-                                            uint32_t (&need)[2], const bool (&active)[2], Q q, F f,
+// The need[s]-th largest value over the entries of side s, for both sides at once, one byte per
+// pass.  mode 0 ranks side keys over all entries; mode 1 ranks complemented indices over the
+// entries whose key equals tie_key[s] (the lowest indices among ties).  Returns the values in
+// out[s]; last[s] is the number of entries equal to out[s]; need[s] ends as the rank of the
+// wanted entry among those equals.  A side that is not active is skipped.  Returns false if a
+// need exceeded a side's population.  Contains barriers; every thread must call it.
+template <int S>
+__device__ __forceinline__ void byte_histogram(SelectShared& sh, const CandLists& l, int pass, int mode,
+                                               uint32_t pfx, uint32_t tk) {
+    const int shift = 24 - 8 * pass;
+    RunCounter rc;
+    uint32_t* h = sh.hist[pass][S];
+    sweep<S>(sh, l, [&](const uint2& e) {
+        const uint32_t v = mode ? ~e.y : e.x;
+        if ((!mode || e.x == tk) && (pass == 0 || (v >> (shift + 8)) == pfx)) rc.add(h, (v >> shift) & 255u);
+    });
+    rc.flush(h);
+}
+
+__device__ __forceinline__ bool select_both(SelectShared& sh, const CandLists& l, uint32_t (&need)[2],
+                                            const bool (&active)[2], int mode, const uint32_t (&tie_key)[2],
                                             uint32_t (&out)[2], uint32_t (&last)[2]) {
     uint32_t prefix[2] = {0u, 0u};
     bool ok = true;
-#pragma unroll
+    for (int i = threadIdx.x; i < 4 * 2 * 256; i += kSelThreads) (&sh.hist[0][0][0])[i] = 0u;
+    __syncthreads();
+#pragma nounroll
     for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
-        for (int i = threadIdx.x; i < 512; i += kSelThreads) (&sh.hist[0][0])[i] = 0u;
+        if (active[0]) byte_histogram<0>(sh, l, pass, mode, prefix[0], tie_key[0]);
+        if (active[1]) byte_histogram<1>(sh, l, pass, mode, prefix[1], tie_key[1]);
         __syncthreads();
-        if (active[0]) cp.for_each([&](const uint2& e) {
-            const uint32_t v = q(e);
-            if (f(0, e) && (pass == 0 || (v >> (shift + 8)) == prefix[0])) atomicAdd(&sh.hist[0][(v >> shift) & 255u], 1u);
-        });
-        if (active[1]) cn.for_each([&](const uint2& e) {
-            const uint32_t v = q(e);
-            if (f(1, e) && (pass == 0 || (v >> (shift + 8)) == prefix[1])) atomicAdd(&sh.hist[1][(v >> shift) & 255u], 1u);
-        });
-        __syncthreads();
-        const BytePick pk = pick_byte_both<kSelThreads>(sh.hist, need, active, sh.res, sh.scratch64);
+        const BytePick pk = pick_byte_both<kSelThreads>(sh.hist[pass], need, active, sh.res[pass], sh.scratch64);
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             if (active[s] && !pk.found[s]) ok = false;
@@ -135,8 +134,32 @@ __device__ __forceinline__ bool select_both(SelectShared& sh, const CandView& cp
             last[s] = pk.count[s];
         }
     }
+    __syncthreads();                                  // hist and res may be reused by the next selection
     out[0] = prefix[0]; out[1] = prefix[1];
     return ok;
+}
+
+// Adds the kept values of side S into acc[S][exponent] as exact integers; a thread first adds
+// up runs of equal exponent in a register.
+template <int S>
+__device__ __forceinline__ void exponent_sums(SelectShared& sh, const CandLists& l, uint32_t tk, uint32_t ti) {
+    uint32_t cur_ex = 0u;
+    long long cur = 0ll;
+    sweep<S>(sh, l, [&](const uint2& e) {
+        if (cand_kept(e.x, e.y, tk, ti)) {
+            const uint32_t u = bits_of_key(S ? ~e.x : e.x);
+            uint32_t ex = (u >> 23) & 0xFFu;
+            long long m = (long long)(ex ? ((u & 0x7FFFFFu) | 0x800000u) : (u & 0x7FFFFFu));
+            if (ex == 0u) ex = 1u;
+            if (((u >> 31) != 0u) != (S != 0)) m = -m;           // the negative side sums -A
+            if (ex != cur_ex) {
+                if (cur != 0ll) atomicAdd(reinterpret_cast<unsigned long long*>(&sh.acc[S][cur_ex]), (unsigned long long)cur);
+                cur_ex = ex; cur = 0ll;
+            }
+            cur += m;
+        }
+    });
+    if (cur != 0ll) atomicAdd(reinterpret_cast<unsigned long long*>(&sh.acc[S][cur_ex]), (unsigned long long)cur);
 }
 
 // One workgroup per tensor; `order` lists the tensors by decreasing size so that the
@@ -152,7 +175,8 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     if (pass == 1 && !(st[t].flags & kStExact)) return;
     const TensorDesc d = desc[t];
     const uint32_t k = d.k, n = d.n;
-    const uint32_t cnt_p = st[t].cand_cnt[0], cnt_n = st[t].cand_cnt[1];
+    const uint32_t cnt_p = __builtin_amdgcn_readfirstlane(st[t].cand_cnt[0]);
+    const uint32_t cnt_n = __builtin_amdgcn_readfirstlane(st[t].cand_cnt[1]);
     if (cnt_p > n || cnt_n > n) {
         if (tid == 0) atomicOr(&result->err, kErrInternal);
         return;
@@ -165,24 +189,32 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         }
         return;
     }
-    CandView cp, cn;
-    cp.init(cand + d.cand_off, cnt_p);
-    cn.init(cand + d.cand_off + n, cnt_n);
+    CandLists list;
+    list.g[0] = cand + d.cand_off; list.cnt[0] = cnt_p;
+    list.g[1] = cand + d.cand_off + n; list.cnt[1] = cnt_n;
+    list.staged = cnt_p <= kSelLds && cnt_n <= kSelLds;
+    if (list.staged) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const uint2* __restrict__ g = list.g[s];
+#pragma unroll 8
+            for (uint32_t i = tid; i < list.cnt[s]; i += kSelThreads) sh.cand[s][i] = g[i];
+        }
+        __syncthreads();
+    }
 
     // exact k-th most extreme key of each side
     uint32_t need[2] = {k, k}, tau[2], ties[2];
     const bool both[2] = {true, true};
-    bool ok = select_both(sh, cp, cn, need, both, [](const uint2& e) { return e.x; },
-                          [](int, const uint2&) { return true; }, tau, ties);
+    const uint32_t no_key[2] = {0u, 0u};
+    bool ok = select_both(sh, list, need, both, 0, no_key, tau, ties);
     // need[s] is now the number r of entries equal to tau[s] that are kept (1 <= r <= ties[s])
     uint32_t itau[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};
-    bool tie_break[2] = {ok && need[0] < ties[0], ok && need[1] < ties[1]};
+    const bool tie_break[2] = {ok && need[0] < ties[0], ok && need[1] < ties[1]};
     if (tie_break[0] || tie_break[1]) {
         // the r lowest indices among the ties: the r-th largest complemented index
         uint32_t rneed[2] = {need[0], need[1]}, ridx[2], one[2];
-        const uint32_t tp = tau[0], tn = tau[1];
-        ok = select_both(sh, cp, cn, rneed, tie_break, [](const uint2& e) { return ~e.y; },
-                         [tp, tn](int s, const uint2& e) { return e.x == (s ? tn : tp); }, ridx, one) && ok;
+        ok = select_both(sh, list, rneed, tie_break, 1, tau, ridx, one) && ok;
         if (tie_break[0]) itau[0] = ~ridx[0];
         if (tie_break[1]) itau[1] = ~ridx[1];
     }
@@ -191,28 +223,8 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     // equal exponent in a register
     for (int i = tid; i < 512; i += kSelThreads) (&sh.acc[0][0])[i] = 0ll;
     __syncthreads();
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        const CandView& cv = s ? cn : cp;
-        const uint32_t tk = tau[s], ti = itau[s];
-        uint32_t cur_ex = 0u;
-        long long cur = 0ll;
-        cv.for_each([&](const uint2& e) {
-            if (cand_kept(e.x, e.y, tk, ti)) {
-                const uint32_t u = bits_of_key(s ? ~e.x : e.x);
-                uint32_t ex = (u >> 23) & 0xFFu;
-                long long m = (long long)(ex ? ((u & 0x7FFFFFu) | 0x800000u) : (u & 0x7FFFFFu));
-                if (ex == 0u) ex = 1u;
-                if (((u >> 31) != 0u) != (s != 0)) m = -m;       // the negative side sums -A
-                if (ex != cur_ex) {
-                    if (cur != 0ll) atomicAdd(reinterpret_cast<unsigned long long*>(&sh.acc[s][cur_ex]), (unsigned long long)cur);
-                    cur_ex = ex; cur = 0ll;
-                }
-                cur += m;
-            }
-        });
-        if (cur != 0ll) atomicAdd(reinterpret_cast<unsigned long long*>(&sh.acc[s][cur_ex]), (unsigned long long)cur);
-    }
+    exponent_sums<0>(sh, list, tau[0], itau[0]);
+    exponent_sums<1>(sh, list, tau[1], itau[1]);
     __syncthreads();
     if (tid < 128) {
         // fixed order: lane l of wavefront s adds exponents 4l..4l+3 ascending, then a fixed shuffle tree
@@ -242,31 +254,36 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     }
     if (!ok) return;
 
-    const CandView& cv = chosen ? cn : cp;
-    const uint32_t ktau = tau[chosen], kitau = itau[chosen];
+    const uint32_t ktau = chosen ? tau[1] : tau[0], kitau = chosen ? itau[1] : itau[0];
+    // one sweep over the chosen side's list
+    auto sweep_kept = [&](auto f) {
+        if (chosen) sweep<1>(sh, list, [&](const uint2& e) { if (cand_kept(e.x, e.y, ktau, kitau)) f(e); });
+        else sweep<0>(sh, list, [&](const uint2& e) { if (cand_kept(e.x, e.y, ktau, kitau)) f(e); });
+    };
     float* __restrict__ R = d.R;
 
     if (!(d.flags & kDescFused)) {
         // residual update; positions go to the bitmap
         uint32_t* __restrict__ bm = bitmap + (uint64_t)d.chunk0 * kChunkWords;
-        cv.for_each([&](const uint2& e) {
-            if (cand_kept(e.x, e.y, ktau, kitau)) {
-                if (e.y >= n) { atomicOr(&result->err, kErrInternal); return; }
-                const float a = __uint_as_float(bits_of_key(chosen ? ~e.x : e.x));
-                R[e.y] = a - mu_signed;
-                atomicOr(&bm[e.y >> 5], 1u << (e.y & 31u));
-            }
+        sweep_kept([&](const uint2& e) {
+            if (e.y >= n) { atomicOr(&result->err, kErrInternal); return; }
+            const float a = __uint_as_float(bits_of_key(chosen ? ~e.x : e.x));
+            R[e.y] = a - mu_signed;
+            atomicOr(&bm[e.y >> 5], 1u << (e.y & 31u));
         });
         return;
     }
 
     // ---- fused: sort the k kept indices, encode their gaps (Alg. 3), write the stream ----
-    int shift = 32 - __clz((int)(n - 1u | 1u)) - kBucketBits;  // bucket = idx >> shift, below kBuckets
+    // the LDS space of the side that was not chosen holds the sort arrays
+    uint32_t* grp = reinterpret_cast<uint32_t*>(sh.cand[chosen ^ 1]);   // kept indices grouped by bucket
+    uint32_t* sorted = grp + kFusedMaxK;                                // kept indices ascending
+    int shift = 32 - __clz((int)(n - 1u | 1u)) - kBucketBits;           // bucket = idx >> shift, below kBuckets
     if (shift < 0) shift = 0;
     for (int i = tid; i < kBuckets; i += kSelThreads) { sh.bucket_cnt[i] = 0u; sh.bucket_fill[i] = 0u; }
     __syncthreads();
-    cv.for_each([&](const uint2& e) {
-        if (cand_kept(e.x, e.y, ktau, kitau) && e.y < n) atomicAdd(&sh.bucket_cnt[e.y >> shift], 1u);
+    sweep_kept([&](const uint2& e) {
+        if (e.y < n) atomicAdd(&sh.bucket_cnt[e.y >> shift], 1u);
     });
     __syncthreads();
     {   // exclusive scan of the bucket counts, in place: consecutive buckets per thread
@@ -284,22 +301,22 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         }
     }
     __syncthreads();
-    cv.for_each([&](const uint2& e) {
-        if (cand_kept(e.x, e.y, ktau, kitau) && e.y < n) {
+    sweep_kept([&](const uint2& e) {
+        if (e.y < n) {
             const uint32_t bk = e.y >> shift;
-            sh.grp[sh.bucket_cnt[bk] + atomicAdd(&sh.bucket_fill[bk], 1u)] = e.y;
+            grp[sh.bucket_cnt[bk] + atomicAdd(&sh.bucket_fill[bk], 1u)] = e.y;
             const float a = __uint_as_float(bits_of_key(chosen ? ~e.x : e.x));
             R[e.y] = a - mu_signed;                   // Alg. 1: R <- dW - dW*
         }
     });
     __syncthreads();
     for (uint32_t i = tid; i < k; i += kSelThreads) {
-        const uint32_t v = sh.grp[i];
+        const uint32_t v = grp[i];
         const uint32_t bk = v >> shift;
         const uint32_t lo = sh.bucket_cnt[bk], hi = lo + sh.bucket_fill[bk];
         uint32_t rank = 0u;
-        for (uint32_t j = lo; j < hi; ++j) rank += (sh.grp[j] < v) ? 1u : 0u;
-        sh.sorted[lo + rank] = v;
+        for (uint32_t j = lo; j < hi; ++j) rank += (grp[j] < v) ? 1u : 0u;
+        sorted[lo + rank] = v;
     }
     __syncthreads();
 
@@ -309,9 +326,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     const uint32_t i1 = i0 + E < k ? i0 + E : k;
     unsigned long long bits = 0ull;
     {
-        uint32_t pe = i0 ? sh.sorted[i0 - 1] + 1u : 0u;
+        uint32_t pe = i0 ? sorted[i0 - 1] + 1u : 0u;
         for (uint32_t i = i0; i < i1; ++i) {
-            const uint32_t x = sh.sorted[i];
+            const uint32_t x = sorted[i];
             bits += golomb_len(x - pe, b);
             pe = x + 1u;
         }
@@ -323,13 +340,13 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         if (tid == 0) atomicOr(&result->err, kErrInternal);
         return;
     }
-    uint32_t* words = sh.grp;                         // the grouping array is free again
+    uint32_t* words = grp;                            // the grouping array is free again
     for (uint32_t w = tid; w < n_words + 1u; w += kSelThreads) words[w] = 0u;
     __syncthreads();
     {
-        uint32_t pe = i0 ? sh.sorted[i0 - 1] + 1u : 0u;
+        uint32_t pe = i0 ? sorted[i0 - 1] + 1u : 0u;
         for (uint32_t i = i0; i < i1; ++i) {
-            const uint32_t x = sh.sorted[i];
+            const uint32_t x = sorted[i];
             const uint32_t gap = x - pe;
             const uint32_t q = gap >> b;
             put_ones(words, pos, q);
@@ -343,7 +360,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     uint32_t* __restrict__ out = stage + d.stage_off;
     for (uint32_t w = tid; w < n_words; w += kSelThreads) out[w] = words[w];
     uint32_t* __restrict__ ki = kept_idx + d.kept_off;
-    for (uint32_t i = tid; i < k; i += kSelThreads) ki[i] = sh.sorted[i];
+    for (uint32_t i = tid; i < k; i += kSelThreads) ki[i] = sorted[i];
     if (tid == 0) { st[t].bit_len = total_bits; st[t].nnz = k; }
 }
 
