@@ -58,7 +58,7 @@ __device__ __forceinline__ uint32_t mix32(uint32_t x) {
 // histogram path then redoes the tensor).  Both sides are selected together, the negative side
 // on complemented keys.  The kernel also clears the per-tensor state and the result block.
 // --------------------------------------------------------------------------
-__global__ __launch_bounds__(kSelThreads) void k_sample_thresholds(
+__global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
         const TensorDesc* __restrict__ desc, TensorState* __restrict__ st,
         ResultBlock* __restrict__ result, int force_exact) {
     constexpr int RUNS = kSampleMax / 64;             // 256
@@ -67,7 +67,8 @@ __global__ __launch_bounds__(kSelThreads) void k_sample_thresholds(
     __shared__ uint32_t hist0[2][256][COPIES];        // first byte: lane-private copies, one bank each
     __shared__ uint32_t hist[3][2][256];
     __shared__ uint32_t res[3][8];
-    __shared__ unsigned long long scratch[kSelThreads / 64];
+    __shared__ unsigned long long scratch[kSampleThreads / 64];
+    SBC_TS(0, 0);
     const int t = blockIdx.x, tid = threadIdx.x;
     const TensorDesc d = desc[t];
     if (tid == 0) {
@@ -93,28 +94,29 @@ __global__ __launch_bounds__(kSelThreads) void k_sample_thresholds(
     }
     if (rs >= m) return;                              // keep the all-pass keys (0, 0)
 
-    for (int i = tid; i < 3 * 2 * 256; i += kSelThreads) (&hist[0][0][0])[i] = 0u;
-    for (int i = tid; i < 2 * 256 * COPIES; i += kSelThreads) (&hist0[0][0][0])[i] = 0u;
+    for (int i = tid; i < 3 * 2 * 256; i += kSampleThreads) (&hist[0][0][0])[i] = 0u;
+    for (int i = tid; i < 2 * 256 * COPIES; i += kSampleThreads) (&hist0[0][0][0])[i] = 0u;
     const float* __restrict__ R = d.R;
     const float* __restrict__ dW = d.dW;
     if (n <= (uint32_t)kSampleMax) {
 #pragma unroll 8
-        for (uint32_t i = tid; i < m; i += kSelThreads)
+        for (uint32_t i = tid; i < m; i += kSampleThreads)
             skey[i] = key_of_bits(__float_as_uint(R[i] + dW[i]));
     } else {
         const unsigned long long slots = n / 64u;     // >= RUNS
         const uint32_t lane = tid & 63u;
 #pragma unroll 16
-        for (uint32_t s = 0; s < (uint32_t)(kSampleMax / kSelThreads); ++s) {
-            const uint32_t run = s * (kSelThreads / 64) + (tid >> 6);             // 0..RUNS-1
+        for (uint32_t s = 0; s < (uint32_t)(kSampleMax / kSampleThreads); ++s) {
+            const uint32_t run = s * (kSampleThreads / 64) + (tid >> 6);             // 0..RUNS-1
             const uint32_t h = mix32(run * 0x9E3779B9u + (uint32_t)t * 0x85EBCA6Bu + 1u);
             const uint32_t s_lo = (uint32_t)(run * slots / RUNS), s_hi = (uint32_t)((run + 1u) * slots / RUNS);
             const uint32_t i = (s_lo + h % (s_hi - s_lo)) * 64u + lane;
-            skey[s * kSelThreads + tid] = key_of_bits(__float_as_uint(R[i] + dW[i]));
+            skey[s * kSampleThreads + tid] = key_of_bits(__float_as_uint(R[i] + dW[i]));
         }
     }
     __syncthreads();
 
+    SBC_TS(0, 1);                                     // sample loaded
     // three bytes of the r-th largest key (positive side) and of the r-th largest complemented
     // key (negative side)
     uint32_t need[2] = {rs, rs};
@@ -124,7 +126,7 @@ __global__ __launch_bounds__(kSelThreads) void k_sample_thresholds(
         // counts into its own copy and the copies are added up afterwards
         const int copy = ((tid >> 6) & 1) * 8 + (tid & 7);
 #pragma unroll 8
-        for (uint32_t i = tid; i < m; i += kSelThreads) {
+        for (uint32_t i = tid; i < m; i += kSampleThreads) {
             const uint32_t kp = skey[i];
             atomicAdd(&hist0[0][kp >> 24][copy], 1u);
             atomicAdd(&hist0[1][(~kp) >> 24][copy], 1u);
@@ -138,13 +140,14 @@ __global__ __launch_bounds__(kSelThreads) void k_sample_thresholds(
         }
         __syncthreads();
     }
+    SBC_TS(0, 2);                                     // first-byte histogram done
 #pragma nounroll
     for (int pass = 0; pass < 3; ++pass) {
         const int shift = 24 - 8 * pass;
         if (pass > 0) {
             RunCounter rp, rn;
 #pragma unroll 8
-            for (uint32_t i = tid; i < m; i += kSelThreads) {
+            for (uint32_t i = tid; i < m; i += kSampleThreads) {
                 const uint32_t kp = skey[i], kn = ~kp;
                 if ((kp >> (shift + 8)) == prefix[0]) rp.add(hist[pass][0], (kp >> shift) & 255u);
                 if ((kn >> (shift + 8)) == prefix[1]) rn.add(hist[pass][1], (kn >> shift) & 255u);
@@ -153,11 +156,14 @@ __global__ __launch_bounds__(kSelThreads) void k_sample_thresholds(
             rn.flush(hist[pass][1]);
             __syncthreads();
         }
-        const BytePick pk = pick_byte_both<kSelThreads>(hist[pass], need, active, res[pass], scratch);
+        SBC_TS(0, 3 + 2 * pass);
+        const BytePick pk = pick_byte_both<kSampleThreads>(hist[pass], need, active, res[pass], scratch);
+        SBC_TS(0, 4 + 2 * pass);
         if (!pk.found[0] || !pk.found[1]) return;     // uniform; cannot happen; all-pass keys stay
         prefix[0] = (prefix[0] << 8) | pk.byte[0];
         prefix[1] = (prefix[1] << 8) | pk.byte[1];
     }
+    SBC_TS(0, 9);
     if (tid == 0) {
         st[t].lo_key[0] = prefix[0] << 8;             // lower edge of the 24-bit bucket
         st[t].lo_key[1] = prefix[1] << 8;             // same, in the complemented key space
@@ -386,6 +392,8 @@ __global__ __launch_bounds__(256) void k_pick_bins(const TensorDesc* __restrict_
         if (bp == 0xFFFFFFFFu || bn == 0xFFFFFFFFu) atomicOr(&result->err, kErrInternal);
         st[t].bin[0] = bp;
         st[t].bin[1] = bn;                            // complemented-key numbering
+        st[t].lo_key[0] = bp << kL1Shift;             // every candidate's side key is at or above these
+        st[t].lo_key[1] = bn << kL1Shift;
         st[t].cand_cnt[0] = 0u; st[t].cand_cnt[1] = 0u;
         st[t].flags = kStExact;
     }

@@ -8,12 +8,24 @@
 
 namespace sbc {
 
+// Optional phase timestamps for tuning (build with -DSBC_PHASE_TIMING): thread 0 of the first
+// 1024 workgroups of a kernel stores the 100 MHz wall clock into slot `i` of table `k`.
+#ifdef SBC_PHASE_TIMING
+__device__ unsigned long long g_phase_clock[2][1024][16];
+#define SBC_TS(k, i) do { if (threadIdx.x == 0 && blockIdx.x < 1024) g_phase_clock[k][blockIdx.x][i] = wall_clock64(); } while (0)
+#define SBC_TS_VAL(k, i, v) do { if (threadIdx.x == 0 && blockIdx.x < 1024) g_phase_clock[k][blockIdx.x][i] = (v); } while (0)
+#else
+#define SBC_TS(k, i) do {} while (0)
+#define SBC_TS_VAL(k, i, v) do {} while (0)
+#endif
+
 // ---------------------------------------------------------------- layout ----
 
 constexpr int kChunk = 8192;             // entries of one tensor handled by one workgroup
 constexpr int kChunkWords = kChunk / 32; // bitmap words per chunk (= threads of a chunk kernel)
 constexpr int kStreamThreads = 256;      // workgroup size of the streaming kernels
-constexpr int kSelThreads = 512;         // workgroup size of the sample and select kernels
+constexpr int kSampleThreads = 512;      // workgroup size of the sample kernel
+constexpr int kSelThreads = 1024;        // workgroup size of the select kernel
 constexpr int kSampleMax = 16384;        // entries sampled per tensor for the prefilter threshold
 
 // first digit of the histogram path: sign, exponent, top three mantissa bits
@@ -226,6 +238,45 @@ struct RunCounter {
 // need exceeds the total, found[s] stays false.  res: 8 words of LDS that nothing else touches
 // until the caller's next barrier, scratch: NT/64 u64 (LDS).  Contains barriers; every thread
 // must call it.
+// Same for a wide digit: hist[s][0..NB-1], PER = NB/NT consecutive bins per thread.
+template <int NB, int NT>
+__device__ __forceinline__ void pick_wide_both(const uint32_t (*hist)[NB], uint32_t (&need)[2],
+                                               const bool (&active)[2], uint32_t* res,
+                                               unsigned long long* scratch, uint32_t (&digit)[2], bool (&found)[2]) {
+    constexpr int PER = NB / NT;
+    static_assert(PER >= 1 && PER * NT == NB, "bins divide evenly over the threads");
+    const int t = threadIdx.x;
+    if (t < 8) res[t] = (t & 3) == 0 ? 0xFFFFFFFFu : 0u;       // res[4*s + {0: digit, 1: above}]
+    uint32_t h[2][PER], loc0 = 0u, loc1 = 0u;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {                            // walking from the top digit down
+        h[0][j] = active[0] ? hist[0][NB - 1 - (t * PER + j)] : 0u;
+        h[1][j] = active[1] ? hist[1][NB - 1 - (t * PER + j)] : 0u;
+        loc0 += h[0][j]; loc1 += h[1][j];
+    }
+    unsigned long long total;
+    const unsigned long long ex =
+        block_excl_sum<unsigned long long, NT>((unsigned long long)loc0 | ((unsigned long long)loc1 << 32), &total, scratch);
+    uint32_t cum[2] = {(uint32_t)ex, (uint32_t)(ex >> 32)};
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            if (active[s] && cum[s] < need[s] && need[s] <= cum[s] + h[s][j]) {
+                res[4 * s] = (uint32_t)(NB - 1 - (t * PER + j)); res[4 * s + 1] = cum[s];
+            }
+            cum[s] += h[s][j];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        digit[s] = res[4 * s];
+        found[s] = active[s] && digit[s] != 0xFFFFFFFFu;
+        if (found[s]) need[s] -= res[4 * s + 1];
+    }
+}
+
 struct BytePick {
     uint32_t byte[2];
     uint32_t count[2];

@@ -383,7 +383,7 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
 
     // ---- fast path: sample -> accumulate + filter -> select (+ fused encode) -> gather ----
     mark(kStSample, true);
-    hipLaunchKernelGGL(k_sample_thresholds, dim3(T), dim3(kSelThreads), 0, stream, c->d_desc, c->d_state,
+    hipLaunchKernelGGL(k_sample_thresholds, dim3(T), dim3(kSampleThreads), 0, stream, c->d_desc, c->d_state,
                        c->d_result, c->force_exact);
     mark(kStSample, false);
     mark(kStAccumulate, true);
@@ -551,6 +551,13 @@ int sbc_last_mask(sbc_ctx* c, int tensor, uint32_t* mask_words, size_t n_words) 
     }
     return SBC_OK;
 }
+
+#ifdef SBC_PHASE_TIMING
+// tuning builds only: copies the phase clock tables (2 x 1024 x 16 u64) to host memory
+int sbc_debug_phase_clocks(unsigned long long* out) {
+    return hipMemcpyFromSymbol(out, HIP_SYMBOL(sbc::g_phase_clock), sizeof(unsigned long long) * 2 * 1024 * 16) == hipSuccess ? 0 : -3;
+}
+#endif
 
 int sbc_last_used_exact_path(sbc_ctx* c) {
     if (!c || !c->last_ok) return SBC_EINVAL;

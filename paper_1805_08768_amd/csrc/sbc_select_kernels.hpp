@@ -47,12 +47,14 @@ __device__ __forceinline__ void put_ones(uint32_t* words, unsigned long long pos
 }
 
 constexpr uint32_t kSelLds = 8192;                       // candidates per side staged in LDS
+constexpr int kWindow = 2048;                            // bins of the leading-bits histogram
 static_assert(2 * kFusedMaxK * 4 <= kSelLds * 8, "sort arrays reuse one side's candidate space");
 static_assert(kFusedMaxWords <= kFusedMaxK, "stream words reuse the grouping array");
 
 struct SelectShared {
     uint2 cand[2][kSelLds];                              // both sides' lists when they fit
     union {
+        uint32_t hist16[2][kWindow];                     // leading 16 key bits, as an offset from the filter key
         struct {
             uint32_t hist[4][2][256];                    // byte histograms: [pass][side][byte]
             long long acc[2][256];                       // per-exponent integer sums
@@ -114,22 +116,26 @@ __device__ __forceinline__ void byte_histogram(SelectShared& sh, const CandLists
     rc.flush(h);
 }
 
+// Side s takes part in byte passes first_pass[s]..3; prefix[s] holds the bytes fixed before.
 __device__ __forceinline__ bool select_both(SelectShared& sh, const CandLists& l, uint32_t (&need)[2],
                                             const bool (&active)[2], int mode, const uint32_t (&tie_key)[2],
+                                            const int (&first_pass)[2], uint32_t (&prefix)[2],
                                             uint32_t (&out)[2], uint32_t (&last)[2]) {
-    uint32_t prefix[2] = {0u, 0u};
     bool ok = true;
     for (int i = threadIdx.x; i < 4 * 2 * 256; i += kSelThreads) (&sh.hist[0][0][0])[i] = 0u;
     __syncthreads();
 #pragma nounroll
     for (int pass = 0; pass < 4; ++pass) {
-        if (active[0]) byte_histogram<0>(sh, l, pass, mode, prefix[0], tie_key[0]);
-        if (active[1]) byte_histogram<1>(sh, l, pass, mode, prefix[1], tie_key[1]);
+        const bool act[2] = {active[0] && pass >= first_pass[0], active[1] && pass >= first_pass[1]};
+        if (!act[0] && !act[1]) continue;
+        if (act[0]) byte_histogram<0>(sh, l, pass, mode, prefix[0], tie_key[0]);
+        if (act[1]) byte_histogram<1>(sh, l, pass, mode, prefix[1], tie_key[1]);
         __syncthreads();
-        const BytePick pk = pick_byte_both<kSelThreads>(sh.hist[pass], need, active, sh.res[pass], sh.scratch64);
+        const BytePick pk = pick_byte_both<kSelThreads>(sh.hist[pass], need, act, sh.res[pass], sh.scratch64);
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
-            if (active[s] && !pk.found[s]) ok = false;
+            if (!act[s]) continue;
+            if (!pk.found[s]) ok = false;
             prefix[s] = (prefix[s] << 8) | pk.byte[s];
             last[s] = pk.count[s];
         }
@@ -171,6 +177,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         uint32_t* __restrict__ stage, uint32_t* __restrict__ kept_idx, int b, int pass,
         ResultBlock* __restrict__ result) {
     __shared__ SelectShared sh;
+    SBC_TS(1, 0);
     const int t = (int)order[blockIdx.x], tid = threadIdx.x;
     if (pass == 1 && !(st[t].flags & kStExact)) return;
     const TensorDesc d = desc[t];
@@ -189,36 +196,87 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         }
         return;
     }
+    SBC_TS(1, 1);                                     // descriptor and counts read
+    SBC_TS_VAL(1, 13, cnt_p); SBC_TS_VAL(1, 14, cnt_n); SBC_TS_VAL(1, 15, (unsigned)t);
     CandLists list;
     list.g[0] = cand + d.cand_off; list.cnt[0] = cnt_p;
     list.g[1] = cand + d.cand_off + n; list.cnt[1] = cnt_n;
     list.staged = cnt_p <= kSelLds && cnt_n <= kSelLds;
-    if (list.staged) {
+
+    // Leading 16 key bits of the k-th most extreme entry of each side.  Every candidate's key is at
+    // or above the side's filter key, and nearly all lie within a few octaves of it, so a window
+    // of kWindow values of (key >> 16) starting at the filter key's is histogrammed in the same
+    // sweep that stages the lists in LDS; the top bin collects everything beyond the window.
+    uint32_t need[2] = {k, k}, tau[2] = {0u, 0u};
+    const bool both[2] = {true, true};
+    const uint32_t base16[2] = {st[t].lo_key[0] >> 16, st[t].lo_key[1] >> 16};
+    bool ok = true;
+    for (int i = tid; i < 2 * kWindow; i += kSelThreads) (&sh.hist16[0][0])[i] = 0u;
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const uint32_t b16 = base16[s];
+        uint32_t* h = sh.hist16[s];
+        auto count = [&](const uint2& e) {
+            const uint32_t v = e.x >> 16;
+            const uint32_t o = v >= b16 ? v - b16 : 0u;   // (no candidate lies below its filter key)
+            atomicAdd(&h[o < (uint32_t)(kWindow - 1) ? o : (uint32_t)(kWindow - 1)], 1u);
+        };
+        if (list.staged) {
+            const uint2* __restrict__ g = list.g[s];
+#pragma unroll 4
+            for (uint32_t i = tid; i < list.cnt[s]; i += kSelThreads) { const uint2 e = g[i]; sh.cand[s][i] = e; count(e); }
+        } else if (s == 0) {
+            sweep<0>(sh, list, count);
+        } else {
+            sweep<1>(sh, list, count);
+        }
+    }
+    __syncthreads();
+    SBC_TS(1, 2);                                     // staged, leading bits counted
+    uint32_t digit[2];
+    bool found[2];
+    pick_wide_both<kWindow, kSelThreads>(sh.hist16, need, both, sh.res[0], sh.scratch64, digit, found);
+    __syncthreads();                                  // hist16 shares its space with the byte histograms
+    SBC_TS(1, 3);
+    // Remaining bytes of tau, then (second round, only if some ties must be dropped) the r lowest
+    // indices among the entries equal to tau.  A side whose k-th entry lies beyond the window is
+    // selected byte by byte from the top instead.
+    uint32_t itau[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};
+    {
+        bool active[2] = {true, true};
+        int first_pass[2];
+        uint32_t prefix[2], tie_key[2] = {0u, 0u};
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
-            const uint2* __restrict__ g = list.g[s];
-#pragma unroll 8
-            for (uint32_t i = tid; i < list.cnt[s]; i += kSelThreads) sh.cand[s][i] = g[i];
+            const bool narrow = found[s] && digit[s] != (uint32_t)(kWindow - 1);
+            first_pass[s] = narrow ? 2 : 0;
+            prefix[s] = narrow ? base16[s] + digit[s] : 0u;
         }
-        __syncthreads();
+#pragma nounroll
+        for (int mode = 0; mode < 2; ++mode) {
+            uint32_t out[2], last[2] = {0u, 0u};
+            ok = select_both(sh, list, need, active, mode, tie_key, first_pass, prefix, out, last) && ok;
+            if (mode == 0) {
+                // need[s] is now the number r of entries equal to tau[s] that are kept (1 <= r <= ties)
+                bool any = false;
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    tau[s] = out[s];
+                    active[s] = ok && need[s] < last[s];      // fewer than all ties are kept
+                    any = any || active[s];
+                    tie_key[s] = tau[s]; first_pass[s] = 0; prefix[s] = 0u;
+                }
+                if (!any) break;
+            } else {
+                // the r-th largest complemented index among the ties
+#pragma unroll
+                for (int s = 0; s < 2; ++s) if (active[s]) itau[s] = ~out[s];
+            }
+        }
     }
 
-    // exact k-th most extreme key of each side
-    uint32_t need[2] = {k, k}, tau[2], ties[2];
-    const bool both[2] = {true, true};
-    const uint32_t no_key[2] = {0u, 0u};
-    bool ok = select_both(sh, list, need, both, 0, no_key, tau, ties);
-    // need[s] is now the number r of entries equal to tau[s] that are kept (1 <= r <= ties[s])
-    uint32_t itau[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};
-    const bool tie_break[2] = {ok && need[0] < ties[0], ok && need[1] < ties[1]};
-    if (tie_break[0] || tie_break[1]) {
-        // the r lowest indices among the ties: the r-th largest complemented index
-        uint32_t rneed[2] = {need[0], need[1]}, ridx[2], one[2];
-        ok = select_both(sh, list, rneed, tie_break, 1, tau, ridx, one) && ok;
-        if (tie_break[0]) itau[0] = ~ridx[0];
-        if (tie_break[1]) itau[1] = ~ridx[1];
-    }
-
+    SBC_TS(1, 4);                                     // tau and tie index known
     // S+ and S-: exact integer accumulation per fp32 exponent; a thread first adds up runs of
     // equal exponent in a register
     for (int i = tid; i < 512; i += kSelThreads) (&sh.acc[0][0])[i] = 0ll;
@@ -240,6 +298,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         if (lane == 0) sh.S[s] = v;
     }
     __syncthreads();
+    SBC_TS(1, 5);                                     // sums done
     const double Sp = sh.S[0], Sn = sh.S[1];
     const int chosen = (Sp >= Sn) ? 0 : 1;            // mu+ >= mu-  <=>  S+ >= S-  (equal counts)
     const float mu32 = (float)((chosen ? Sn : Sp) / (double)k);
@@ -274,6 +333,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         return;
     }
 
+    SBC_TS(1, 6);
     // ---- fused: sort the k kept indices, encode their gaps (Alg. 3), write the stream ----
     // the LDS space of the side that was not chosen holds the sort arrays
     uint32_t* grp = reinterpret_cast<uint32_t*>(sh.cand[chosen ^ 1]);   // kept indices grouped by bucket
@@ -286,6 +346,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         if (e.y < n) atomicAdd(&sh.bucket_cnt[e.y >> shift], 1u);
     });
     __syncthreads();
+    SBC_TS(1, 7);                                     // buckets counted
     {   // exclusive scan of the bucket counts, in place: consecutive buckets per thread
         constexpr int PB = kBuckets / kSelThreads;
         uint32_t loc[PB], sum = 0u;
@@ -310,6 +371,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         }
     });
     __syncthreads();
+    SBC_TS(1, 8);                                     // grouped, residual updated
     for (uint32_t i = tid; i < k; i += kSelThreads) {
         const uint32_t v = grp[i];
         const uint32_t bk = v >> shift;
@@ -320,6 +382,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     }
     __syncthreads();
 
+    SBC_TS(1, 9);                                     // sorted
     // Golomb code lengths of E consecutive entries per thread, then their bit offsets
     const uint32_t E = (k + kSelThreads - 1) / kSelThreads;
     const uint32_t i0 = tid * E < k ? tid * E : k;
@@ -340,6 +403,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         if (tid == 0) atomicOr(&result->err, kErrInternal);
         return;
     }
+    SBC_TS(1, 10);
     uint32_t* words = grp;                            // the grouping array is free again
     for (uint32_t w = tid; w < n_words + 1u; w += kSelThreads) words[w] = 0u;
     __syncthreads();
@@ -357,11 +421,13 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         }
     }
     __syncthreads();
+    SBC_TS(1, 11);                                    // encoded
     uint32_t* __restrict__ out = stage + d.stage_off;
     for (uint32_t w = tid; w < n_words; w += kSelThreads) out[w] = words[w];
     uint32_t* __restrict__ ki = kept_idx + d.kept_off;
     for (uint32_t i = tid; i < k; i += kSelThreads) ki[i] = sorted[i];
     if (tid == 0) { st[t].bit_len = total_bits; st[t].nnz = k; }
+    SBC_TS(1, 12);
 }
 
 }  // namespace sbc
