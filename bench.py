@@ -95,6 +95,7 @@ def main() -> int:
     sbc.sbc_profile_enable(ctx, 1)
     msg_bytes = 0
     t_compress = 0.0
+    routes = {}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -103,6 +104,8 @@ def main() -> int:
         t_compress += time.perf_counter() - ta
         sbc.sbc_decompress_accumulate(ctx, msg, nbytes, P, scale, out)
         msg_bytes += nbytes
+        rt = sbc.sbc_last_route(ctx)
+        routes[rt] = routes.get(rt, 0) + 1
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     prof = {name: (ms, calls) for name, ms, calls in sbc.sbc_profile_read(ctx)}
@@ -180,6 +183,8 @@ def main() -> int:
         "kernel_us": breakdown,
         "copy_kernel_GBs": copy_gbs,
         "message_bytes": msg_bytes / args.steps,
+        "routes": {"sampled": routes.get(0, 0), "carried_keys": routes.get(1, 0),
+                   "histogram_fallback": sum(v for k, v in routes.items() if k & 2)},
         "compression_ratio_paper_accounting": ratio,
     }
     print(json.dumps(line))

@@ -129,18 +129,27 @@ int sbc_decompress_accumulate(sbc_ctx* ctx, void* hip_stream,
                               const int64_t* numel, int n_tensors, double p,
                               float scale, float* const* out);
 
-/* Options of a context.
- *   SBC_OPT_FORCE_EXACT_PATH  (value 0/1, default 0)  sbc_compress normally finds each tensor's
- *       candidates with a sampled threshold and falls back, per tensor, to an exact histogram
- *       of a second read when the sample misleads it; 1 makes every tensor take that second
- *       path.  The results are identical either way (the option exists to exercise and to time
- *       the histogram path). */
-enum { SBC_OPT_FORCE_EXACT_PATH = 1 };
+/* Options of a context.  None of them changes a result: sbc_compress is exact on every route.
+ * It finds each tensor's top-k candidates with a filter key per sign side and, for a tensor
+ * whose filter turns out to have kept fewer than k entries, falls back to an exact histogram
+ * of a second read of that tensor.
+ *   SBC_OPT_FORCE_EXACT_PATH   (0/1, default 0)  1 makes every tensor take the histogram route
+ *       (to exercise and to time it).
+ *   SBC_OPT_CARRY_FILTER_KEYS  (0/1, default 0)  0 estimates the filter keys from a sample of
+ *       the new data in every call.  1 lets a call start from keys derived from the exact
+ *       thresholds of the previous successful call on this context when tensor sizes and p
+ *       are unchanged (successive rounds of one training run) and skips the sampling kernel;
+ *       it pays off when the thresholds move by less than a few percent from round to round,
+ *       and costs time when they move more (a flood of candidates, then a sampled round). */
+enum { SBC_OPT_FORCE_EXACT_PATH = 1, SBC_OPT_CARRY_FILTER_KEYS = 2 };
 int sbc_set_option(sbc_ctx* ctx, int option, int value);
 
-/* 1 if the most recent successful sbc_compress() had to run the histogram path for at least
- * one tensor, 0 if not; SBC_EINVAL without a successful call. */
-int sbc_last_used_exact_path(sbc_ctx* ctx);
+/* Which routes the most recent successful sbc_compress() took: a bit set of
+ * SBC_ROUTE_CARRIED_KEYS (filter keys came from the previous call, no sampling) and
+ * SBC_ROUTE_HISTOGRAM (the histogram route ran for at least one tensor); SBC_EINVAL (negative)
+ * without a successful call. */
+enum { SBC_ROUTE_CARRIED_KEYS = 1, SBC_ROUTE_HISTOGRAM = 2 };
+int sbc_last_route(sbc_ctx* ctx);
 
 /* Inspection of the most recent sbc_compress() on this context, for tests and reports
  * (Alg. 2 intermediates).  All out pointers are host memory and may be NULL.

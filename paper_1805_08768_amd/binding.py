@@ -24,12 +24,15 @@ SBC_ECORRUPT = -4
 SBC_ENONFINITE = -5
 SBC_EINTERNAL = -6
 SBC_OPT_FORCE_EXACT_PATH = 1
+SBC_OPT_CARRY_FILTER_KEYS = 2
+SBC_ROUTE_CARRIED_KEYS = 1
+SBC_ROUTE_HISTOGRAM = 2
 
 EXPORTS = (
     "sbc_create", "sbc_destroy", "sbc_golomb_bstar", "sbc_num_kept", "sbc_msg_bound",
     "sbc_compress", "sbc_decompress_accumulate", "sbc_last_tensor_stats", "sbc_last_mask",
     "sbc_profile_enable", "sbc_profile_read", "sbc_copy_baseline", "sbc_set_option",
-    "sbc_last_used_exact_path", "sbc_strerror",
+    "sbc_last_route", "sbc_strerror",
 )
 
 
@@ -80,8 +83,8 @@ def load() -> ctypes.CDLL:
     lib.sbc_copy_baseline.restype = ctypes.c_int
     lib.sbc_set_option.argtypes = [vp, ctypes.c_int, ctypes.c_int]
     lib.sbc_set_option.restype = ctypes.c_int
-    lib.sbc_last_used_exact_path.argtypes = [vp]
-    lib.sbc_last_used_exact_path.restype = ctypes.c_int
+    lib.sbc_last_route.argtypes = [vp]
+    lib.sbc_last_route.restype = ctypes.c_int
     lib.sbc_strerror.argtypes = [ctypes.c_int]
     lib.sbc_strerror.restype = ctypes.c_char_p
     _lib = lib
@@ -262,8 +265,9 @@ def sbc_set_option(ctx, option: int, value: int) -> None:
         raise SbcError(rc, "sbc_set_option")
 
 
-def sbc_last_used_exact_path(ctx) -> bool:
-    rc = load().sbc_last_used_exact_path(ctx)
+def sbc_last_route(ctx) -> int:
+    """Bit set of SBC_ROUTE_CARRIED_KEYS / SBC_ROUTE_HISTOGRAM for the latest sbc_compress call."""
+    rc = load().sbc_last_route(ctx)
     if rc < 0:
-        raise SbcError(rc, "sbc_last_used_exact_path")
-    return bool(rc)
+        raise SbcError(rc, "sbc_last_route")
+    return rc

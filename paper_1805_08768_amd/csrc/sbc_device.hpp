@@ -44,6 +44,7 @@ constexpr uint32_t kErrNonFinite = 1u;
 constexpr uint32_t kErrInternal = 2u;
 constexpr uint32_t kErrCorrupt = 4u;
 constexpr uint32_t kErrPrefilter = 8u;   // not an error: some tensor needs the histogram path
+constexpr uint32_t kErrLoose = 16u;      // not an error: a carried-over filter key let far too many entries pass
 
 // TensorDesc::flags
 constexpr uint32_t kDescFused = 1u;      // sorted and encoded inside the select kernel

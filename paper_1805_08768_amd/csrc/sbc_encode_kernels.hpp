@@ -142,11 +142,14 @@ __global__ __launch_bounds__(kChunkWords) void k_pack(
     }
 }
 
-// grid (T, P): workgroup (t, y) copies every P-th 256-word slice of tensor t's stream.
+// grid (T, P): workgroup (t, y) copies every P-th 256-word slice of tensor t's stream.  The
+// lead workgroup of a tensor also leaves the tensor's candidate counters and flags clean for the
+// next call (which may skip the sampling kernel that otherwise resets them).
 __global__ __launch_bounds__(256) void k_gather(const TensorDesc* __restrict__ desc,
-                                                const TensorState* __restrict__ st, int T, int b,
+                                                TensorState* __restrict__ st, int T, int b,
                                                 const uint32_t* __restrict__ stage, uint8_t* __restrict__ msg,
-                                                uint64_t msg_capacity, ResultBlock* __restrict__ result) {
+                                                uint64_t msg_capacity, ResultBlock* __restrict__ result,
+                                                ResultBlock* __restrict__ next_result) {
     __shared__ unsigned long long scratch64[4];
     const int t = blockIdx.x, tid = threadIdx.x;
     const bool lead = (blockIdx.y == 0);
@@ -177,12 +180,15 @@ __global__ __launch_bounds__(256) void k_gather(const TensorDesc* __restrict__ d
         *reinterpret_cast<uint64_t*>(e + 8) = bit_len;
         *reinterpret_cast<uint64_t*>(e + 16) = word_off;
         if (st[t].nnz != d.k) atomicOr(&result->err, kErrInternal);
+        st[t].cand_cnt[0] = 0u; st[t].cand_cnt[1] = 0u; st[t].flags = 0u;
         if (t == 0) {
             uint32_t* h = reinterpret_cast<uint32_t*>(msg);
             h[0] = 0x31434253u; h[1] = 1u; h[2] = (uint32_t)T; h[3] = (uint32_t)b;
             *reinterpret_cast<uint64_t*>(msg + 16) = tot_all;
             *reinterpret_cast<uint64_t*>(msg + 24) = 0ull;
             result->msg_bytes = table_end + 4ull * tot_all;
+            // the result block of the next call starts out clean
+            next_result->err = 0u; next_result->pad = 0u; next_result->msg_bytes = 0ull;
         }
     }
     const uint32_t* __restrict__ src = stage + d.stage_off;
@@ -191,5 +197,6 @@ __global__ __launch_bounds__(256) void k_gather(const TensorDesc* __restrict__ d
          w += 256ull * gridDim.y)
         dst[w] = src[w];
 }
+
 
 }  // namespace sbc

@@ -69,6 +69,14 @@ struct sbc_ctx {
 
     // options
     int force_exact = 0;
+    int carry_keys = 0;
+
+    // filter keys carried over from the previous successful call (same tensor sizes, same p)
+    bool hist_valid = false;
+    double hist_p = 0.0;
+    std::vector<uint32_t> hist_n;
+    int result_idx = 0;           // compress calls alternate between result blocks 0 and 1; decode uses 2
+    bool result_dirty = true;     // the next compress call must clear its result blocks itself
 
     // optional per-kernel timing with HIP events on the caller's stream
     int profile_level = 0;
@@ -81,6 +89,7 @@ struct sbc_ctx {
     int last_T = 0;
     bool last_ok = false;
     bool last_used_exact_path = false;
+    bool last_used_history = false;
     std::vector<TensorDesc> plan;
     std::vector<uint32_t> plan_order;
 };
@@ -216,7 +225,7 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     ok = ok && dev_alloc(&c->d_sum, (size_t)c->max_chunks) == hipSuccess;
     ok = ok && dev_alloc(&c->d_prev_end, (size_t)c->max_chunks) == hipSuccess;
     ok = ok && dev_alloc(&c->d_bitoff, (size_t)c->max_chunks) == hipSuccess;
-    ok = ok && dev_alloc(&c->d_result, 1) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_result, 3) == hipSuccess;
     ok = ok && dev_alloc(&c->d_dec, T) == hipSuccess;
     ok = ok && host_alloc(&c->h_desc, T) == hipSuccess;
     ok = ok && host_alloc(&c->h_chunk_tensor, (size_t)c->max_chunks) == hipSuccess;
@@ -255,7 +264,8 @@ void sbc_destroy(sbc_ctx* c) {
 int sbc_set_option(sbc_ctx* c, int option, int value) {
     if (!c) return SBC_EINVAL;
     switch (option) {
-        case SBC_OPT_FORCE_EXACT_PATH: c->force_exact = value ? 1 : 0; return SBC_OK;
+        case SBC_OPT_FORCE_EXACT_PATH: c->force_exact = value ? 1 : 0; c->hist_valid = false; return SBC_OK;
+        case SBC_OPT_CARRY_FILTER_KEYS: c->carry_keys = value ? 1 : 0; c->hist_valid = false; return SBC_OK;
         default: return SBC_EINVAL;
     }
 }
@@ -276,6 +286,7 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
     uint64_t total = 0, chunks = 0, stage_words = 0, kept_total = 0, max_bound = 0;
     bool same = c->dev_desc_valid && c->dev_T == T;
     bool any_bitmap = false;
+    bool use_history = c->hist_valid && !c->force_exact && c->hist_p == p && c->hist_n.size() == (size_t)T;
     if (c->plan.size() < (size_t)T) c->plan.resize(T);
     for (int t = 0; t < T; ++t) {
         const int64_t n = numel[t];
@@ -303,6 +314,7 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
         d.kept_off = (uint32_t)kept_total;
         if (fused) kept_total += d.k; else any_bitmap = true;
         if (same && std::memcmp(&d, &c->h_desc[t], sizeof(d)) != 0) same = false;
+        if (use_history && c->hist_n[t] != d.n) use_history = false;
         total += (uint64_t)n;
         chunks += d.nchunks;
         stage_words += bw;
@@ -341,6 +353,16 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
 
     uint8_t* msg8 = static_cast<uint8_t*>(msg);
     const uint32_t n_chunks = (uint32_t)chunks;
+    if (c->result_dirty) {                            // after an error, or on the first call
+        hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(c->d_result),
+                           (uint64_t)(2 * sizeof(ResultBlock) / 4));
+        use_history = false;
+    }
+    c->result_dirty = true;                           // until this call has completed normally
+    c->hist_valid = false;
+    ResultBlock* const res_now = c->d_result + c->result_idx;
+    ResultBlock* const res_next = c->d_result + (c->result_idx ^ 1);
+    c->result_idx ^= 1;
     const unsigned gather_y = (unsigned)std::min<uint64_t>(64, std::max<uint64_t>(1, (max_bound + 1023) / 1024));
 
     // stage boundaries are timed with events only when profiling was asked for:
@@ -363,17 +385,17 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
                                c->d_bitoff, c->d_state, b);
             if (profile) { mark(kStTensorScan, false); mark(kStPack, true); }
             hipLaunchKernelGGL(k_pack, dim3(n_chunks), dim3(kChunkWords), 0, stream, c->d_desc, c->d_chunk_tensor,
-                               c->d_bitmap, c->d_sum, c->d_prev_end, c->d_bitoff, b, c->d_stage, c->d_result);
+                               c->d_bitmap, c->d_sum, c->d_prev_end, c->d_bitoff, b, c->d_stage, res_now);
             if (profile) mark(kStPack, false);
         }
         if (profile) mark(kStGather, true);
         hipLaunchKernelGGL(k_gather, dim3(T, gather_y), dim3(256), 0, stream, c->d_desc, c->d_state, T, b,
-                           c->d_stage, msg8, (uint64_t)msg_capacity, c->d_result);
+                           c->d_stage, msg8, (uint64_t)msg_capacity, res_now, res_next);
         if (profile) mark(kStGather, false);
     };
     auto finish = [&]() -> int {                      // copy the result block back and wait
         if (hipGetLastError() != hipSuccess) return SBC_EHIP;
-        if (hipMemcpyAsync(c->h_result, c->d_result, sizeof(ResultBlock), hipMemcpyDeviceToHost, stream) != hipSuccess ||
+        if (hipMemcpyAsync(c->h_result, res_now, sizeof(ResultBlock), hipMemcpyDeviceToHost, stream) != hipSuccess ||
             hipStreamSynchronize(stream) != hipSuccess) {
             (void)hipGetLastError();
             return SBC_EHIP;
@@ -381,18 +403,22 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
         return SBC_OK;
     };
 
-    // ---- fast path: sample -> accumulate + filter -> select (+ fused encode) -> gather ----
-    mark(kStSample, true);
-    hipLaunchKernelGGL(k_sample_thresholds, dim3(T), dim3(kSampleThreads), 0, stream, c->d_desc, c->d_state,
-                       c->d_result, c->force_exact);
-    mark(kStSample, false);
+    // ---- fast path: [sample ->] accumulate + filter -> select (+ fused encode) -> gather ----
+    // The sampling kernel is skipped when the previous call left filter keys for the same tensor
+    // sizes and sparsity (its select kernel derives them from the exact thresholds it found).
+    if (!use_history) {
+        mark(kStSample, true);
+        hipLaunchKernelGGL(k_sample_thresholds, dim3(T), dim3(kSampleThreads), 0, stream, c->d_desc, c->d_state,
+                           res_now, c->force_exact);
+        mark(kStSample, false);
+    }
     mark(kStAccumulate, true);
     hipLaunchKernelGGL(k_accumulate_filter, dim3(n_chunks), dim3(kStreamThreads), 0, stream, c->d_desc,
-                       c->d_chunk_tensor, c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_result);
+                       c->d_chunk_tensor, c->d_state, c->d_cand, c->d_bitmap, c->d_stage, res_now);
     mark(kStAccumulate, false);
     mark(kStSelect, true);
     hipLaunchKernelGGL(k_select, dim3(T), dim3(kSelThreads), 0, stream, c->d_desc, c->d_order,
-                       c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 0, c->d_result);
+                       c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 0, res_now);
     mark(kStSelect, false);
     encode_and_gather(true);
     int rc = finish();
@@ -418,15 +444,15 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
         const uint32_t hist_words = (uint32_t)T * kL1Bins;
         hipLaunchKernelGGL(k_zero_words, dim3((hist_words + 2047) / 2048), dim3(256), 0, stream, c->d_hist,
                            (uint64_t)hist_words);
-        hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(c->d_result),
+        hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(res_now),
                            (uint64_t)(sizeof(ResultBlock) / 4));
         hipLaunchKernelGGL(k_hist_flagged, dim3(n_chunks), dim3(kStreamThreads), 0, stream, c->d_desc,
                            c->d_chunk_tensor, c->d_state, c->d_hist);
-        hipLaunchKernelGGL(k_pick_bins, dim3(T), dim3(256), 0, stream, c->d_desc, c->d_hist, c->d_state, c->d_result);
+        hipLaunchKernelGGL(k_pick_bins, dim3(T), dim3(256), 0, stream, c->d_desc, c->d_hist, c->d_state, res_now);
         hipLaunchKernelGGL(k_extract, dim3(n_chunks), dim3(kStreamThreads), 0, stream, c->d_desc,
-                           c->d_chunk_tensor, c->d_state, c->d_cand, c->d_result);
+                           c->d_chunk_tensor, c->d_state, c->d_cand, res_now);
         hipLaunchKernelGGL(k_select, dim3(T), dim3(kSelThreads), 0, stream, c->d_desc, c->d_order,
-                           c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 1, c->d_result);
+                           c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 1, res_now);
         encode_and_gather(false);
         rc = finish();
         if (rc != SBC_OK) return rc;
@@ -438,6 +464,15 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
     if (c->h_result->msg_bytes > need) return SBC_EINTERNAL;
     *msg_bytes = (size_t)c->h_result->msg_bytes;
     c->last_ok = true;
+    c->last_used_history = use_history;
+    c->result_dirty = false;
+    // the next call may start from this call's thresholds unless they proved unhelpful
+    c->hist_valid = c->carry_keys && !c->force_exact && !c->last_used_exact_path && !(err & kErrLoose);
+    if (c->hist_valid) {
+        c->hist_p = p;
+        c->hist_n.resize(T);
+        for (int t = 0; t < T; ++t) c->hist_n[t] = c->plan[t].n;
+    }
     return SBC_OK;
 }
 
@@ -467,13 +502,14 @@ int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, siz
         }
         c->dev_dec_T = T;
     }
-    hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(c->d_result),
+    ResultBlock* const res_dec = c->d_result + 2;
+    hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(res_dec),
                        (uint64_t)(sizeof(ResultBlock) / 4));
     hipLaunchKernelGGL(k_decode_accumulate, dim3(T), dim3(kDecThreads), 0, stream,
                        static_cast<const uint8_t*>(msg), (unsigned long long)msg_bytes, c->d_dec, T, b, scale,
-                       c->d_result);
+                       res_dec);
     if (hipGetLastError() != hipSuccess) return SBC_EHIP;
-    if (hipMemcpyAsync(c->h_result, c->d_result, sizeof(ResultBlock), hipMemcpyDeviceToHost, stream) != hipSuccess ||
+    if (hipMemcpyAsync(c->h_result, res_dec, sizeof(ResultBlock), hipMemcpyDeviceToHost, stream) != hipSuccess ||
         hipStreamSynchronize(stream) != hipSuccess) {
         (void)hipGetLastError();
         return SBC_EHIP;
@@ -559,9 +595,9 @@ int sbc_debug_phase_clocks(unsigned long long* out) {
 }
 #endif
 
-int sbc_last_used_exact_path(sbc_ctx* c) {
+int sbc_last_route(sbc_ctx* c) {
     if (!c || !c->last_ok) return SBC_EINVAL;
-    return c->last_used_exact_path ? 1 : 0;
+    return (c->last_used_history ? SBC_ROUTE_CARRIED_KEYS : 0) | (c->last_used_exact_path ? SBC_ROUTE_HISTOGRAM : 0);
 }
 
 }  // extern "C"

@@ -310,6 +310,23 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         st[t].side = chosen ? -1 : 1;
         st[t].mu_signed = mu_signed;
         if (!ok) atomicOr(&result->err, kErrInternal);
+        // Filter keys a following round may start from instead of sampling: this round's exact
+        // threshold, lowered by a margin that shrinks with k (the k-th order statistic of similar
+        // data moves by about 1/sqrt(k) of the tail's scale from round to round).  Only a filter:
+        // if it misleads, the select kernel notices and the histogram path takes over.
+        const float margin = fminf(0.75f, fmaxf(0.04f, 3.0f * rsqrtf((float)k)));
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const float x = __uint_as_float(bits_of_key(tau[s]));      // how extreme the k-th entry is
+            const float lo_x = x - margin * fabsf(x) - 1.17549435e-38f;
+            uint32_t lo = key_of_bits(__float_as_uint(lo_x));
+            if (lo > tau[s]) lo = tau[s];
+            st[t].lo_key[s] = lo;
+        }
+        // far more candidates than needed (the lists no longer fit in LDS, or many times k):
+        // the next call should estimate its keys afresh
+        const uint32_t many = min(kSelLds, 8u * k + 4096u);
+        if (cnt_p > many || cnt_n > many) atomicOr(&result->err, kErrLoose);
     }
     if (!ok) return;
 

@@ -110,13 +110,17 @@ def palette_update(n: int, *, config: int = 6, client: int = 0, round_: int = 0,
     return (i * 2.0 ** -17).astype(np.float32)
 
 
+def tensor_scale(config: int, tensor: int) -> float:
+    """s_t = 10^U(-4, -2): a property of the tensor (layer), the same in every round and client."""
+    return 10.0 ** rng_for(config, 0, 0, tensor).uniform(-4.0, -2.0)
+
+
 def resnet50_update(*, client: int = 0, round_: int = 0, config: int = 3) -> List[np.ndarray]:
     """Config 3: Laplace(0, s_t) per tensor with s_t = 10^U(-4, -2)."""
     out = []
     for t, n in enumerate(numels(resnet50_shapes())):
-        g = rng_for(config, client, round_, t)
-        s_t = 10.0 ** g.uniform(-4.0, -2.0)
-        out.append(g.laplace(0.0, s_t, n).astype(np.float32))
+        g = rng_for(config, client + 1, round_ + 1, t)
+        out.append(g.laplace(0.0, tensor_scale(config, t), n).astype(np.float32))
     return out
 
 
@@ -158,7 +162,6 @@ def small_model_update(sizes, *, config: int = 7, client: int = 0, round_: int =
     still span several tiles and ragged tails."""
     out = []
     for t, n in enumerate(sizes):
-        g = rng_for(config, client, round_, t)
-        s_t = 10.0 ** g.uniform(-4.0, -2.0)
-        out.append(g.laplace(0.0, s_t, int(n)).astype(np.float32))
+        g = rng_for(config, client + 1, round_ + 1, t)
+        out.append(g.laplace(0.0, tensor_scale(config, t), int(n)).astype(np.float32))
     return out

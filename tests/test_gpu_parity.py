@@ -106,7 +106,7 @@ def test_histogram_path_forced():
             R = [np.zeros(n, np.float32) for n in sizes]
             for r in range(2):
                 res = check_round(run, synth.small_model_update(sizes, round_=r), R, p)
-                assert sbc.sbc_last_used_exact_path(run.ctx)
+                assert sbc.sbc_last_route(run.ctx) == sbc.SBC_ROUTE_HISTOGRAM
                 R = [x.R_new for x in res]
     dWs = [synth.palette_update(200000), np.zeros(70000, np.float32)]
     with DeviceRun([200000, 70000]) as run:
@@ -150,12 +150,46 @@ def test_misleading_sample_falls_back_per_tensor():
     with DeviceRun(sizes) as run:
         R = [np.zeros(n, np.float32) for n in sizes]
         res = check_round(run, dWs, R, 0.001)                # k = 400 for tensor 1
-        assert sbc.sbc_last_used_exact_path(run.ctx), "the sample was meant to mislead the filter"
-        # the residual still holds the planted entries, so the next round falls back again
+        assert sbc.sbc_last_route(run.ctx) == sbc.SBC_ROUTE_HISTOGRAM, "the sample was meant to mislead the filter"
+        # after a fallback the next round samples again; the residual still holds the planted
+        # entries, so it falls back again
         check_round(run, synth.small_model_update(sizes, round_=5), [r.R_new for r in res], 0.001)
+        assert sbc.sbc_last_route(run.ctx) == sbc.SBC_ROUTE_HISTOGRAM
     with DeviceRun(sizes) as run:                            # ordinary data: the fast route alone
         check_round(run, synth.small_model_update(sizes, round_=5), [np.zeros(n, np.float32) for n in sizes], 0.001)
-        assert not sbc.sbc_last_used_exact_path(run.ctx)
+        assert sbc.sbc_last_route(run.ctx) == 0
+
+
+def test_carried_filter_keys():
+    """From the second round on the filter keys come from the previous round's exact thresholds.
+    Results stay exact when the data scale drifts, jumps up (keys far too low: a flood of
+    candidates) or collapses (keys far too high: the histogram route takes over)."""
+    sizes = [300000, 64, 20000, 8193]
+    scales = [1.0, 1.05, 0.9, 1.2, 40.0, 40.0, 0.01, 0.01, 1.0]
+    routes = []
+    with DeviceRun(sizes) as run:
+        sbc.sbc_set_option(run.ctx, sbc.SBC_OPT_CARRY_FILTER_KEYS, 1)
+        R = [np.zeros(n, np.float32) for n in sizes]
+        for r, sc in enumerate(scales):
+            if r == 6:                                       # the client starts over: residual cleared
+                R = [np.zeros(n, np.float32) for n in sizes]
+                for x in run.R:
+                    x.zero_()
+            dWs = [(d * np.float32(sc)).astype(np.float32) for d in synth.small_model_update(sizes, round_=r)]
+            res = check_round(run, dWs, R, 0.001, check_decode=(r % 4 == 0))
+            routes.append(sbc.sbc_last_route(run.ctx))
+            R = [x.R_new for x in res]
+    print("routes", routes)
+    assert routes[0] == 0                                    # first round samples
+    assert routes[1] == sbc.SBC_ROUTE_CARRIED_KEYS and routes[2] == sbc.SBC_ROUTE_CARRIED_KEYS
+    assert routes[5] == 0                                    # the flood of candidates made round 5 sample again
+    assert routes[6] & sbc.SBC_ROUTE_HISTOGRAM               # the collapse forces the exact route
+    with DeviceRun(sizes) as run:                            # default: every round samples
+        R = [np.zeros(n, np.float32) for n in sizes]
+        for r in range(3):
+            res = check_round(run, synth.small_model_update(sizes, round_=r), R, 0.001, check_decode=False)
+            assert sbc.sbc_last_route(run.ctx) == 0
+            R = [x.R_new for x in res]
 
 
 def test_candidate_lists_beyond_the_register_cache():
