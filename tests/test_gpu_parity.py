@@ -269,6 +269,74 @@ def test_config5a_server_average_of_clients():
         assert np.array_equal(outs[t].cpu().numpy(), want[t]), t
 
 
+def test_config5b_flat_1p5e9_properties():
+    """One flat tensor of 1.5e9 entries, p = 0.001 (k = 1.5e6, b* = 9).  A full sort on the host is
+    out of reach, so the result is checked by what defines it, with no sort: exactly k kept
+    entries, every kept entry at least as extreme as every dropped one with equal values resolved
+    to the lowest indices, mu = mean of the kept values, residual identity, the closed-form bit
+    length of the Golomb stream, the oracle's bit-serial decoder on the first codes, and the
+    library's decoder on the whole stream."""
+    n, p = 1_500_000_000, 0.001
+    free, total = torch.cuda.mem_get_info()
+    if free < 60 * 2 ** 30:
+        pytest.skip("needs about 60 GiB of free device memory")
+    k = o.num_kept(n, p)
+    b = o.golomb_bstar(p)
+    dW = torch.empty(n, dtype=torch.float32, device="cuda:0")
+    host = np.empty(n, dtype=np.float32)
+    for off, chunk in synth.flat_gaussian_chunks(n):
+        host[off:off + len(chunk)] = chunk
+        dW[off:off + len(chunk)].copy_(torch.from_numpy(chunk))
+    print("generated", flush=True)
+    R = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    ctx = sbc.sbc_create(0, n, 1)
+    try:
+        bound = sbc.sbc_msg_bound([n], p)
+        msg = torch.zeros(bound, dtype=torch.uint8, device="cuda:0")
+        nbytes = sbc.sbc_compress(ctx, [dW], [R], p, msg)
+        print("compressed", nbytes, flush=True)
+        mu_pos, mu_neg, side, nnz, bit_len = sbc.sbc_last_tensor_stats(ctx, 0)
+        assert nnz == k
+        kept = mask_to_positions(sbc.sbc_last_mask(ctx, 0, n), n)
+        assert len(kept) == k
+        A = host                                              # zero residual: A = dW
+        vals = A[kept].astype(np.float64) * side
+        mask = np.zeros(n, dtype=bool); mask[kept] = True
+        dropped_max = (A[~mask] * np.float32(side)).max()
+        assert vals.min() >= dropped_max                      # kept entries are the k most extreme of the side
+        if vals.min() == dropped_max:                         # ties at the threshold: lowest indices win
+            tied = np.flatnonzero(A * np.float32(side) == np.float32(dropped_max))
+            assert mask[tied[: int(mask[tied].sum())]].all()
+        mu = mu_pos if side > 0 else mu_neg
+        assert abs(mu - vals.mean()) <= 1e-5 * abs(vals.mean())
+        other = np.partition(A * np.float32(-side), n - k)[n - k:].astype(np.float64).mean()
+        assert abs((mu_neg if side > 0 else mu_pos) - other) <= 1e-5 * abs(other) and mu >= other
+        header = msg[:56].cpu().numpy().tobytes()
+        import struct
+        mu_signed, nnz_m, bl_m, woff = struct.unpack_from("<fIQQ", header, 32)
+        assert nnz_m == k and woff == 0 and np.float32(mu_signed) == np.float32(side * mu)
+        # residual
+        Rh = R.cpu().numpy()
+        assert np.array_equal(Rh[~mask], A[~mask])
+        assert np.allclose(Rh[kept], A[kept] - np.float32(mu_signed), rtol=0, atol=1e-5 * abs(mu))
+        # code lengths in closed form
+        gaps = np.diff(np.concatenate(([-1], kept))) - 1
+        assert bl_m == bit_len == int(((gaps >> b) + 1 + b).sum())
+        assert nbytes == 32 + 24 + 4 * ((bl_m + 31) // 32)
+        # the oracle's decoder on the first 20000 codes
+        first_bits = int(((gaps[:20000] >> b) + 1 + b).sum())
+        words = msg[56:56 + 4 * ((first_bits + 31) // 32)].cpu().numpy().view("<u4")
+        assert o.golomb_decode(o.unpack_bits(words, first_bits), b) == kept[:20000].tolist()
+        # the library's decoder on the whole stream
+        del dW
+        out = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+        sbc.sbc_decompress_accumulate(ctx, msg, nbytes, p, 1.0, [out])
+        nz = torch.nonzero(out).flatten().cpu().numpy()
+        assert np.array_equal(nz, kept) and bool((out[torch.from_numpy(kept).cuda()] == mu_signed).all())
+    finally:
+        sbc.sbc_destroy(ctx)
+
+
 # ------------------------------------------------------- determinism and errors ----
 
 def test_same_input_twice_gives_identical_bytes():
