@@ -43,6 +43,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--breakdown", action="store_true", help="also print per-kernel times to stderr")
+    ap.add_argument("--workload", default="resnet50", choices=["resnet50", "lstm", "gauss2p20", "student4m", "flat1p5e9"],
+                    help="resnet50 (default) is the benchmark workload; the others are reported for reference")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported "
@@ -56,14 +58,35 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     dev = "cuda:0"
-    sizes = synth.numels(synth.resnet50_shapes())
+    global P
+    n_sets = 3
+    if args.workload == "resnet50":
+        sizes = synth.numels(synth.resnet50_shapes())
+        gen = lambda r: synth.resnet50_update(round_=r)
+        name = ("ResNet-50-shaped update: 161 fp32 tensors, 25,557,032 entries, "
+                "Laplace values with per-tensor scale 10^U(-4,-2), p=0.001, residual carried")
+    elif args.workload == "lstm":
+        sizes = synth.numels(synth.lstm_lm_shapes()); P = 1e-4
+        gen = lambda r: synth.lstm_lm_update(round_=r)
+        name = "2-layer LSTM LM-shaped update: 9 tensors, 66,022,000 entries, p=1e-4"
+    elif args.workload == "gauss2p20":
+        sizes = [1 << 20]; P = 0.01
+        gen = lambda r: [synth.gaussian_update(1 << 20, round_=r)]
+        name = "one tensor, 2^20 entries, N(0,1e-6), p=0.01"
+    elif args.workload == "student4m":
+        sizes = [4194304]
+        gen = lambda r: [synth.student_t_update(4194304, round_=r)]
+        name = "one tensor, 4,194,304 entries, Student-t(3), p=0.001"
+    else:
+        sizes = [1_500_000_000]; n_sets = 1
+        gen = lambda r: [np.concatenate([c for _, c in synth.flat_gaussian_chunks(sizes[0])])]
+        name = "one flat tensor, 1.5e9 entries, N(0,1e-6), p=0.001"
     N = sum(sizes)
     T = len(sizes)
 
-    # three different updates resident in HBM, used round-robin; the residual carries over
-    n_sets = 3
-    host_sets = [synth.resnet50_update(round_=r) for r in range(n_sets)]
-    flat_sets = [torch.from_numpy(np.concatenate(h)).to(dev) for h in host_sets]
+    # a few different updates resident in HBM, used round-robin; the residual carries over
+    host_sets = [gen(r) for r in range(n_sets)]
+    flat_sets = [torch.from_numpy(np.concatenate(h) if len(h) > 1 else h[0]).to(dev) for h in host_sets]
     flat_R = torch.zeros(N, dtype=torch.float32, device=dev)
     flat_out = torch.zeros(N, dtype=torch.float32, device=dev)
 
@@ -122,7 +145,7 @@ def main() -> int:
     breakdown = {name: round(ms / max(1, calls) * 1e3, 2) for name, ms, calls in sbc.sbc_profile_read(ctx)}
     sbc.sbc_profile_enable(ctx, 0)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    src, dst = flat_sets[0], flat_sets[1]
+    src, dst = flat_sets[0], (flat_sets[1] if n_sets > 1 else flat_out)
     for _ in range(3):
         sbc.sbc_copy_baseline(dst, src)
     torch.cuda.synchronize()
@@ -138,7 +161,7 @@ def main() -> int:
         print("per-kernel us (event-bracketed):", breakdown, file=sys.stderr)
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.workload == "resnet50":
         from oracle import sbc_oracle as oracle
         dWs = host_sets[0]
         zeros = [np.zeros_like(d) for d in dWs]
@@ -166,9 +189,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "ResNet-50-shaped update: 161 fp32 tensors, 25,557,032 entries, "
-                               "Laplace values with per-tensor scale 10^U(-4,-2), p=0.001, residual carried",
-                   "p": P, "tensors": T, "entries": N,
+        "config": {"workload": name, "p": P, "tensors": T, "entries": N,
                    "step": "sbc_compress + sbc_decompress_accumulate (one client, one round)"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
