@@ -96,8 +96,8 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
 
     for (int i = tid; i < 3 * 2 * 256; i += kSampleThreads) (&hist[0][0][0])[i] = 0u;
     for (int i = tid; i < 2 * 256 * COPIES; i += kSampleThreads) (&hist0[0][0][0])[i] = 0u;
-    const float* __restrict__ R = d.R;
-    const float* __restrict__ dW = d.dW;
+    const gcfloat_ptr R = as_global(d.R);
+    const gcfloat_ptr dW = as_global(d.dW);
     if (n <= (uint32_t)kSampleMax) {
 #pragma unroll 8
         for (uint32_t i = tid; i < m; i += kSampleThreads)
@@ -189,8 +189,10 @@ __device__ __forceinline__ void append_candidates(const uint32_t (&key)[PER], ui
     if (total == 0u) return;                          // uniform
     if (tid == 0) {
         const uint32_t tp = total & 0xFFFFu, tn = total >> 16;
-        base[0] = tp ? atomicAdd(&st_t->cand_cnt[0], tp) : 0u;
-        base[1] = tn ? atomicAdd(&st_t->cand_cnt[1], tn) : 0u;
+        const unsigned long long old = atomicAdd(reinterpret_cast<unsigned long long*>(&st_t->cand_cnt[0]),
+                                                 (unsigned long long)tp | ((unsigned long long)tn << 32));
+        base[0] = (uint32_t)old;
+        base[1] = (uint32_t)(old >> 32);
     }
     __syncthreads();
     uint32_t op = base[0] + (ex & 0xFFFFu);
@@ -265,15 +267,15 @@ __global__ __launch_bounds__(kStreamThreads) void k_accumulate_filter(
     }
     __syncthreads();
 
-    const float* __restrict__ dw = d.dW + e0;
-    float* __restrict__ r = d.R + e0;
+    const gcfloat_ptr dw = as_global(d.dW + e0);
+    const gfloat_ptr r = as_global(d.R + e0);
     uint32_t bad = 0u;
-    const bool vec = (cnt == (uint32_t)kChunk) && ((((uintptr_t)dw | (uintptr_t)r) & 15u) == 0u);
+    const bool vec = (cnt == (uint32_t)kChunk) && ((((uintptr_t)(d.dW + e0) | (uintptr_t)(d.R + e0)) & 15u) == 0u);
     if (vec) {
-        const float4* __restrict__ dw4 = reinterpret_cast<const float4*>(dw);
-        float4* __restrict__ r4 = reinterpret_cast<float4*>(r);
+        const gcf32x4_ptr dw4 = (gcf32x4_ptr)dw;
+        const gf32x4_ptr r4 = (gf32x4_ptr)r;
         constexpr int IT = kChunk / 4 / kStreamThreads;   // 8
-        float4 dv[IT], rv[IT];
+        f32x4 dv[IT], rv[IT];
 #pragma unroll
         for (int i = 0; i < IT; ++i) {
             dv[i] = dw4[i * kStreamThreads + tid];
@@ -281,7 +283,7 @@ __global__ __launch_bounds__(kStreamThreads) void k_accumulate_filter(
         }
 #pragma unroll
         for (int i = 0; i < IT; ++i) {
-            float4 a;
+            f32x4 a;
             a.x = rv[i].x + dv[i].x;
             a.y = rv[i].y + dv[i].y;
             a.z = rv[i].z + dv[i].z;
@@ -306,8 +308,12 @@ __global__ __launch_bounds__(kStreamThreads) void k_accumulate_filter(
     if (qp <= (uint32_t)kFilterQueue && qn <= (uint32_t)kFilterQueue) {
         if (qp + qn == 0u) return;
         if (tid == 0) {
-            sh.base[0] = qp ? atomicAdd(&st[t].cand_cnt[0], qp) : 0u;
-            sh.base[1] = qn ? atomicAdd(&st[t].cand_cnt[1], qn) : 0u;
+            // both sides' counters advance in one 64-bit atomic: workgroups of one tensor queue up
+            // on this address, and the wait grows with the number of atomics
+            const unsigned long long old = atomicAdd(reinterpret_cast<unsigned long long*>(&st[t].cand_cnt[0]),
+                                                     (unsigned long long)qp | ((unsigned long long)qn << 32));
+            sh.base[0] = (uint32_t)old;
+            sh.base[1] = (uint32_t)(old >> 32);
         }
         __syncthreads();
         if ((uint64_t)sh.base[0] + qp > d.n || (uint64_t)sh.base[1] + qn > d.n) {   // cannot happen
@@ -353,7 +359,7 @@ __global__ __launch_bounds__(kStreamThreads) void k_hist_flagged(
     const uint32_t cnt = min((uint32_t)kChunk, d.n - e0);
     for (int i = tid; i < kL1Bins; i += kStreamThreads) lh[i] = 0u;
     __syncthreads();
-    const float* __restrict__ a = d.R + e0;
+    const gcfloat_ptr a = as_global(d.R + e0);
     uint32_t zeros = 0u;
     for (uint32_t i = tid; i < cnt; i += kStreamThreads) {
         const uint32_t u = __float_as_uint(a[i]);
@@ -416,7 +422,7 @@ __global__ __launch_bounds__(kStreamThreads) void k_extract(
     const uint32_t cnt = min((uint32_t)kChunk, d.n - e0);
     const uint32_t bin_p = st[t].bin[0];
     const uint32_t bin_n = (uint32_t)(kL1Bins - 1) - st[t].bin[1];  // in the plain key space
-    const float* __restrict__ a = d.R + e0;
+    const gcfloat_ptr a = as_global(d.R + e0);
     uint32_t key[PER];
     uint32_t mp = 0u, mn = 0u;
 #pragma unroll

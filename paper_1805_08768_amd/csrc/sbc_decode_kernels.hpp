@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
     if (nnz == 0u) return;
 
     const uint32_t n = dd[t].n;
-    float* __restrict__ out = dd[t].out;
+    const gfloat_ptr out = as_global(dd[t].out);
     const float addend = scale * mu;
     const uint32_t* __restrict__ words =
         reinterpret_cast<const uint32_t*>(msg + table_end) + word_off;

@@ -19,6 +19,21 @@ __device__ unsigned long long g_phase_clock[2][1024][16];
 #define SBC_TS_VAL(k, i, v) do {} while (0)
 #endif
 
+// Pointers that a kernel reads out of a descriptor table reach the compiler as generic
+// pointers, and it would use flat memory instructions for them: those are counted against the
+// LDS counter as well, so the first use of any loaded value waits for every outstanding load
+// and LDS operation.  Naming the global address space gives global_load / global_store.
+#ifndef SBC_GLOBAL_AS
+#define SBC_GLOBAL_AS __attribute__((address_space(1)))
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+#endif
+typedef SBC_GLOBAL_AS float* gfloat_ptr;
+typedef const SBC_GLOBAL_AS float* gcfloat_ptr;
+typedef SBC_GLOBAL_AS f32x4* gf32x4_ptr;
+typedef const SBC_GLOBAL_AS f32x4* gcf32x4_ptr;
+__device__ __forceinline__ gfloat_ptr as_global(float* p) { return (gfloat_ptr)p; }
+__device__ __forceinline__ gcfloat_ptr as_global(const float* p) { return (gcfloat_ptr)p; }
+
 // ---------------------------------------------------------------- layout ----
 
 constexpr int kChunk = 8192;             // entries of one tensor handled by one workgroup
@@ -69,9 +84,9 @@ struct TensorDesc {
 };
 
 // Per-tensor results, written on the device.
-struct TensorState {
+struct alignas(8) TensorState {
     uint32_t lo_key[2];    // prefilter: side keys at or above these become candidates
-    uint32_t cand_cnt[2];  // candidates appended per side
+    uint32_t cand_cnt[2];  // candidates appended per side (8-byte aligned: advanced together as one u64)
     uint32_t bin[2];       // histogram path: first-digit bin holding the k-th entry of each side
     uint32_t tau[2];       // full 32-bit threshold key per side (side key space)
     uint32_t itau[2];      // ties at tau are kept up to this index

@@ -4,6 +4,7 @@
 #include "../../include/sbc.h"
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <cmath>
@@ -365,33 +366,32 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
     c->result_idx ^= 1;
     const unsigned gather_y = (unsigned)std::min<uint64_t>(64, std::max<uint64_t>(1, (max_bound + 1023) / 1024));
 
-    // stage boundaries are timed with events only when profiling was asked for:
-    // event 2s is recorded before stage s, event 2s+1 after it
+    // Kernels are timed only when profiling was asked for: the launch then carries a start and a
+    // stop event that take the dispatch's own begin and end time stamps (event 2s and 2s+1 for
+    // stage s), so the figure is the kernel's duration without the gaps between dispatches.
     const int lvl = c->profile_level;
     bool timed[kNumStages] = {};
-    auto mark = [&](int stage, bool begin) {
-        if (lvl >= 2 || (lvl == 1 && stage == kStAccumulate)) {
-            (void)hipEventRecord(c->ev[2 * stage + (begin ? 0 : 1)], stream);
-            if (!begin) timed[stage] = true;
-        }
-    };
+#define SBC_LAUNCH(stage, on, kernel, grid, block, ...)                                                    \
+    do {                                                                                                   \
+        if ((on) && (lvl >= 2 || (lvl == 1 && (stage) == kStAccumulate))) {                                \
+            hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, c->ev[2 * (stage)], c->ev[2 * (stage) + 1], 0, \
+                                  __VA_ARGS__);                                                            \
+            timed[stage] = true;                                                                           \
+        } else {                                                                                           \
+            hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);                               \
+        }                                                                                                  \
+    } while (0)
     auto encode_and_gather = [&](bool profile) {
         if (any_bitmap) {
-            if (profile) mark(kStChunkSummary, true);
-            hipLaunchKernelGGL(k_chunk_summary, dim3(n_chunks), dim3(kChunkWords), 0, stream, c->d_desc,
-                               c->d_chunk_tensor, c->d_bitmap, c->d_sum, b);
-            if (profile) { mark(kStChunkSummary, false); mark(kStTensorScan, true); }
-            hipLaunchKernelGGL(k_tensor_scan, dim3(T), dim3(256), 0, stream, c->d_desc, c->d_sum, c->d_prev_end,
-                               c->d_bitoff, c->d_state, b);
-            if (profile) { mark(kStTensorScan, false); mark(kStPack, true); }
-            hipLaunchKernelGGL(k_pack, dim3(n_chunks), dim3(kChunkWords), 0, stream, c->d_desc, c->d_chunk_tensor,
-                               c->d_bitmap, c->d_sum, c->d_prev_end, c->d_bitoff, b, c->d_stage, res_now);
-            if (profile) mark(kStPack, false);
+            SBC_LAUNCH(kStChunkSummary, profile, k_chunk_summary, dim3(n_chunks), dim3(kChunkWords), c->d_desc,
+                       c->d_chunk_tensor, c->d_bitmap, c->d_sum, b);
+            SBC_LAUNCH(kStTensorScan, profile, k_tensor_scan, dim3(T), dim3(256), c->d_desc, c->d_sum, c->d_prev_end,
+                       c->d_bitoff, c->d_state, b);
+            SBC_LAUNCH(kStPack, profile, k_pack, dim3(n_chunks), dim3(kChunkWords), c->d_desc, c->d_chunk_tensor,
+                       c->d_bitmap, c->d_sum, c->d_prev_end, c->d_bitoff, b, c->d_stage, res_now);
         }
-        if (profile) mark(kStGather, true);
-        hipLaunchKernelGGL(k_gather, dim3(T, gather_y), dim3(256), 0, stream, c->d_desc, c->d_state, T, b,
-                           c->d_stage, msg8, (uint64_t)msg_capacity, res_now, res_next);
-        if (profile) mark(kStGather, false);
+        SBC_LAUNCH(kStGather, profile, k_gather, dim3(T, gather_y), dim3(256), c->d_desc, c->d_state, T, b,
+                   c->d_stage, msg8, (uint64_t)msg_capacity, res_now, res_next);
     };
     auto finish = [&]() -> int {                      // copy the result block back and wait
         if (hipGetLastError() != hipSuccess) return SBC_EHIP;
@@ -407,20 +407,15 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
     // The sampling kernel is skipped when the previous call left filter keys for the same tensor
     // sizes and sparsity (its select kernel derives them from the exact thresholds it found).
     if (!use_history) {
-        mark(kStSample, true);
-        hipLaunchKernelGGL(k_sample_thresholds, dim3(T), dim3(kSampleThreads), 0, stream, c->d_desc, c->d_state,
-                           res_now, c->force_exact);
-        mark(kStSample, false);
+        SBC_LAUNCH(kStSample, true, k_sample_thresholds, dim3(T), dim3(kSampleThreads), c->d_desc, c->d_state,
+                   res_now, c->force_exact);
     }
-    mark(kStAccumulate, true);
-    hipLaunchKernelGGL(k_accumulate_filter, dim3(n_chunks), dim3(kStreamThreads), 0, stream, c->d_desc,
-                       c->d_chunk_tensor, c->d_state, c->d_cand, c->d_bitmap, c->d_stage, res_now);
-    mark(kStAccumulate, false);
-    mark(kStSelect, true);
-    hipLaunchKernelGGL(k_select, dim3(T), dim3(kSelThreads), 0, stream, c->d_desc, c->d_order,
-                       c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 0, res_now);
-    mark(kStSelect, false);
+    SBC_LAUNCH(kStAccumulate, true, k_accumulate_filter, dim3(n_chunks), dim3(kStreamThreads), c->d_desc,
+               c->d_chunk_tensor, c->d_state, c->d_cand, c->d_bitmap, c->d_stage, res_now);
+    SBC_LAUNCH(kStSelect, true, k_select, dim3(T), dim3(kSelThreads), c->d_desc, c->d_order,
+               c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 0, res_now);
     encode_and_gather(true);
+#undef SBC_LAUNCH
     int rc = finish();
     if (rc != SBC_OK) return rc;
     c->dev_desc_valid = true;

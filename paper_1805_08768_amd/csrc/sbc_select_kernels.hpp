@@ -336,7 +336,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         if (chosen) sweep<1>(sh, list, [&](const uint2& e) { if (cand_kept(e.x, e.y, ktau, kitau)) f(e); });
         else sweep<0>(sh, list, [&](const uint2& e) { if (cand_kept(e.x, e.y, ktau, kitau)) f(e); });
     };
-    float* __restrict__ R = d.R;
+    const gfloat_ptr R = as_global(d.R);
 
     if (!(d.flags & kDescFused)) {
         // residual update; positions go to the bitmap
