@@ -49,11 +49,11 @@ __device__ __forceinline__ uint32_t mix32(uint32_t x) {
 
 // --------------------------------------------------------------------------
 // Prefilter thresholds from a sample.  One workgroup per tensor.  Tensors of up to
-// kSampleMax entries are read completely (the threshold is then the exact k-th key to 24
+// kSampleMax entries are read completely (the threshold is then the exact k-th key to 16
 // bits); larger ones contribute 256 runs of 64 consecutive entries, one run at a pseudo-random
 // place in each of 256 equal strata.  With m sampled entries out of n, lambda = k*m/n of them
 // are expected among the tensor's k most extreme; the filter key is the lower edge of the
-// 24-bit key bucket holding the sample's r-th most extreme entry, r = lambda + 5*sqrt(lambda)
+// 16-bit key bucket holding the sample's r-th most extreme entry, r = lambda + 5*sqrt(lambda)
 // + 3, so that the chance of cutting into the true top k is negligible (and harmless: the
 // histogram path then redoes the tensor).  Both sides are selected together, the negative side
 // on complemented keys.  The kernel also clears the per-tensor state and the result block.
@@ -65,8 +65,8 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
     constexpr int COPIES = 16;
     __shared__ uint32_t skey[kSampleMax];             // the sample, as keys (loops stay rolled: small code)
     __shared__ uint32_t hist0[2][256][COPIES];        // first byte: lane-private copies, one bank each
-    __shared__ uint32_t hist[3][2][256];
-    __shared__ uint32_t res[3][8];
+    __shared__ uint32_t hist[2][2][256];
+    __shared__ uint32_t res[2][8];
     __shared__ unsigned long long scratch[kSampleThreads / 64];
     SBC_TS(0, 0);
     const int t = blockIdx.x, tid = threadIdx.x;
@@ -94,34 +94,40 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
     }
     if (rs >= m) return;                              // keep the all-pass keys (0, 0)
 
-    for (int i = tid; i < 3 * 2 * 256; i += kSampleThreads) (&hist[0][0][0])[i] = 0u;
+    for (int i = tid; i < 2 * 256; i += kSampleThreads) (&hist[1][0][0])[i] = 0u;
     for (int i = tid; i < 2 * 256 * COPIES; i += kSampleThreads) (&hist0[0][0][0])[i] = 0u;
+    __syncthreads();
+    // The sample: all of a thread's loads are issued before the first key is formed, so that the
+    // kernel pays the memory latency once.
     const gcfloat_ptr R = as_global(d.R);
     const gcfloat_ptr dW = as_global(d.dW);
-    if (n <= (uint32_t)kSampleMax) {
-#pragma unroll 8
-        for (uint32_t i = tid; i < m; i += kSampleThreads)
-            skey[i] = key_of_bits(__float_as_uint(R[i] + dW[i]));
-    } else {
-        const unsigned long long slots = n / 64u;     // >= RUNS
-        const uint32_t lane = tid & 63u;
-#pragma unroll 16
-        for (uint32_t s = 0; s < (uint32_t)(kSampleMax / kSampleThreads); ++s) {
-            const uint32_t run = s * (kSampleThreads / 64) + (tid >> 6);             // 0..RUNS-1
-            const uint32_t h = mix32(run * 0x9E3779B9u + (uint32_t)t * 0x85EBCA6Bu + 1u);
-            const uint32_t s_lo = (uint32_t)(run * slots / RUNS), s_hi = (uint32_t)((run + 1u) * slots / RUNS);
-            const uint32_t i = (s_lo + h % (s_hi - s_lo)) * 64u + lane;
-            skey[s * kSampleThreads + tid] = key_of_bits(__float_as_uint(R[i] + dW[i]));
+    {
+        constexpr int PER = kSampleMax / kSampleThreads;      // 32
+        float a[PER], w[PER];
+        if (n <= (uint32_t)kSampleMax) {
+#pragma unroll
+            for (int s = 0; s < PER; ++s) {
+                const uint32_t i = s * kSampleThreads + tid;
+                const uint32_t j = i < m ? i : 0u;
+                a[s] = R[j]; w[s] = dW[j];
+            }
+        } else {
+            const unsigned long long slots = n / 64u;     // >= RUNS
+            const uint32_t lane = tid & 63u;
+#pragma unroll
+            for (int s = 0; s < PER; ++s) {
+                const uint32_t run = s * (kSampleThreads / 64) + (tid >> 6);             // 0..RUNS-1
+                const uint32_t h = mix32(run * 0x9E3779B9u + (uint32_t)t * 0x85EBCA6Bu + 1u);
+                const uint32_t s_lo = (uint32_t)(run * slots / RUNS), s_hi = (uint32_t)((run + 1u) * slots / RUNS);
+                const uint32_t i = (s_lo + __umulhi(h, s_hi - s_lo)) * 64u + lane;       // a slot of the run's stratum
+                a[s] = R[i]; w[s] = dW[i];
+            }
         }
+#pragma unroll
+        for (int s = 0; s < PER; ++s) skey[s * kSampleThreads + tid] = key_of_bits(__float_as_uint(a[s] + w[s]));
     }
     __syncthreads();
-
     SBC_TS(0, 1);                                     // sample loaded
-    // three bytes of the r-th largest key (positive side) and of the r-th largest complemented
-    // key (negative side)
-    uint32_t need[2] = {rs, rs};
-    const bool active[2] = {true, true};
-    uint32_t prefix[2] = {0u, 0u};
     {   // first byte: floating-point keys take only a handful of values here, so every lane group
         // counts into its own copy and the copies are added up afterwards
         const int copy = ((tid >> 6) & 1) * 8 + (tid & 7);
@@ -132,28 +138,27 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
             atomicAdd(&hist0[1][(~kp) >> 24][copy], 1u);
         }
         __syncthreads();
-        {
-            uint32_t sum = 0u;
+        uint32_t sum = 0u;
 #pragma unroll
-            for (int c = 0; c < COPIES; ++c) sum += (&hist0[0][0][0])[tid * COPIES + c];   // tid = side*256 + byte
-            (&hist[0][0][0])[tid] = sum;
-        }
+        for (int c = 0; c < COPIES; ++c) sum += (&hist0[0][0][0])[tid * COPIES + c];   // tid = side*256 + byte
+        (&hist[0][0][0])[tid] = sum;
         __syncthreads();
     }
     SBC_TS(0, 2);                                     // first-byte histogram done
+    // two bytes of the r-th largest key (positive side) and of the r-th largest complemented
+    // key (negative side)
+    uint32_t need[2] = {rs, rs};
+    const bool active[2] = {true, true};
+    uint32_t prefix[2] = {0u, 0u};
 #pragma nounroll
-    for (int pass = 0; pass < 3; ++pass) {
-        const int shift = 24 - 8 * pass;
+    for (int pass = 0; pass < 2; ++pass) {
         if (pass > 0) {
-            RunCounter rp, rn;
 #pragma unroll 8
             for (uint32_t i = tid; i < m; i += kSampleThreads) {
                 const uint32_t kp = skey[i], kn = ~kp;
-                if ((kp >> (shift + 8)) == prefix[0]) rp.add(hist[pass][0], (kp >> shift) & 255u);
-                if ((kn >> (shift + 8)) == prefix[1]) rn.add(hist[pass][1], (kn >> shift) & 255u);
+                if ((kp >> 24) == prefix[0]) atomicAdd(&hist[1][0][(kp >> 16) & 255u], 1u);
+                if ((kn >> 24) == prefix[1]) atomicAdd(&hist[1][1][(kn >> 16) & 255u], 1u);
             }
-            rp.flush(hist[pass][0]);
-            rn.flush(hist[pass][1]);
             __syncthreads();
         }
         SBC_TS(0, 3 + 2 * pass);
@@ -165,8 +170,8 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
     }
     SBC_TS(0, 9);
     if (tid == 0) {
-        st[t].lo_key[0] = prefix[0] << 8;             // lower edge of the 24-bit bucket
-        st[t].lo_key[1] = prefix[1] << 8;             // same, in the complemented key space
+        st[t].lo_key[0] = prefix[0] << 16;            // lower edge of the 16-bit bucket
+        st[t].lo_key[1] = prefix[1] << 16;            // same, in the complemented key space
     }
 }
 

@@ -1,10 +1,12 @@
 // Alg. 2 in full, Alg. 1's residual line, and (for tensors of ordinary size) Alg. 3.
 //
 // k_select runs one workgroup per tensor and works on both sign sides together:
-//   * a byte-wise radix select (four passes) over each side's candidate list finds the exact
-//     k-th most extreme key tau and the number r of entries equal to tau that are kept; if
-//     fewer than all ties are kept, a second radix select over the tied indices finds the r
-//     lowest (equal values go to the lowest index);
+//   * a histogram of the leading key bits over a window above the filter key finds the bucket of
+//     the k-th most extreme entry of each side; the few entries of that bucket are ranked
+//     against each other by (key descending, index ascending), which yields the threshold key
+//     tau and the highest index kept among entries equal to tau (equal values go to the lowest
+//     index).  Tie-heavy data falls back to a byte-wise radix select (four passes) for tau and
+//     a second one over the tied indices;
 //   * S, the sum of the k kept values of a side, is accumulated as exact integers per fp32
 //     exponent (independent of the order of the list) and combined in a fixed order in fp64.
 // It then decides the side (positive iff mu+ >= mu-, which for equal counts is S+ >= S-)
@@ -48,16 +50,22 @@ __device__ __forceinline__ void put_ones(uint32_t* words, unsigned long long pos
 
 constexpr uint32_t kSelLds = 8192;                       // candidates per side staged in LDS
 constexpr int kWindow = 2048;                            // bins of the leading-bits histogram
+constexpr int kWinShift = 13;                            // it counts key >> kWinShift: 2^10 steps per octave, two octaves
+constexpr uint32_t kRankMax = 256;                       // threshold buckets up to this size are ranked directly
 static_assert(2 * kFusedMaxK * 4 <= kSelLds * 8, "sort arrays reuse one side's candidate space");
 static_assert(kFusedMaxWords <= kFusedMaxK, "stream words reuse the grouping array");
 
 struct SelectShared {
     uint2 cand[2][kSelLds];                              // both sides' lists when they fit
     union {
-        uint32_t hist16[2][kWindow];                     // leading 16 key bits, as an offset from the filter key
+        uint32_t whist[2][kWindow];                     // leading 19 key bits, as an offset from the filter key
         struct {
             uint32_t hist[4][2][256];                    // byte histograms: [pass][side][byte]
             long long acc[2][256];                       // per-exponent integer sums
+        };
+        struct {                                         // the entries sharing the threshold's leading 16 bits,
+            uint2 bucket[2][kRankMax];                   // and how many of them rank ahead of each
+            uint32_t ahead[2][kRankMax];
         };
         struct {                                         // index sort, after the side is decided
             uint32_t bucket_cnt[kBuckets];               // entries per bucket, then offsets
@@ -67,6 +75,7 @@ struct SelectShared {
     uint32_t res[4][8];
     uint32_t scratch[kSelThreads / 64];
     unsigned long long scratch64[kSelThreads / 64];
+    long long fast_sum[2][kSelThreads / 64];             // per-wavefront partial sums of the common-scale path
     double S[2];
 };
 
@@ -145,18 +154,28 @@ __device__ __forceinline__ bool select_both(SelectShared& sh, const CandLists& l
     return ok;
 }
 
-// Adds the kept values of side S into acc[S][exponent] as exact integers; a thread first adds
-// up runs of equal exponent in a register.
+// Exact sum of the kept values of side S (of -A on the negative side), in two parts.  If
+// `common` is set, every kept entry has the sign of its side and a biased exponent of at least
+// e_ref, and there are at most 2^15 of them: an entry whose exponent exceeds e_ref by at most
+// 24 is added, shifted to the scale of e_ref, to a 64-bit integer the thread keeps in a
+// register (24 + 24 + 15 bits at most); the function returns that integer.  Every other entry
+// goes to acc[S][exponent], exact integers per fp32 exponent in LDS; a thread first adds up
+// runs of equal exponent in a register.
 template <int S>
-__device__ __forceinline__ void exponent_sums(SelectShared& sh, const CandLists& l, uint32_t tk, uint32_t ti) {
+__device__ __forceinline__ long long exponent_sums(SelectShared& sh, const CandLists& l, uint32_t tk, uint32_t ti,
+                                                   bool common, uint32_t e_ref) {
     uint32_t cur_ex = 0u;
-    long long cur = 0ll;
+    long long cur = 0ll, scaled = 0ll;
     sweep<S>(sh, l, [&](const uint2& e) {
         if (cand_kept(e.x, e.y, tk, ti)) {
             const uint32_t u = bits_of_key(S ? ~e.x : e.x);
             uint32_t ex = (u >> 23) & 0xFFu;
             long long m = (long long)(ex ? ((u & 0x7FFFFFu) | 0x800000u) : (u & 0x7FFFFFu));
             if (ex == 0u) ex = 1u;
+            if (common && ex >= e_ref && ex - e_ref <= 24u) {
+                scaled += m << (ex - e_ref);
+                return;
+            }
             if (((u >> 31) != 0u) != (S != 0)) m = -m;           // the negative side sums -A
             if (ex != cur_ex) {
                 if (cur != 0ll) atomicAdd(reinterpret_cast<unsigned long long*>(&sh.acc[S][cur_ex]), (unsigned long long)cur);
@@ -166,6 +185,7 @@ __device__ __forceinline__ void exponent_sums(SelectShared& sh, const CandLists&
         }
     });
     if (cur != 0ll) atomicAdd(reinterpret_cast<unsigned long long*>(&sh.acc[S][cur_ex]), (unsigned long long)cur);
+    return scaled;
 }
 
 // One workgroup per tensor; `order` lists the tensors by decreasing size so that the
@@ -203,23 +223,23 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     list.g[1] = cand + d.cand_off + n; list.cnt[1] = cnt_n;
     list.staged = cnt_p <= kSelLds && cnt_n <= kSelLds;
 
-    // Leading 16 key bits of the k-th most extreme entry of each side.  Every candidate's key is at
-    // or above the side's filter key, and nearly all lie within a few octaves of it, so a window
-    // of kWindow values of (key >> 16) starting at the filter key's is histogrammed in the same
-    // sweep that stages the lists in LDS; the top bin collects everything beyond the window.
+    // Leading 19 key bits of the k-th most extreme entry of each side.  Every candidate's key is at
+    // or above the side's filter key, and the k-th lies close above it, so a window of kWindow
+    // values of (key >> kWinShift) starting at the filter key's is histogrammed in the same sweep
+    // that stages the lists in LDS; the top bin collects everything beyond the window.
     uint32_t need[2] = {k, k}, tau[2] = {0u, 0u};
     const bool both[2] = {true, true};
-    const uint32_t base16[2] = {st[t].lo_key[0] >> 16, st[t].lo_key[1] >> 16};
+    const uint32_t wbase[2] = {st[t].lo_key[0] >> kWinShift, st[t].lo_key[1] >> kWinShift};
     bool ok = true;
-    for (int i = tid; i < 2 * kWindow; i += kSelThreads) (&sh.hist16[0][0])[i] = 0u;
+    for (int i = tid; i < 2 * kWindow; i += kSelThreads) (&sh.whist[0][0])[i] = 0u;
     __syncthreads();
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-        const uint32_t b16 = base16[s];
-        uint32_t* h = sh.hist16[s];
+        const uint32_t wb = wbase[s];
+        uint32_t* h = sh.whist[s];
         auto count = [&](const uint2& e) {
-            const uint32_t v = e.x >> 16;
-            const uint32_t o = v >= b16 ? v - b16 : 0u;   // (no candidate lies below its filter key)
+            const uint32_t v = e.x >> kWinShift;
+            const uint32_t o = v >= wb ? v - wb : 0u;   // (no candidate lies below its filter key)
             atomicAdd(&h[o < (uint32_t)(kWindow - 1) ? o : (uint32_t)(kWindow - 1)], 1u);
         };
         if (list.staged) {
@@ -236,22 +256,76 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     SBC_TS(1, 2);                                     // staged, leading bits counted
     uint32_t digit[2];
     bool found[2];
-    pick_wide_both<kWindow, kSelThreads>(sh.hist16, need, both, sh.res[0], sh.scratch64, digit, found);
-    __syncthreads();                                  // hist16 shares its space with the byte histograms
+    pick_wide_both<kWindow, kSelThreads>(sh.whist, need, both, sh.res[0], sh.scratch64, digit, found);
+    // entries in each side's threshold bucket (same leading 16 bits as the k-th entry)
+    uint32_t bsize[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) bsize[s] = found[s] ? sh.whist[s][digit[s]] : 0u;
+    __syncthreads();                                  // whist shares its space with what follows
     SBC_TS(1, 3);
-    // Remaining bytes of tau, then (second round, only if some ties must be dropped) the r lowest
-    // indices among the entries equal to tau.  A side whose k-th entry lies beyond the window is
-    // selected byte by byte from the top instead.
     uint32_t itau[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};
-    {
+    const bool rankable = found[0] && found[1] && digit[0] != (uint32_t)(kWindow - 1) &&
+                          digit[1] != (uint32_t)(kWindow - 1) && bsize[0] <= kRankMax && bsize[1] <= kRankMax;
+    if (rankable) {
+        // The usual case: few entries share the threshold's leading bits.  They are copied out,
+        // and every thread ranks one of them against the others by (key descending, index
+        // ascending); the entry of rank need - 1 is the k-th of its side, ties included.
+        if (tid < 4) { sh.res[1][tid] = 0u; sh.res[2][tid] = 0u; }
+        for (int i = tid; i < 2 * (int)kRankMax; i += kSelThreads) (&sh.ahead[0][0])[i] = 0u;
+        __syncthreads();
+        auto copy_out = [&](int sd, const uint2& e) {
+            if ((e.x >> kWinShift) == wbase[sd] + digit[sd]) {
+                const uint32_t q = atomicAdd(&sh.res[1][sd], 1u);
+                if (q < kRankMax) sh.bucket[sd][q] = e;
+            }
+        };
+        sweep<0>(sh, list, [&](const uint2& e) { copy_out(0, e); });
+        sweep<1>(sh, list, [&](const uint2& e) { copy_out(1, e); });
+        __syncthreads();
+        SBC_TS_VAL(1, 13, cnt_p | ((unsigned long long)sh.res[1][0] << 32)); SBC_TS_VAL(1, 14, cnt_n | ((unsigned long long)sh.res[1][1] << 32));
+#pragma unroll
+        for (int sd = 0; sd < 2; ++sd) {
+            const uint32_t m = sh.res[1][sd];
+            if (m != bsize[sd] || m == 0u || m > kRankMax) { ok = false; continue; }   // uniform; cannot happen
+            // M = m rounded up to a power of two; kSelThreads / M threads share the work on one entry
+            const uint32_t M = m > 1u ? 1u << (32 - __clz((int)(m - 1u))) : 1u;
+            const uint32_t parts = (uint32_t)kSelThreads / M, i = (uint32_t)tid & (M - 1u), part = (uint32_t)tid / M;
+            if (i < m) {
+                const uint2 me = sh.bucket[sd][i];
+                uint32_t ahead = 0u;
+#pragma unroll 8
+                for (uint32_t j = part; j < m; j += parts) {
+                    const uint2 o = sh.bucket[sd][j];
+                    ahead += (o.x > me.x || (o.x == me.x && o.y < me.y)) ? 1u : 0u;
+                }
+                if (ahead) atomicAdd(&sh.ahead[sd][i], ahead);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int sd = 0; sd < 2; ++sd) {
+            if (ok && (uint32_t)tid < bsize[sd] && sh.ahead[sd][tid] + 1u == need[sd]) {
+                const uint2 me = sh.bucket[sd][tid];
+                sh.res[2][2 * sd] = me.x; sh.res[2][2 * sd + 1] = me.y; sh.res[1][2 + sd] = 1u;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int sd = 0; sd < 2; ++sd) {
+            tau[sd] = sh.res[2][2 * sd]; itau[sd] = sh.res[2][2 * sd + 1];
+            if (sh.res[1][2 + sd] != 1u) ok = false;
+        }
+        __syncthreads();                              // the bucket space is reused below
+    } else {
+        // Tie-heavy data, or a k-th entry beyond the window: tau byte by byte from the top, then
+        // (second round, only if some ties must be dropped) the r lowest indices among the
+        // entries equal to tau.
         bool active[2] = {true, true};
         int first_pass[2];
         uint32_t prefix[2], tie_key[2] = {0u, 0u};
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
-            const bool narrow = found[s] && digit[s] != (uint32_t)(kWindow - 1);
-            first_pass[s] = narrow ? 2 : 0;
-            prefix[s] = narrow ? base16[s] + digit[s] : 0u;
+            first_pass[s] = 0; prefix[s] = 0u; need[s] = k;
         }
 #pragma nounroll
         for (int mode = 0; mode < 2; ++mode) {
@@ -281,11 +355,29 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     // equal exponent in a register
     for (int i = tid; i < 512; i += kSelThreads) (&sh.acc[0][0])[i] = 0ll;
     __syncthreads();
-    exponent_sums<0>(sh, list, tau[0], itau[0]);
-    exponent_sums<1>(sh, list, tau[1], itau[1]);
+    // common-scale path: the k-th entry of a side has the side's sign (so have all kept ones)
+    const bool common[2] = {k <= 32768u && tau[0] > 0x80000000u, k <= 32768u && tau[1] >= 0x80000000u};
+    uint32_t e_ref[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const uint32_t ex = (bits_of_key(s ? ~tau[s] : tau[s]) >> 23) & 0xFFu;
+        e_ref[s] = ex ? ex : 1u;
+    }
+    {
+        long long part[2];
+        part[0] = exponent_sums<0>(sh, list, tau[0], itau[0], common[0], e_ref[0]);
+        part[1] = exponent_sums<1>(sh, list, tau[1], itau[1], common[1], e_ref[1]);
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) part[s] += __shfl_down(part[s], off, 64);
+            if ((tid & 63) == 0) sh.fast_sum[s][tid >> 6] = part[s];
+        }
+    }
     __syncthreads();
     if (tid < 128) {
-        // fixed order: lane l of wavefront s adds exponents 4l..4l+3 ascending, then a fixed shuffle tree
+        // fixed order: lane l of wavefront s adds exponents 4l..4l+3 ascending, then a fixed shuffle
+        // tree; the common-scale integer is added last
         const int s = tid >> 6, lane = tid & 63;
         double v = 0.0;
 #pragma unroll
@@ -295,7 +387,12 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
-        if (lane == 0) sh.S[s] = v;
+        if (lane == 0) {
+            long long total = 0ll;
+#pragma unroll
+            for (int w = 0; w < kSelThreads / 64; ++w) total += sh.fast_sum[s][w];
+            sh.S[s] = v + ldexp((double)total, (int)e_ref[s] - 150);
+        }
     }
     __syncthreads();
     SBC_TS(1, 5);                                     // sums done

@@ -131,7 +131,7 @@ def sampled_positions(n, tensor):
     for run in range(256):
         h = _mix32(run * 0x9E3779B9 + tensor * 0x85EBCA6B + 1)
         lo, hi = run * slots // 256, (run + 1) * slots // 256
-        first = (lo + h % (hi - lo)) * 64
+        first = (lo + ((h * (hi - lo)) >> 32)) * 64
         pos.extend(range(first, first + 64))
     return np.array(pos)
 
