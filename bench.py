@@ -30,10 +30,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 BYTES_PER_ENTRY = 12           # read dW, read R, write R'
 P = 0.001
 
-# HBM bytes per launch of k_accumulate_filter on this workload from rocprofv3 --pmc runs
-# (FETCH_SIZE + WRITE_SIZE, scaled by the same counters on the plain copy kernel); see
-# profiles/.  None until measured.
-MEASURED_TRAFFIC_BYTES = None
+# HBM bytes per launch of k_accumulate_filter on the default workload from two rocprofv3 --pmc
+# runs (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter shows for the plain
+# copy kernel of known size); the figures and commands are in profiles/.
+MEASURED_TRAFFIC_BYTES = 308426510
 
 
 def main() -> int:
@@ -192,7 +192,8 @@ def main() -> int:
         "config": {"workload": name, "p": P, "tensors": T, "entries": N,
                    "step": "sbc_compress + sbc_decompress_accumulate (one client, one round)"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES if args.workload == "resnet50" else None,
                      "kernel": "k_accumulate_filter", "kernel_avg_us": k1_avg_ms * 1e3,
                      "algorithmic_bytes_per_launch": BYTES_PER_ENTRY * N},
         "cpu_baseline": cpu,
