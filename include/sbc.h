@@ -165,14 +165,17 @@ int sbc_last_tensor_stats(sbc_ctx* ctx, int tensor, double* mu_pos, double* mu_n
  * ceil(numel/32). */
 int sbc_last_mask(sbc_ctx* ctx, int tensor, uint32_t* mask_words, size_t n_words);
 
-/* Measurement support: per-kernel durations of sbc_compress(), taken with HIP events
- * recorded on the caller's stream between the kernels of each call.
+/* Measurement support: per-kernel durations of sbc_compress().  A profiled launch carries a
+ * start and a stop event on the caller's stream that take the begin and end time stamps of that
+ * dispatch, so the figure is the kernel's own duration.
  *   level 0  off (default; no events are recorded)
  *   level 1  only the residual-accumulation kernel (the pass that carries the method's
- *            mandatory 12 bytes per entry) is bracketed
- *   level 2  every kernel is bracketed
- * Enabling (or re-enabling) clears the accumulated totals. */
+ *            mandatory 12 bytes per entry) is timed
+ *   level 2  every kernel is timed
+ * sbc_profile_enable sets the level and clears the accumulated totals; sbc_profile_level only
+ * sets the level (a caller may time every n-th call and keep adding up). */
 int sbc_profile_enable(sbc_ctx* ctx, int level);
+int sbc_profile_level(sbc_ctx* ctx, int level);
 
 /* Accumulated time of stage `stage` (0 .. n-1 in launch order; SBC_EINVAL past the end):
  * *name gets a static string (the kernel's name), *total_ms the summed duration over

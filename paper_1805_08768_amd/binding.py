@@ -31,7 +31,7 @@ SBC_ROUTE_HISTOGRAM = 2
 EXPORTS = (
     "sbc_create", "sbc_destroy", "sbc_golomb_bstar", "sbc_num_kept", "sbc_msg_bound",
     "sbc_compress", "sbc_decompress_accumulate", "sbc_last_tensor_stats", "sbc_last_mask",
-    "sbc_profile_enable", "sbc_profile_read", "sbc_copy_baseline", "sbc_set_option",
+    "sbc_profile_enable", "sbc_profile_level", "sbc_profile_read", "sbc_copy_baseline", "sbc_set_option",
     "sbc_last_route", "sbc_strerror",
 )
 
@@ -76,6 +76,8 @@ def load() -> ctypes.CDLL:
     lib.sbc_last_mask.restype = ctypes.c_int
     lib.sbc_profile_enable.argtypes = [vp, ctypes.c_int]
     lib.sbc_profile_enable.restype = ctypes.c_int
+    lib.sbc_profile_level.argtypes = [vp, ctypes.c_int]
+    lib.sbc_profile_level.restype = ctypes.c_int
     lib.sbc_profile_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_char_p),
                                      ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
     lib.sbc_profile_read.restype = ctypes.c_int
@@ -222,6 +224,12 @@ def sbc_last_mask(ctx, tensor: int, numel: int) -> torch.Tensor:
     if rc != SBC_OK:
         raise SbcError(rc, "sbc_last_mask")
     return words
+
+
+def sbc_profile_level(ctx, level: int) -> None:
+    rc = load().sbc_profile_level(ctx, int(level))
+    if rc != SBC_OK:
+        raise SbcError(rc, "sbc_profile_level")
 
 
 def sbc_profile_enable(ctx, level: int) -> None:

@@ -17,9 +17,10 @@
 
 namespace sbc {
 
-constexpr int kDecThreads = 256;
+constexpr int kDecThreads = 512;
 constexpr int kMaxB = 30;
 constexpr int kStates = kMaxB + 1;
+constexpr int kPackedMaxB = 15;               // up to 16 states fit one 64-bit word of 4-bit fields
 
 struct DecDesc {
     float* out;
@@ -45,37 +46,61 @@ __device__ __forceinline__ int first_zero_from(unsigned long long w, int x) {
     return zz ? __clzll((long long)zz) : 64;
 }
 
+// State in which Alg. 4 leaves a 64-bit segment that it enters in state s (the first s bits
+// finish a remainder).
+__device__ __forceinline__ int exit_state_of(unsigned long long w64, int s, int b) {
+    int x = s;
+    while (true) {
+        if (x >= 64) return x - 64;
+        const int z = first_zero_from(w64, x);
+        if (z == 64) return 0;
+        x = z + b + 1;
+    }
+}
+
+// Transition functions over at most 16 states as 4-bit fields of one word: field s holds f(s).
+__device__ __forceinline__ int apply_packed(unsigned long long f, int s) { return (int)((f >> (4 * s)) & 15ull); }
+// later o earlier
+__device__ __forceinline__ unsigned long long compose_packed(unsigned long long later, unsigned long long earlier, int S) {
+    unsigned long long r = 0ull;
+    for (int s = 0; s < S; ++s) r |= ((later >> (4 * apply_packed(earlier, s))) & 15ull) << (4 * s);
+    return r;
+}
+
 __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
         const uint8_t* __restrict__ msg, unsigned long long msg_bytes,
-        const DecDesc* __restrict__ dd, int T, int b, float scale, ResultBlock* __restrict__ result) {
-    __shared__ uint8_t fn[2][kStates][kDecThreads];       // transition functions, [state][segment]
+        const DecDesc* __restrict__ dd, int T, int b, float scale, ResultBlock* __restrict__ result,
+        ResultBlock* __restrict__ next_result) {
+    __shared__ uint8_t fn[2][kStates][kDecThreads];       // transition functions, [state][segment] (b > kPackedMaxB)
+    __shared__ unsigned long long wave_fn[kDecThreads / 64];
     __shared__ unsigned long long scratch64[kDecThreads / 64];
     __shared__ uint32_t s_state;
     __shared__ uint32_t tile[kTileWords + kTileSlack];   // words past the stream read as ones
 
     const int tid = threadIdx.x;
     const int t = blockIdx.x;
+    if (t == 0 && tid == 0) { next_result->err = 0u; next_result->pad = 0u; next_result->msg_bytes = 0ull; }
 
-    // ---- header and table entry (validated by every workgroup; all threads agree) ----
+    // ---- header and table entry (validated by every workgroup; all threads agree).  The host has
+    // checked that the message holds the header and T table entries, so all loads go out together.
     const uint32_t* h = reinterpret_cast<const uint32_t*>(msg);
     const unsigned long long table_end = 32ull + 24ull * (unsigned)T;
-    bool ok = msg_bytes >= table_end && h[0] == 0x31434253u && h[1] == 1u &&
-              h[2] == (uint32_t)T && h[3] == (uint32_t)b;
-    unsigned long long payload_words = 0ull, bit_len = 0ull, word_off = 0ull;
-    uint32_t nnz = 0u;
-    float mu = 0.f;
+    const uint8_t* e = msg + 32 + 24ull * (unsigned)t;
+    const uint32_t h0 = h[0], h1 = h[1], h2 = h[2], h3 = h[3];
+    const unsigned long long payload_words = *reinterpret_cast<const unsigned long long*>(msg + 16);
+    const float mu = *reinterpret_cast<const float*>(e);
+    const uint32_t nnz = *reinterpret_cast<const uint32_t*>(e + 4);
+    const unsigned long long bit_len = *reinterpret_cast<const unsigned long long*>(e + 8);
+    const unsigned long long word_off = *reinterpret_cast<const unsigned long long*>(e + 16);
+    const uint32_t n = dd[t].n;
+    const gfloat_ptr out = as_global(dd[t].out);
+    bool ok = msg_bytes >= table_end && h0 == 0x31434253u && h1 == 1u && h2 == (uint32_t)T && h3 == (uint32_t)b;
     if (ok) {
-        payload_words = *reinterpret_cast<const unsigned long long*>(msg + 16);
-        const uint8_t* e = msg + 32 + 24ull * (unsigned)t;
-        mu = *reinterpret_cast<const float*>(e);
-        nnz = *reinterpret_cast<const uint32_t*>(e + 4);
-        bit_len = *reinterpret_cast<const unsigned long long*>(e + 8);
-        word_off = *reinterpret_cast<const unsigned long long*>(e + 16);
         const unsigned long long max_words = (msg_bytes - table_end) >> 2;
         const unsigned long long n_words_t = (bit_len + 31ull) >> 5;
         ok = payload_words <= max_words && bit_len <= (max_words << 5) &&
              word_off <= payload_words && n_words_t <= payload_words - word_off &&
-             nnz <= dd[t].n && (unsigned long long)nnz * (unsigned)(b + 1) <= bit_len &&
+             nnz <= n && (unsigned long long)nnz * (unsigned)(b + 1) <= bit_len &&
              (nnz != 0u || bit_len == 0ull);
     }
     if (!ok) {
@@ -84,14 +109,14 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
     }
     if (nnz == 0u) return;
 
-    const uint32_t n = dd[t].n;
-    const gfloat_ptr out = as_global(dd[t].out);
     const float addend = scale * mu;
     const uint32_t* __restrict__ words =
         reinterpret_cast<const uint32_t*>(msg + table_end) + word_off;
     const unsigned long long n_words = (bit_len + 31ull) >> 5;
     const unsigned long long n_seg = (bit_len + 63ull) >> 6;
     const int S = b + 1;                                  // number of states
+    const bool packed = b <= kPackedMaxB;
+    const int lane = tid & 63, wave = tid >> 6;
 
     int carry_state = 0;
     unsigned long long carry_U = 0ull;   // unary ones so far
@@ -116,36 +141,49 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
         __syncthreads();
         const unsigned long long w64 = ((unsigned long long)tile[2 * tid] << 32) | tile[2 * tid + 1];
 
-        // ---- exit state for every entry state ----
-        for (int s = 0; s < S; ++s) {
-            int x = s;                       // entry state j: the first j bits finish a remainder
-            int exit_state = 0;
-            while (true) {
-                if (x >= 64) { exit_state = x - 64; break; }
-                const int z = first_zero_from(w64, x);
-                if (z == 64) { exit_state = 0; break; }
-                x = z + b + 1;
+        int entry;
+        if (packed) {
+            // ---- exit state per entry state in one word; scan under composition with shuffles
+            // inside a wavefront, then the state is walked through the wavefronts' totals ----
+            unsigned long long f = 0ull;
+            for (int s = 0; s < S; ++s) f |= (unsigned long long)exit_state_of(w64, s, b) << (4 * s);
+#pragma unroll
+            for (int dlt = 1; dlt < 64; dlt <<= 1) {
+                const unsigned long long o = __shfl_up(f, dlt, 64);
+                if (lane >= dlt) f = compose_packed(f, o, S);
             }
-            fn[0][s][tid] = (uint8_t)exit_state;
-        }
-        __syncthreads();
-
-        // ---- inclusive scan under composition: fn[cur][.][i] = f_i o ... o f_0 ----
-        int cur = 0;
-        for (int dlt = 1; dlt < kDecThreads; dlt <<= 1) {
-            for (int s = 0; s < S; ++s) {
-                uint8_t v;
-                if (tid >= dlt) v = fn[cur][fn[cur][s][tid - dlt]][tid];
-                else v = fn[cur][s][tid];
-                fn[cur ^ 1][s][tid] = v;
-            }
+            if (lane == 63) wave_fn[wave] = f;
+            const unsigned long long before = __shfl_up(f, 1, 64);   // lanes 0..lane-1 of this wavefront
             __syncthreads();
-            cur ^= 1;
+            int st = carry_state, st_mine = carry_state;
+#pragma unroll
+            for (int w = 0; w < kDecThreads / 64; ++w) {
+                if (w == wave) st_mine = st;
+                st = apply_packed(wave_fn[w], st);
+            }
+            entry = lane == 0 ? st_mine : apply_packed(before, st_mine);
+            carry_state = st;                              // the same in every thread
+        } else {
+            // ---- exit state for every entry state, one byte each ----
+            for (int s = 0; s < S; ++s) fn[0][s][tid] = (uint8_t)exit_state_of(w64, s, b);
+            __syncthreads();
+            // ---- inclusive scan under composition: fn[cur][.][i] = f_i o ... o f_0 ----
+            int cur = 0;
+            for (int dlt = 1; dlt < kDecThreads; dlt <<= 1) {
+                for (int s = 0; s < S; ++s) {
+                    uint8_t v;
+                    if (tid >= dlt) v = fn[cur][fn[cur][s][tid - dlt]][tid];
+                    else v = fn[cur][s][tid];
+                    fn[cur ^ 1][s][tid] = v;
+                }
+                __syncthreads();
+                cur ^= 1;
+            }
+            entry = (tid == 0) ? carry_state : (int)fn[cur][carry_state][tid - 1];
+            if (tid == kDecThreads - 1) s_state = fn[cur][carry_state][tid];
+            __syncthreads();
+            carry_state = (int)s_state;
         }
-        const int entry = (tid == 0) ? carry_state : (int)fn[cur][carry_state][tid - 1];
-        if (tid == kDecThreads - 1) s_state = fn[cur][carry_state][tid];
-        __syncthreads();
-        carry_state = (int)s_state;
 
         // ---- first walk: unary ones, terminators and remainder sum of this segment ----
         uint32_t nU = 0u, nT = 0u;
@@ -163,16 +201,25 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
                 x = z + b + 1;
             }
         }
-        unsigned long long tile_U, tile_T, tile_R;
-        const unsigned long long exU = block_excl_sum<unsigned long long, kDecThreads>(nU, &tile_U, scratch64);
-        const unsigned long long exT = block_excl_sum<unsigned long long, kDecThreads>(nT, &tile_T, scratch64);
-        const unsigned long long exR = block_excl_sum<unsigned long long, kDecThreads>(sR, &tile_R, scratch64);
+        unsigned long long exU, exT, exR, tile_U, tile_T, tile_R;
+        if (packed) {
+            // a tile holds at most 2^15 ones and codes, and remainders below 2^32 in total
+            unsigned long long tot;
+            const unsigned long long ex = block_excl_sum<unsigned long long, kDecThreads>(
+                (unsigned long long)nU | ((unsigned long long)nT << 16) | (sR << 32), &tot, scratch64);
+            exU = ex & 0xFFFFull; exT = (ex >> 16) & 0xFFFFull; exR = ex >> 32;
+            tile_U = tot & 0xFFFFull; tile_T = (tot >> 16) & 0xFFFFull; tile_R = tot >> 32;
+        } else {
+            exU = block_excl_sum<unsigned long long, kDecThreads>(nU, &tile_U, scratch64);
+            exT = block_excl_sum<unsigned long long, kDecThreads>(nT, &tile_T, scratch64);
+            exR = block_excl_sum<unsigned long long, kDecThreads>(sR, &tile_R, scratch64);
+        }
 
         // ---- second walk: place every code whose terminating zero lies in this segment ----
         if (seg < n_seg && !bad) {
             unsigned long long U = carry_U + exU, Tn = carry_T + exT, R = carry_R + exR;
             int x = entry;
-            uint32_t pend[4];                // positions are distinct: update them four at a time
+            uint32_t pend[8];                // positions are distinct: update them eight at a time
             int np = 0;
             while (x < 64) {
                 const int z = first_zero_from(w64, x);
@@ -184,16 +231,24 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
                 if (pos >= n || Tn >= nnz) { bad = true; break; }
                 if (Tn == (unsigned long long)nnz - 1ull && zpos + 1ull + (unsigned)b != bit_len) bad = true;
                 pend[np++] = (uint32_t)pos;
-                if (np == 4) {
-                    const float v0 = out[pend[0]], v1 = out[pend[1]], v2 = out[pend[2]], v3 = out[pend[3]];
-                    out[pend[0]] = v0 + addend; out[pend[1]] = v1 + addend;
-                    out[pend[2]] = v2 + addend; out[pend[3]] = v3 + addend;
+                if (np == 8) {
+                    float v[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) v[i] = out[pend[i]];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) out[pend[i]] = v[i] + addend;
                     np = 0;
                 }
                 ++Tn;
                 x = z + b + 1;
             }
-            for (int i = 0; i < np; ++i) out[pend[i]] += addend;
+            if (np) {
+                float v[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) v[i] = out[pend[i < np ? i : 0]];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) if (i < np) out[pend[i]] = v[i] + addend;
+            }
         }
         carry_U += tile_U; carry_T += tile_T; carry_R += tile_R;
     }

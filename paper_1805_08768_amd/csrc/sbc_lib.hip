@@ -30,6 +30,14 @@ const char* const kStageNames[kNumStages] = {
     "k_pack", "k_gather"};
 }  // namespace
 
+constexpr int kDescSlots = 4;
+struct DescSlot {
+    bool valid = false;
+    uint64_t stamp = 0;
+    std::vector<const float*> dW;
+    std::vector<float*> R;
+};
+
 struct sbc_ctx {
     int device = 0;
     int64_t max_elems = 0;
@@ -40,6 +48,13 @@ struct sbc_ctx {
 
     // device scratch
     TensorDesc* d_desc = nullptr;
+    // sizes and totals of the last planned call, and the device copies of the tensor table
+    bool cache_valid = false; int cache_T = 0; double cache_p = 0.0;
+    std::vector<int64_t> cache_numel;
+    DescSlot slot[kDescSlots];
+    uint64_t slot_clock = 0;
+    uint64_t cache_total = 0, cache_chunks = 0, cache_stage_words = 0, cache_kept_total = 0, cache_max_bound = 0;
+    bool cache_any_bitmap = false;
     uint32_t* d_chunk_tensor = nullptr;
     uint32_t* d_order = nullptr;
     uint32_t* d_hist = nullptr;
@@ -63,8 +78,6 @@ struct sbc_ctx {
     TensorState* h_state = nullptr;
 
     // what the device tables currently hold
-    int dev_T = 0;
-    bool dev_desc_valid = false;
     int dev_dec_T = 0;
     bool dev_dec_valid = false;
 
@@ -78,6 +91,8 @@ struct sbc_ctx {
     std::vector<uint32_t> hist_n;
     int result_idx = 0;           // compress calls alternate between result blocks 0 and 1; decode uses 2
     bool result_dirty = true;     // the next compress call must clear its result blocks itself
+    bool dec_result_dirty = true; // same for decode
+    int dec_result_idx = 0;
 
     // optional per-kernel timing with HIP events on the caller's stream
     int profile_level = 0;
@@ -157,6 +172,14 @@ int status_of_err(uint32_t err) {
 
 }  // namespace
 
+#ifdef SBC_PHASE_TIMING
+#include <chrono>
+static double g_host_ts[16];
+#define SBC_HOST_TS(i) (g_host_ts[i] = std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now().time_since_epoch()).count())
+#else
+#define SBC_HOST_TS(i) ((void)0)
+#endif
+
 extern "C" {
 
 const char* sbc_strerror(int code) {
@@ -214,7 +237,7 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     DeviceGuard guard(device);
     const size_t T = (size_t)max_tensors;
     bool ok = true;
-    ok = ok && dev_alloc(&c->d_desc, T) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_desc, (size_t)kDescSlots * T) == hipSuccess;
     ok = ok && dev_alloc(&c->d_chunk_tensor, (size_t)c->max_chunks) == hipSuccess;
     ok = ok && dev_alloc(&c->d_order, T) == hipSuccess;
     ok = ok && dev_alloc(&c->d_hist, T * kL1Bins) == hipSuccess;
@@ -226,7 +249,7 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     ok = ok && dev_alloc(&c->d_sum, (size_t)c->max_chunks) == hipSuccess;
     ok = ok && dev_alloc(&c->d_prev_end, (size_t)c->max_chunks) == hipSuccess;
     ok = ok && dev_alloc(&c->d_bitoff, (size_t)c->max_chunks) == hipSuccess;
-    ok = ok && dev_alloc(&c->d_result, 3) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_result, 4) == hipSuccess;      // two for compress, two for decode, used in turn
     ok = ok && dev_alloc(&c->d_dec, T) == hipSuccess;
     ok = ok && host_alloc(&c->h_desc, T) == hipSuccess;
     ok = ok && host_alloc(&c->h_chunk_tensor, (size_t)c->max_chunks) == hipSuccess;
@@ -282,75 +305,126 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
     const int b = bstar_of(p);
     if (b > kMaxB) return SBC_EINVAL;
     c->last_ok = false;
+    SBC_HOST_TS(0);
 
     // ---- plan: tensor table, chunk numbering, staging layout ----
+    // Everything but the pointers depends only on the tensor sizes and p, and is kept from call
+    // to call while those stay the same.  The tensor table itself (sizes, offsets and the
+    // pointers) lives in one of kDescSlots device copies keyed by the pointer lists, so a caller
+    // that alternates between a few sets of buffers uploads nothing in the steady state.
     uint64_t total = 0, chunks = 0, stage_words = 0, kept_total = 0, max_bound = 0;
-    bool same = c->dev_desc_valid && c->dev_T == T;
     bool any_bitmap = false;
     bool use_history = c->hist_valid && !c->force_exact && c->hist_p == p && c->hist_n.size() == (size_t)T;
-    if (c->plan.size() < (size_t)T) c->plan.resize(T);
-    for (int t = 0; t < T; ++t) {
-        const int64_t n = numel[t];
-        if (n < 1 || n >= (int64_t)1 << 32) return SBC_EINVAL;
-        if (!dW[t] || !residual[t]) return SBC_EINVAL;
+    const bool sizes_same = c->cache_valid && c->cache_T == T && c->cache_p == p &&
+                            std::memcmp(c->cache_numel.data(), numel, sizeof(int64_t) * T) == 0;
+    auto pointers_ok = [&](int t) -> bool {
+        if (!dW[t] || !residual[t]) return false;
         const uintptr_t a = (uintptr_t)dW[t], r = (uintptr_t)residual[t];
-        if ((a & 3u) || (r & 3u)) return SBC_EINVAL;
-        const uintptr_t bytes = (uintptr_t)n * 4u;
-        if (a < r + bytes && r < a + bytes) return SBC_EINVAL;    // dW overlaps the residual
-        TensorDesc d;
-        std::memset(&d, 0, sizeof(d));
-        d.dW = dW[t];
-        d.R = residual[t];
-        d.n = (uint32_t)n;
-        d.k = (uint32_t)kept_of(n, p);
-        d.chunk0 = (uint32_t)chunks;
-        d.nchunks = (uint32_t)((n + kChunk - 1) / kChunk);
-        d.cand_off = 2 * total;
-        d.stage_off = stage_words;
-        const uint64_t bw = bound_words_of(n, d.k, b);
-        if (bw >= (1ull << 32)) return SBC_ECAPACITY;
-        d.bound_words = (uint32_t)bw;
-        const bool fused = d.k <= kFusedMaxK && bw <= kFusedMaxWords;
-        d.flags = fused ? kDescFused : 0u;
-        d.kept_off = (uint32_t)kept_total;
-        if (fused) kept_total += d.k; else any_bitmap = true;
-        if (same && std::memcmp(&d, &c->h_desc[t], sizeof(d)) != 0) same = false;
-        if (use_history && c->hist_n[t] != d.n) use_history = false;
-        total += (uint64_t)n;
-        chunks += d.nchunks;
-        stage_words += bw;
-        max_bound = std::max<uint64_t>(max_bound, bw);
-        if (total > (uint64_t)c->max_elems || chunks > c->max_chunks || kept_total > c->kept_cap ||
-            stage_words > c->stage_cap)
-            return SBC_ECAPACITY;
-        c->plan[t] = d;                               // h_desc may still mirror the device copy
+        if ((a & 3u) || (r & 3u)) return false;
+        const uintptr_t bytes = (uintptr_t)numel[t] * 4u;
+        return !(a < r + bytes && r < a + bytes);     // dW must not overlap the residual
+    };
+    int slot = -1;
+    if (sizes_same) {
+        total = c->cache_total; chunks = c->cache_chunks; stage_words = c->cache_stage_words;
+        kept_total = c->cache_kept_total; max_bound = c->cache_max_bound; any_bitmap = c->cache_any_bitmap;
+        if (use_history)
+            for (int t = 0; t < T; ++t) if (c->hist_n[t] != c->plan[t].n) { use_history = false; break; }
+        for (int i = 0; i < kDescSlots; ++i) {
+            const DescSlot& sl = c->slot[i];
+            if (sl.valid && std::memcmp(sl.dW.data(), dW, sizeof(float*) * T) == 0 &&
+                std::memcmp(sl.R.data(), residual, sizeof(float*) * T) == 0) { slot = i; break; }
+        }
+        if (slot < 0)
+            for (int t = 0; t < T; ++t) if (!pointers_ok(t)) return SBC_EINVAL;
+    } else {
+        c->cache_valid = false;
+        for (int i = 0; i < kDescSlots; ++i) c->slot[i].valid = false;
+        if (c->plan.size() < (size_t)T) c->plan.resize(T);
+        for (int t = 0; t < T; ++t) {
+            const int64_t n = numel[t];
+            if (n < 1 || n >= (int64_t)1 << 32) return SBC_EINVAL;
+            if (!pointers_ok(t)) return SBC_EINVAL;
+            TensorDesc d;
+            std::memset(&d, 0, sizeof(d));
+            d.n = (uint32_t)n;
+            d.k = (uint32_t)kept_of(n, p);
+            d.chunk0 = (uint32_t)chunks;
+            d.nchunks = (uint32_t)((n + kChunk - 1) / kChunk);
+            d.cand_off = 2 * total;
+            d.stage_off = stage_words;
+            const uint64_t bw = bound_words_of(n, d.k, b);
+            if (bw >= (1ull << 32)) return SBC_ECAPACITY;
+            d.bound_words = (uint32_t)bw;
+            const bool fused = d.k <= kFusedMaxK && bw <= kFusedMaxWords;
+            d.flags = fused ? kDescFused : 0u;
+            d.kept_off = (uint32_t)kept_total;
+            if (fused) kept_total += d.k; else any_bitmap = true;
+            if (use_history && c->hist_n[t] != d.n) use_history = false;
+            total += (uint64_t)n;
+            chunks += d.nchunks;
+            stage_words += bw;
+            max_bound = std::max<uint64_t>(max_bound, bw);
+            if (total > (uint64_t)c->max_elems || chunks > c->max_chunks || kept_total > c->kept_cap ||
+                stage_words > c->stage_cap)
+                return SBC_ECAPACITY;
+            c->plan[t] = d;
+        }
+        if (chunks >= (1ull << 31)) return SBC_ECAPACITY;
     }
-    if (chunks >= (1ull << 31)) return SBC_ECAPACITY;
     const size_t need = (size_t)(32 + 24ull * (unsigned)T + 4ull * stage_words);
     if (msg_capacity < need) return SBC_ECAPACITY;
 
     DeviceGuard guard(c->device);
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
-    if (!same) {
+    if (!sizes_same) {
+        // tables that depend on the sizes only: tensors by decreasing size, chunk -> tensor
         c->plan_order.resize(T);
         std::iota(c->plan_order.begin(), c->plan_order.end(), 0u);
         std::stable_sort(c->plan_order.begin(), c->plan_order.end(),
                          [&](uint32_t x, uint32_t y) { return c->plan[x].n > c->plan[y].n; });
         for (int t = 0; t < T; ++t) {
-            c->h_desc[t] = c->plan[t];
             c->h_order[t] = c->plan_order[t];
             uint32_t* ct = c->h_chunk_tensor + c->plan[t].chunk0;
             for (uint32_t j = 0; j < c->plan[t].nchunks; ++j) ct[j] = (uint32_t)t;
         }
-        c->dev_desc_valid = false;
-        if (hipMemcpyAsync(c->d_desc, c->h_desc, sizeof(TensorDesc) * T, hipMemcpyHostToDevice, stream) != hipSuccess ||
-            hipMemcpyAsync(c->d_order, c->h_order, sizeof(uint32_t) * T, hipMemcpyHostToDevice, stream) != hipSuccess ||
+        if (hipMemcpyAsync(c->d_order, c->h_order, sizeof(uint32_t) * T, hipMemcpyHostToDevice, stream) != hipSuccess ||
             hipMemcpyAsync(c->d_chunk_tensor, c->h_chunk_tensor, sizeof(uint32_t) * chunks, hipMemcpyHostToDevice, stream) != hipSuccess) {
             (void)hipGetLastError();
             return SBC_EHIP;
         }
-        c->dev_T = T;
+        c->cache_numel.assign(numel, numel + T);
+        c->cache_T = T; c->cache_p = p;
+        c->cache_total = total; c->cache_chunks = chunks; c->cache_stage_words = stage_words;
+        c->cache_kept_total = kept_total; c->cache_max_bound = max_bound; c->cache_any_bitmap = any_bitmap;
+        // (cache_valid is set once this call has completed: the uploads above must have happened)
     }
+    bool slot_is_new = false;
+    if (slot < 0) {
+        // the least recently used slot receives this call's table
+        slot = 0;
+        for (int i = 0; i < kDescSlots; ++i) {
+            if (!c->slot[i].valid) { slot = i; break; }
+            if (c->slot[i].stamp < c->slot[slot].stamp) slot = i;
+        }
+        DescSlot& sl = c->slot[slot];
+        sl.valid = false;
+        for (int t = 0; t < T; ++t) {
+            c->h_desc[t] = c->plan[t];
+            c->h_desc[t].dW = dW[t];
+            c->h_desc[t].R = residual[t];
+        }
+        if (hipMemcpyAsync(c->d_desc + (size_t)slot * c->max_tensors, c->h_desc, sizeof(TensorDesc) * T,
+                           hipMemcpyHostToDevice, stream) != hipSuccess) {
+            (void)hipGetLastError();
+            return SBC_EHIP;
+        }
+        sl.dW.assign(dW, dW + T);
+        sl.R.assign(residual, residual + T);
+        slot_is_new = true;
+    }
+    c->slot[slot].stamp = ++c->slot_clock;
+    TensorDesc* const d_desc = c->d_desc + (size_t)slot * c->max_tensors;
 
     uint8_t* msg8 = static_cast<uint8_t*>(msg);
     const uint32_t n_chunks = (uint32_t)chunks;
@@ -383,42 +457,50 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
     } while (0)
     auto encode_and_gather = [&](bool profile) {
         if (any_bitmap) {
-            SBC_LAUNCH(kStChunkSummary, profile, k_chunk_summary, dim3(n_chunks), dim3(kChunkWords), c->d_desc,
+            SBC_LAUNCH(kStChunkSummary, profile, k_chunk_summary, dim3(n_chunks), dim3(kChunkWords), d_desc,
                        c->d_chunk_tensor, c->d_bitmap, c->d_sum, b);
-            SBC_LAUNCH(kStTensorScan, profile, k_tensor_scan, dim3(T), dim3(256), c->d_desc, c->d_sum, c->d_prev_end,
+            SBC_LAUNCH(kStTensorScan, profile, k_tensor_scan, dim3(T), dim3(256), d_desc, c->d_sum, c->d_prev_end,
                        c->d_bitoff, c->d_state, b);
-            SBC_LAUNCH(kStPack, profile, k_pack, dim3(n_chunks), dim3(kChunkWords), c->d_desc, c->d_chunk_tensor,
+            SBC_LAUNCH(kStPack, profile, k_pack, dim3(n_chunks), dim3(kChunkWords), d_desc, c->d_chunk_tensor,
                        c->d_bitmap, c->d_sum, c->d_prev_end, c->d_bitoff, b, c->d_stage, res_now);
         }
-        SBC_LAUNCH(kStGather, profile, k_gather, dim3(T, gather_y), dim3(256), c->d_desc, c->d_state, T, b,
+        SBC_LAUNCH(kStGather, profile, k_gather, dim3(T, gather_y), dim3(256), d_desc, c->d_state, T, b,
                    c->d_stage, msg8, (uint64_t)msg_capacity, res_now, res_next);
     };
     auto finish = [&]() -> int {                      // copy the result block back and wait
+        SBC_HOST_TS(2);
         if (hipGetLastError() != hipSuccess) return SBC_EHIP;
-        if (hipMemcpyAsync(c->h_result, res_now, sizeof(ResultBlock), hipMemcpyDeviceToHost, stream) != hipSuccess ||
-            hipStreamSynchronize(stream) != hipSuccess) {
+        if (hipMemcpyAsync(c->h_result, res_now, sizeof(ResultBlock), hipMemcpyDeviceToHost, stream) != hipSuccess) {
             (void)hipGetLastError();
             return SBC_EHIP;
         }
+        SBC_HOST_TS(3);
+        if (hipStreamSynchronize(stream) != hipSuccess) {
+            (void)hipGetLastError();
+            return SBC_EHIP;
+        }
+        SBC_HOST_TS(4);
         return SBC_OK;
     };
 
+    SBC_HOST_TS(1);
     // ---- fast path: [sample ->] accumulate + filter -> select (+ fused encode) -> gather ----
     // The sampling kernel is skipped when the previous call left filter keys for the same tensor
     // sizes and sparsity (its select kernel derives them from the exact thresholds it found).
     if (!use_history) {
-        SBC_LAUNCH(kStSample, true, k_sample_thresholds, dim3(T), dim3(kSampleThreads), c->d_desc, c->d_state,
+        SBC_LAUNCH(kStSample, true, k_sample_thresholds, dim3(T), dim3(kSampleThreads), d_desc, c->d_state,
                    res_now, c->force_exact);
     }
-    SBC_LAUNCH(kStAccumulate, true, k_accumulate_filter, dim3(n_chunks), dim3(kStreamThreads), c->d_desc,
+    SBC_LAUNCH(kStAccumulate, true, k_accumulate_filter, dim3(n_chunks), dim3(kStreamThreads), d_desc,
                c->d_chunk_tensor, c->d_state, c->d_cand, c->d_bitmap, c->d_stage, res_now);
-    SBC_LAUNCH(kStSelect, true, k_select, dim3(T), dim3(kSelThreads), c->d_desc, c->d_order,
+    SBC_LAUNCH(kStSelect, true, k_select, dim3(T), dim3(kSelThreads), d_desc, c->d_order,
                c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 0, res_now);
     encode_and_gather(true);
 #undef SBC_LAUNCH
     int rc = finish();
     if (rc != SBC_OK) return rc;
-    c->dev_desc_valid = true;
+    c->cache_valid = true;
+    if (slot_is_new) c->slot[slot].valid = true;
     c->last_T = T;
     for (int st = 0; st < kNumStages; ++st) {
         if (!timed[st]) continue;
@@ -441,12 +523,12 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
                            (uint64_t)hist_words);
         hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(res_now),
                            (uint64_t)(sizeof(ResultBlock) / 4));
-        hipLaunchKernelGGL(k_hist_flagged, dim3(n_chunks), dim3(kStreamThreads), 0, stream, c->d_desc,
+        hipLaunchKernelGGL(k_hist_flagged, dim3(n_chunks), dim3(kStreamThreads), 0, stream, d_desc,
                            c->d_chunk_tensor, c->d_state, c->d_hist);
-        hipLaunchKernelGGL(k_pick_bins, dim3(T), dim3(256), 0, stream, c->d_desc, c->d_hist, c->d_state, res_now);
-        hipLaunchKernelGGL(k_extract, dim3(n_chunks), dim3(kStreamThreads), 0, stream, c->d_desc,
+        hipLaunchKernelGGL(k_pick_bins, dim3(T), dim3(256), 0, stream, d_desc, c->d_hist, c->d_state, res_now);
+        hipLaunchKernelGGL(k_extract, dim3(n_chunks), dim3(kStreamThreads), 0, stream, d_desc,
                            c->d_chunk_tensor, c->d_state, c->d_cand, res_now);
-        hipLaunchKernelGGL(k_select, dim3(T), dim3(kSelThreads), 0, stream, c->d_desc, c->d_order,
+        hipLaunchKernelGGL(k_select, dim3(T), dim3(kSelThreads), 0, stream, d_desc, c->d_order,
                            c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 1, res_now);
         encode_and_gather(false);
         rc = finish();
@@ -480,6 +562,7 @@ int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, siz
     const int T = n_tensors;
     const int b = bstar_of(p);
     if (b > kMaxB) return SBC_EINVAL;
+    SBC_HOST_TS(8);
     if (msg_bytes < 32 + 24ull * (unsigned)T) return SBC_ECORRUPT;
     bool same = c->dev_dec_valid && c->dev_dec_T == T;
     for (int t = 0; t < T; ++t) {
@@ -497,19 +580,29 @@ int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, siz
         }
         c->dev_dec_T = T;
     }
-    ResultBlock* const res_dec = c->d_result + 2;
-    hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(res_dec),
-                       (uint64_t)(sizeof(ResultBlock) / 4));
+    // the decode kernel leaves the other of its two result blocks clean for the next call
+    if (c->dec_result_dirty) {                        // after an error, or on the first call
+        hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(c->d_result + 2),
+                           (uint64_t)(2 * sizeof(ResultBlock) / 4));
+    }
+    c->dec_result_dirty = true;                       // until this call has completed normally
+    ResultBlock* const res_dec = c->d_result + 2 + c->dec_result_idx;
+    ResultBlock* const res_dec_next = c->d_result + 2 + (c->dec_result_idx ^ 1);
+    c->dec_result_idx ^= 1;
+    SBC_HOST_TS(9);
     hipLaunchKernelGGL(k_decode_accumulate, dim3(T), dim3(kDecThreads), 0, stream,
                        static_cast<const uint8_t*>(msg), (unsigned long long)msg_bytes, c->d_dec, T, b, scale,
-                       res_dec);
+                       res_dec, res_dec_next);
+    SBC_HOST_TS(10);
     if (hipGetLastError() != hipSuccess) return SBC_EHIP;
     if (hipMemcpyAsync(c->h_result, res_dec, sizeof(ResultBlock), hipMemcpyDeviceToHost, stream) != hipSuccess ||
         hipStreamSynchronize(stream) != hipSuccess) {
         (void)hipGetLastError();
         return SBC_EHIP;
     }
+    SBC_HOST_TS(11);
     c->dev_dec_valid = true;
+    if (c->h_result->err == 0u) c->dec_result_dirty = false;
     return status_of_err(c->h_result->err);
 }
 
@@ -528,6 +621,12 @@ int sbc_profile_enable(sbc_ctx* c, int level) {
     if (!c || level < 0 || level > 2) return SBC_EINVAL;
     c->profile_level = level;
     for (int st = 0; st < kNumStages; ++st) { c->stage_ms[st] = 0.0; c->stage_calls[st] = 0; }
+    return SBC_OK;
+}
+
+int sbc_profile_level(sbc_ctx* c, int level) {
+    if (!c || level < 0 || level > 2) return SBC_EINVAL;
+    c->profile_level = level;
     return SBC_OK;
 }
 
@@ -584,6 +683,7 @@ int sbc_last_mask(sbc_ctx* c, int tensor, uint32_t* mask_words, size_t n_words) 
 }
 
 #ifdef SBC_PHASE_TIMING
+int sbc_debug_host_times(double* out) { for (int i = 0; i < 16; ++i) out[i] = g_host_ts[i]; return 0; }
 // tuning builds only: copies the phase clock tables (2 x 1024 x 16 u64) to host memory
 int sbc_debug_phase_clocks(unsigned long long* out) {
     return hipMemcpyFromSymbol(out, HIP_SYMBOL(sbc::g_phase_clock), sizeof(unsigned long long) * 2 * 1024 * 16) == hipSuccess ? 0 : -3;

@@ -421,3 +421,27 @@ def test_inspection_requires_a_successful_compress():
             sbc.sbc_last_mask(ctx, 0, 100)
     finally:
         sbc.sbc_destroy(ctx)
+
+
+def test_alternating_buffer_sets():
+    """A caller that cycles through more sets of update buffers than the library keeps tensor
+    tables for (hits, misses and evictions of the table cache), one residual throughout."""
+    sizes = [5000, 64, 20000, 8193]
+    p = 0.01
+    n_sets = 6
+    host = [synth.small_model_update(sizes, round_=s) for s in range(n_sets)]
+    order = [0, 1, 0, 1, 2, 3, 4, 5, 0, 5, 5, 1]
+    with DeviceRun(sizes) as run:
+        dev = [[torch.from_numpy(x).to(run.device) for x in h] for h in host]
+        lists = [sbc.TensorList(d) for d in dev]
+        R_list = sbc.TensorList(run.R)
+        bound = sbc.sbc_msg_bound(sizes, p)
+        msg = torch.zeros(bound, dtype=torch.uint8, device=run.device)
+        R = [np.zeros(n, np.float32) for n in sizes]
+        for s in order:
+            want = o.compress_model(host[s], R, p)
+            nbytes = sbc.sbc_compress(run.ctx, lists[s], R_list, p, msg)
+            assert bytes(msg[:nbytes].cpu().numpy().tobytes()) == o.build_message(want), "set %d" % s
+            R = [w.R_new for w in want]
+            for t, w in enumerate(want):
+                assert np.array_equal(run.R[t].cpu().numpy(), w.R_new.astype(np.float32)), (s, t)
