@@ -79,6 +79,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
 
     const int tid = threadIdx.x;
     const int t = blockIdx.x;
+    SBC_TS(2, 0);
     if (t == 0 && tid == 0) { next_result->err = 0u; next_result->pad = 0u; next_result->msg_bytes = 0ull; }
 
     // ---- header and table entry (validated by every workgroup; all threads agree).  The host has
@@ -108,6 +109,8 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
         return;
     }
     if (nnz == 0u) return;
+    SBC_TS(2, 1);                                     // header read
+    SBC_TS_VAL(2, 15, nnz);
 
     const float addend = scale * mu;
     const uint32_t* __restrict__ words =
@@ -140,13 +143,21 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
         }
         __syncthreads();
         const unsigned long long w64 = ((unsigned long long)tile[2 * tid] << 32) | tile[2 * tid + 1];
+        SBC_TS(2, 2);                                 // tile staged
 
         int entry;
         if (packed) {
             // ---- exit state per entry state in one word; scan under composition with shuffles
             // inside a wavefront, then the state is walked through the wavefronts' totals ----
-            unsigned long long f = 0ull;
-            for (int s = 0; s < S; ++s) f |= (unsigned long long)exit_state_of(w64, s, b) << (4 * s);
+            // (entering with s bits of a remainder left is entering at bit s in the unary state, and
+            // if bit s - 1 is a one that is the same walk as from bit s - 1)
+            int ex = exit_state_of(w64, 0, b);
+            unsigned long long f = (unsigned long long)ex;
+            for (int s = 1; s < S; ++s) {
+                if (!((w64 >> (64 - s)) & 1ull)) ex = exit_state_of(w64, s, b);
+                f |= (unsigned long long)ex << (4 * s);
+            }
+            SBC_TS(2, 3);                             // exit states
 #pragma unroll
             for (int dlt = 1; dlt < 64; dlt <<= 1) {
                 const unsigned long long o = __shfl_up(f, dlt, 64);
@@ -165,7 +176,12 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
             carry_state = st;                              // the same in every thread
         } else {
             // ---- exit state for every entry state, one byte each ----
-            for (int s = 0; s < S; ++s) fn[0][s][tid] = (uint8_t)exit_state_of(w64, s, b);
+            int ex = exit_state_of(w64, 0, b);
+            fn[0][0][tid] = (uint8_t)ex;
+            for (int s = 1; s < S; ++s) {
+                if (!((w64 >> (64 - s)) & 1ull)) ex = exit_state_of(w64, s, b);
+                fn[0][s][tid] = (uint8_t)ex;
+            }
             __syncthreads();
             // ---- inclusive scan under composition: fn[cur][.][i] = f_i o ... o f_0 ----
             int cur = 0;
@@ -185,6 +201,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
             carry_state = (int)s_state;
         }
 
+        SBC_TS(2, 4);                                 // entry states known
         // ---- first walk: unary ones, terminators and remainder sum of this segment ----
         uint32_t nU = 0u, nT = 0u;
         unsigned long long sR = 0ull;
@@ -201,6 +218,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
                 x = z + b + 1;
             }
         }
+        SBC_TS(2, 5);                                 // first walk
         unsigned long long exU, exT, exR, tile_U, tile_T, tile_R;
         if (packed) {
             // a tile holds at most 2^15 ones and codes, and remainders below 2^32 in total
@@ -215,6 +233,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
             exR = block_excl_sum<unsigned long long, kDecThreads>(sR, &tile_R, scratch64);
         }
 
+        SBC_TS(2, 6);                                 // offsets known
         // ---- second walk: place every code whose terminating zero lies in this segment ----
         if (seg < n_seg && !bad) {
             unsigned long long U = carry_U + exU, Tn = carry_T + exT, R = carry_R + exR;
@@ -242,15 +261,18 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
                 ++Tn;
                 x = z + b + 1;
             }
+            SBC_TS(2, 8);
             if (np) {
                 float v[8];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) v[i] = out[pend[i < np ? i : 0]];
+                for (int i = 0; i < 8; ++i) v[i] = i < np ? out[pend[i]] : 0.f;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) if (i < np) out[pend[i]] = v[i] + addend;
+                SBC_TS(2, 9);
             }
         }
         carry_U += tile_U; carry_T += tile_T; carry_R += tile_R;
+        SBC_TS(2, 7);                                 // placed
     }
     if (carry_T != nnz) bad = true;           // identical in every thread
     if (bad) atomicOr(&result->err, kErrCorrupt);

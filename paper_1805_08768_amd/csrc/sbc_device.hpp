@@ -11,7 +11,7 @@ namespace sbc {
 // Optional phase timestamps for tuning (build with -DSBC_PHASE_TIMING): thread 0 of the first
 // 1024 workgroups of a kernel stores the 100 MHz wall clock into slot `i` of table `k`.
 #ifdef SBC_PHASE_TIMING
-__device__ unsigned long long g_phase_clock[2][1024][16];
+__device__ unsigned long long g_phase_clock[3][1024][16];
 #define SBC_TS(k, i) do { if (threadIdx.x == 0 && blockIdx.x < 1024) g_phase_clock[k][blockIdx.x][i] = wall_clock64(); } while (0)
 #define SBC_TS_VAL(k, i, v) do { if (threadIdx.x == 0 && blockIdx.x < 1024) g_phase_clock[k][blockIdx.x][i] = (v); } while (0)
 #else

@@ -684,9 +684,9 @@ int sbc_last_mask(sbc_ctx* c, int tensor, uint32_t* mask_words, size_t n_words) 
 
 #ifdef SBC_PHASE_TIMING
 int sbc_debug_host_times(double* out) { for (int i = 0; i < 16; ++i) out[i] = g_host_ts[i]; return 0; }
-// tuning builds only: copies the phase clock tables (2 x 1024 x 16 u64) to host memory
+// tuning builds only: copies the phase clock tables (3 x 1024 x 16 u64) to host memory
 int sbc_debug_phase_clocks(unsigned long long* out) {
-    return hipMemcpyFromSymbol(out, HIP_SYMBOL(sbc::g_phase_clock), sizeof(unsigned long long) * 2 * 1024 * 16) == hipSuccess ? 0 : -3;
+    return hipMemcpyFromSymbol(out, HIP_SYMBOL(sbc::g_phase_clock), sizeof(unsigned long long) * 3 * 1024 * 16) == hipSuccess ? 0 : -3;
 }
 #endif
 
