@@ -211,8 +211,10 @@ def main() -> int:
         "kernel_us": breakdown,
         "copy_kernel_GBs": copy_gbs,
         "message_bytes": msg_bytes / args.steps,
-        "routes": {"sampled": routes.get(0, 0), "carried_keys": routes.get(1, 0),
-                   "histogram_fallback": sum(v for k, v in routes.items() if k & 2)},
+        "routes": {"sampled": sum(v for k, v in routes.items() if not k & 1),
+                   "carried_keys": sum(v for k, v in routes.items() if k & 1),
+                   "histogram_fallback": sum(v for k, v in routes.items() if k & 2),
+                   "grid_wide_selection": sum(v for k, v in routes.items() if k & 4)},
         "compression_ratio_paper_accounting": ratio,
     }
     print(json.dumps(line))

@@ -140,15 +140,19 @@ int sbc_decompress_accumulate(sbc_ctx* ctx, void* hip_stream,
  *       thresholds of the previous successful call on this context when tensor sizes and p
  *       are unchanged (successive rounds of one training run) and skips the sampling kernel;
  *       it pays off when the thresholds move by less than a few percent from round to round,
- *       and costs time when they move more (a flood of candidates, then a sampled round). */
-enum { SBC_OPT_FORCE_EXACT_PATH = 1, SBC_OPT_CARRY_FILTER_KEYS = 2 };
+ *       and costs time when they move more (a flood of candidates, then a sampled round).
+ *   SBC_OPT_WIDE_MIN_KEPT      (default 0 = 65536)  a tensor that keeps at least this many entries
+ *       per side is selected by grid-wide kernels instead of one workgroup (a 1.5e9-entry tensor
+ *       at p = 0.001 keeps 1.5e6); tests lower it to send small tensors that way. */
+enum { SBC_OPT_FORCE_EXACT_PATH = 1, SBC_OPT_CARRY_FILTER_KEYS = 2, SBC_OPT_WIDE_MIN_KEPT = 3 };
 int sbc_set_option(sbc_ctx* ctx, int option, int value);
 
 /* Which routes the most recent successful sbc_compress() took: a bit set of
  * SBC_ROUTE_CARRIED_KEYS (filter keys came from the previous call, no sampling) and
- * SBC_ROUTE_HISTOGRAM (the histogram route ran for at least one tensor); SBC_EINVAL (negative)
- * without a successful call. */
-enum { SBC_ROUTE_CARRIED_KEYS = 1, SBC_ROUTE_HISTOGRAM = 2 };
+ * SBC_ROUTE_HISTOGRAM (the histogram route ran for at least one tensor), SBC_ROUTE_WIDE (the
+ * grid-wide selection kernels completed at least one tensor); SBC_EINVAL (negative) without a
+ * successful call. */
+enum { SBC_ROUTE_CARRIED_KEYS = 1, SBC_ROUTE_HISTOGRAM = 2, SBC_ROUTE_WIDE = 4 };
 int sbc_last_route(sbc_ctx* ctx);
 
 /* Inspection of the most recent sbc_compress() on this context, for tests and reports

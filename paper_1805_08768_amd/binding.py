@@ -25,8 +25,10 @@ SBC_ENONFINITE = -5
 SBC_EINTERNAL = -6
 SBC_OPT_FORCE_EXACT_PATH = 1
 SBC_OPT_CARRY_FILTER_KEYS = 2
+SBC_OPT_WIDE_MIN_KEPT = 3
 SBC_ROUTE_CARRIED_KEYS = 1
 SBC_ROUTE_HISTOGRAM = 2
+SBC_ROUTE_WIDE = 4
 
 EXPORTS = (
     "sbc_create", "sbc_destroy", "sbc_golomb_bstar", "sbc_num_kept", "sbc_msg_bound",

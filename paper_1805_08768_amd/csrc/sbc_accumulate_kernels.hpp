@@ -48,7 +48,7 @@ __device__ __forceinline__ uint32_t mix32(uint32_t x) {
 }
 
 // --------------------------------------------------------------------------
-// Prefilter thresholds from a sample.  One workgroup per tensor.  Tensors of up to
+// Prefilter thresholds from a sample.  One workgroup (1024 threads) per tensor.  Tensors of up to
 // kSampleMax entries are read completely (the threshold is then the exact k-th key to 16
 // bits); larger ones contribute 256 runs of 64 consecutive entries, one run at a pseudo-random
 // place in each of 256 equal strata.  With m sampled entries out of n, lambda = k*m/n of them
@@ -138,10 +138,12 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
             atomicAdd(&hist0[1][(~kp) >> 24][copy], 1u);
         }
         __syncthreads();
-        uint32_t sum = 0u;
+        if (tid < 2 * 256) {
+            uint32_t sum = 0u;
 #pragma unroll
-        for (int c = 0; c < COPIES; ++c) sum += (&hist0[0][0][0])[tid * COPIES + c];   // tid = side*256 + byte
-        (&hist[0][0][0])[tid] = sum;
+            for (int c = 0; c < COPIES; ++c) sum += (&hist0[0][0][0])[tid * COPIES + c];   // tid = side*256 + byte
+            (&hist[0][0][0])[tid] = sum;
+        }
         __syncthreads();
     }
     SBC_TS(0, 2);                                     // first-byte histogram done

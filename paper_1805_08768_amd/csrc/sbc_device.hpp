@@ -59,13 +59,16 @@ constexpr uint32_t kErrNonFinite = 1u;
 constexpr uint32_t kErrInternal = 2u;
 constexpr uint32_t kErrCorrupt = 4u;
 constexpr uint32_t kErrPrefilter = 8u;   // not an error: some tensor needs the histogram path
+constexpr uint32_t kErrWide = 32u;       // not an error: the grid-wide selection kernels completed some tensor
 constexpr uint32_t kErrLoose = 16u;      // not an error: a carried-over filter key let far too many entries pass
 
 // TensorDesc::flags
 constexpr uint32_t kDescFused = 1u;      // sorted and encoded inside the select kernel
+constexpr uint32_t kDescWide = 2u;       // keeps so many entries that the grid-wide selection kernels take it
 // TensorState::flags
 constexpr uint32_t kStFailed = 1u;       // prefilter kept fewer than k candidates on a side
 constexpr uint32_t kStExact = 2u;        // taken over by the histogram path
+constexpr uint32_t kStWideDone = 4u;     // selected and applied by the grid-wide kernels
 
 // One tensor of the call, built on the host.
 struct TensorDesc {

@@ -18,19 +18,22 @@
 #include "sbc_select_kernels.hpp"
 #include "sbc_encode_kernels.hpp"
 #include "sbc_decode_kernels.hpp"
+#include "sbc_wide_kernels.hpp"
 
 using namespace sbc;
 
 namespace {
 // kernels of sbc_compress in launch order (the histogram path repeats some of them)
-enum Stage { kStSample = 0, kStAccumulate, kStSelect, kStChunkSummary, kStTensorScan, kStPack, kStGather,
-             kNumStages };
+enum Stage { kStSample = 0, kStAccumulate, kStWide, kStSelect, kStChunkSummary, kStTensorScan, kStPack,
+             kStGather, kNumStages };
 const char* const kStageNames[kNumStages] = {
-    "k_sample_thresholds", "k_accumulate_filter", "k_select", "k_chunk_summary", "k_tensor_scan",
-    "k_pack", "k_gather"};
+    "k_sample_thresholds", "k_accumulate_filter", "k_wide_* (grid-wide selection, all launches)", "k_select",
+    "k_chunk_summary", "k_tensor_scan", "k_pack", "k_gather"};
 }  // namespace
 
 constexpr int kDescSlots = 4;
+constexpr int kMaxWide = 64;             // tensors per call that the grid-wide selection kernels can take
+constexpr uint32_t kWideMinKept = 65536; // ... and how many entries a tensor must keep to be given to them
 struct DescSlot {
     bool valid = false;
     uint64_t stamp = 0;
@@ -55,6 +58,16 @@ struct sbc_ctx {
     uint64_t slot_clock = 0;
     uint64_t cache_total = 0, cache_chunks = 0, cache_stage_words = 0, cache_kept_total = 0, cache_max_bound = 0;
     bool cache_any_bitmap = false;
+    // grid-wide selection
+    uint32_t wide_min_kept = kWideMinKept;
+    int n_wide = 0;
+    uint32_t wide_blocks = 0;
+    uint32_t* d_wide_ids = nullptr;
+    uint32_t* h_wide_ids = nullptr;
+    WideState* d_wide_state = nullptr;
+    uint32_t* d_wide_hist = nullptr;
+    long long* d_wide_acc = nullptr;
+    uint32_t* d_wide_tie = nullptr;
     uint32_t* d_chunk_tensor = nullptr;
     uint32_t* d_order = nullptr;
     uint32_t* d_hist = nullptr;
@@ -106,6 +119,7 @@ struct sbc_ctx {
     bool last_ok = false;
     bool last_used_exact_path = false;
     bool last_used_history = false;
+    bool last_used_wide = false;
     std::vector<TensorDesc> plan;
     std::vector<uint32_t> plan_order;
 };
@@ -153,6 +167,9 @@ void free_all(sbc_ctx* c) {
     (void)hipFree(c->d_state); (void)hipFree(c->d_cand); (void)hipFree(c->d_bitmap); (void)hipFree(c->d_stage);
     (void)hipFree(c->d_kept); (void)hipFree(c->d_sum); (void)hipFree(c->d_prev_end); (void)hipFree(c->d_bitoff);
     (void)hipFree(c->d_result); (void)hipFree(c->d_dec);
+    (void)hipFree(c->d_wide_ids); (void)hipFree(c->d_wide_state); (void)hipFree(c->d_wide_hist);
+    (void)hipFree(c->d_wide_acc); (void)hipFree(c->d_wide_tie);
+    if (c->h_wide_ids) (void)hipHostFree(c->h_wide_ids);
     if (c->h_desc) (void)hipHostFree(c->h_desc);
     if (c->h_chunk_tensor) (void)hipHostFree(c->h_chunk_tensor);
     if (c->h_order) (void)hipHostFree(c->h_order);
@@ -251,6 +268,15 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     ok = ok && dev_alloc(&c->d_bitoff, (size_t)c->max_chunks) == hipSuccess;
     ok = ok && dev_alloc(&c->d_result, 4) == hipSuccess;      // two for compress, two for decode, used in turn
     ok = ok && dev_alloc(&c->d_dec, T) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_wide_ids, (size_t)kMaxWide) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_wide_state, (size_t)kMaxWide) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_wide_hist, (size_t)kMaxWide * 2 * kWindow) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_wide_acc, (size_t)kMaxWide * 512) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_wide_tie, (size_t)kMaxWide * 2 * kWideTieMax) == hipSuccess;
+    ok = ok && host_alloc(&c->h_wide_ids, (size_t)kMaxWide) == hipSuccess;
+    // the histograms and accumulators start out zero; the kernels that read them leave them zero
+    ok = ok && hipMemset(c->d_wide_hist, 0, sizeof(uint32_t) * kMaxWide * 2 * kWindow) == hipSuccess;
+    ok = ok && hipMemset(c->d_wide_acc, 0, sizeof(long long) * kMaxWide * 512) == hipSuccess;
     ok = ok && host_alloc(&c->h_desc, T) == hipSuccess;
     ok = ok && host_alloc(&c->h_chunk_tensor, (size_t)c->max_chunks) == hipSuccess;
     ok = ok && host_alloc(&c->h_order, T) == hipSuccess;
@@ -290,6 +316,11 @@ int sbc_set_option(sbc_ctx* c, int option, int value) {
     switch (option) {
         case SBC_OPT_FORCE_EXACT_PATH: c->force_exact = value ? 1 : 0; c->hist_valid = false; return SBC_OK;
         case SBC_OPT_CARRY_FILTER_KEYS: c->carry_keys = value ? 1 : 0; c->hist_valid = false; return SBC_OK;
+        case SBC_OPT_WIDE_MIN_KEPT:
+            if (value < 0) return SBC_EINVAL;
+            c->wide_min_kept = value ? (uint32_t)value : kWideMinKept;
+            c->cache_valid = false;                    // which tensors are wide is part of the plan
+            return SBC_OK;
         default: return SBC_EINVAL;
     }
 }
@@ -341,6 +372,8 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
         c->cache_valid = false;
         for (int i = 0; i < kDescSlots; ++i) c->slot[i].valid = false;
         if (c->plan.size() < (size_t)T) c->plan.resize(T);
+        int n_wide = 0;
+        uint64_t wide_max_n = 0;
         for (int t = 0; t < T; ++t) {
             const int64_t n = numel[t];
             if (n < 1 || n >= (int64_t)1 << 32) return SBC_EINVAL;
@@ -358,6 +391,11 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
             d.bound_words = (uint32_t)bw;
             const bool fused = d.k <= kFusedMaxK && bw <= kFusedMaxWords;
             d.flags = fused ? kDescFused : 0u;
+            if (!fused && d.k >= c->wide_min_kept && n_wide < kMaxWide) {
+                d.flags |= kDescWide;
+                c->h_wide_ids[n_wide++] = (uint32_t)t;
+                wide_max_n = std::max<uint64_t>(wide_max_n, (uint64_t)n);
+            }
             d.kept_off = (uint32_t)kept_total;
             if (fused) kept_total += d.k; else any_bitmap = true;
             if (use_history && c->hist_n[t] != d.n) use_history = false;
@@ -371,6 +409,9 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
             c->plan[t] = d;
         }
         if (chunks >= (1ull << 31)) return SBC_ECAPACITY;
+        c->n_wide = n_wide;
+        // sweeps over a candidate list: enough workgroups to fill the chip, each with several rounds
+        c->wide_blocks = (uint32_t)std::min<uint64_t>(2048, std::max<uint64_t>(64, wide_max_n / 65536));
     }
     const size_t need = (size_t)(32 + 24ull * (unsigned)T + 4ull * stage_words);
     if (msg_capacity < need) return SBC_ECAPACITY;
@@ -388,7 +429,8 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
             uint32_t* ct = c->h_chunk_tensor + c->plan[t].chunk0;
             for (uint32_t j = 0; j < c->plan[t].nchunks; ++j) ct[j] = (uint32_t)t;
         }
-        if (hipMemcpyAsync(c->d_order, c->h_order, sizeof(uint32_t) * T, hipMemcpyHostToDevice, stream) != hipSuccess ||
+        if ((c->n_wide > 0 && hipMemcpyAsync(c->d_wide_ids, c->h_wide_ids, sizeof(uint32_t) * c->n_wide, hipMemcpyHostToDevice, stream) != hipSuccess) ||
+            hipMemcpyAsync(c->d_order, c->h_order, sizeof(uint32_t) * T, hipMemcpyHostToDevice, stream) != hipSuccess ||
             hipMemcpyAsync(c->d_chunk_tensor, c->h_chunk_tensor, sizeof(uint32_t) * chunks, hipMemcpyHostToDevice, stream) != hipSuccess) {
             (void)hipGetLastError();
             return SBC_EHIP;
@@ -493,6 +535,37 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
     }
     SBC_LAUNCH(kStAccumulate, true, k_accumulate_filter, dim3(n_chunks), dim3(kStreamThreads), d_desc,
                c->d_chunk_tensor, c->d_state, c->d_cand, c->d_bitmap, c->d_stage, res_now);
+    if (c->n_wide > 0) {
+        // tensors that keep very many entries: Alg. 2 as grid-wide sweeps over their candidate lists
+        const dim3 sweep(c->wide_blocks, (unsigned)c->n_wide), one((unsigned)c->n_wide);
+        const bool time_wide = lvl >= 2;
+        for (int pass = 0; pass < 3; ++pass) {
+            if (pass == 0 && time_wide) {
+                hipExtLaunchKernelGGL(k_wide_count, sweep, dim3(kWideThreads), 0, stream, c->ev[2 * kStWide], nullptr, 0,
+                                      d_desc, c->d_wide_ids, c->d_state, c->d_cand, c->d_wide_state, c->d_wide_hist, pass);
+            } else {
+                hipLaunchKernelGGL(k_wide_count, sweep, dim3(kWideThreads), 0, stream, d_desc, c->d_wide_ids, c->d_state,
+                                   c->d_cand, c->d_wide_state, c->d_wide_hist, pass);
+            }
+            hipLaunchKernelGGL(k_wide_pick, one, dim3(kSelThreads), 0, stream, d_desc, c->d_wide_ids, c->d_state,
+                               c->d_wide_state, c->d_wide_hist, pass);
+        }
+        hipLaunchKernelGGL(k_wide_ties, sweep, dim3(kWideThreads), 0, stream, d_desc, c->d_wide_ids, c->d_state,
+                           c->d_cand, c->d_wide_state, c->d_wide_tie);
+        hipLaunchKernelGGL(k_wide_rank, one, dim3(kSelThreads), 0, stream, c->d_wide_ids, c->d_wide_state, c->d_wide_tie);
+        hipLaunchKernelGGL(k_wide_sums, sweep, dim3(kWideThreads), 0, stream, d_desc, c->d_wide_ids, c->d_state,
+                           c->d_cand, c->d_wide_state, c->d_wide_acc);
+        hipLaunchKernelGGL(k_wide_decide, one, dim3(128), 0, stream, d_desc, c->d_wide_ids, c->d_state,
+                           c->d_wide_state, c->d_wide_acc, res_now);
+        if (time_wide) {
+            hipExtLaunchKernelGGL(k_wide_apply, sweep, dim3(kWideThreads), 0, stream, nullptr, c->ev[2 * kStWide + 1], 0,
+                                  d_desc, c->d_wide_ids, c->d_state, c->d_cand, c->d_wide_state, c->d_bitmap, res_now);
+            timed[kStWide] = true;
+        } else {
+            hipLaunchKernelGGL(k_wide_apply, sweep, dim3(kWideThreads), 0, stream, d_desc, c->d_wide_ids, c->d_state,
+                               c->d_cand, c->d_wide_state, c->d_bitmap, res_now);
+        }
+    }
     SBC_LAUNCH(kStSelect, true, k_select, dim3(T), dim3(kSelThreads), d_desc, c->d_order,
                c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 0, res_now);
     encode_and_gather(true);
@@ -514,6 +587,7 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
     }
     uint32_t err = c->h_result->err;
     c->last_used_exact_path = false;
+    c->last_used_wide = (err & kErrWide) != 0u;
 
     // ---- histogram path for the tensors whose filter kept fewer than k candidates ----
     if ((err & kErrPrefilter) && !(err & (kErrInternal | kErrNonFinite))) {
@@ -692,7 +766,8 @@ int sbc_debug_phase_clocks(unsigned long long* out) {
 
 int sbc_last_route(sbc_ctx* c) {
     if (!c || !c->last_ok) return SBC_EINVAL;
-    return (c->last_used_history ? SBC_ROUTE_CARRIED_KEYS : 0) | (c->last_used_exact_path ? SBC_ROUTE_HISTOGRAM : 0);
+    return (c->last_used_history ? SBC_ROUTE_CARRIED_KEYS : 0) | (c->last_used_exact_path ? SBC_ROUTE_HISTOGRAM : 0) |
+           (c->last_used_wide ? SBC_ROUTE_WIDE : 0);
 }
 
 }  // extern "C"

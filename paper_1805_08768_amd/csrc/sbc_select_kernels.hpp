@@ -201,6 +201,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     const int t = (int)order[blockIdx.x], tid = threadIdx.x;
     if (pass == 1 && !(st[t].flags & kStExact)) return;
     const TensorDesc d = desc[t];
+    if (pass == 0 && (d.flags & kDescWide) && (st[t].flags & kStWideDone)) return;   // done by the grid-wide kernels
     const uint32_t k = d.k, n = d.n;
     const uint32_t cnt_p = __builtin_amdgcn_readfirstlane(st[t].cand_cnt[0]);
     const uint32_t cnt_n = __builtin_amdgcn_readfirstlane(st[t].cand_cnt[1]);

@@ -445,3 +445,43 @@ def test_alternating_buffer_sets():
             R = [w.R_new for w in want]
             for t, w in enumerate(want):
                 assert np.array_equal(run.R[t].cpu().numpy(), w.R_new.astype(np.float32)), (s, t)
+
+
+def _planted_threshold_ties(n, k, seed_tensor):
+    """Gaussian values with 40 more copies of the k-th largest and of the k-th smallest value at
+    random places, so that both thresholds fall inside a group of equal values."""
+    x = synth.gaussian_update(n, tensor=seed_tensor)
+    g = synth.rng_for(8, 0, 0, seed_tensor)
+    order = np.argsort(-x, kind="stable")
+    hi, lo = x[order[k - 1]], x[order[n - k]]
+    mid = order[2 * k: n - 2 * k]
+    where = g.choice(mid, size=80, replace=False)
+    x[where[:40]] = hi
+    x[where[40:]] = lo
+    return x
+
+
+def test_grid_wide_selection():
+    """Tensors that keep many entries take the grid-wide selection kernels (threshold lowered by
+    option so that the oracle finishes in seconds): plain data, thresholds inside groups of
+    equal values, and tie-heavy data that those kernels hand back to the one-workgroup kernel."""
+    sizes = [100000, 300, 65536, 9000]
+    p = 0.1
+    with DeviceRun(sizes) as run:
+        sbc.sbc_set_option(run.ctx, sbc.SBC_OPT_WIDE_MIN_KEPT, 6500)
+        R = [np.zeros(n, np.float32) for n in sizes]
+        for r in range(3):
+            dWs = [synth.gaussian_update(n, round_=r, tensor=i) for i, n in enumerate(sizes)]
+            res = check_round(run, dWs, R, p)
+            assert sbc.sbc_last_route(run.ctx) & sbc.SBC_ROUTE_WIDE
+            R = [x.R_new for x in res]
+    sizes = [200000, 80000]
+    with DeviceRun(sizes) as run:
+        sbc.sbc_set_option(run.ctx, sbc.SBC_OPT_WIDE_MIN_KEPT, 6500)
+        dWs = [_planted_threshold_ties(n, int(p * n), i) for i, n in enumerate(sizes)]
+        check_round(run, dWs, [np.zeros(n, np.float32) for n in sizes], p)
+        assert sbc.sbc_last_route(run.ctx) & sbc.SBC_ROUTE_WIDE
+    with DeviceRun(sizes) as run:
+        sbc.sbc_set_option(run.ctx, sbc.SBC_OPT_WIDE_MIN_KEPT, 6500)
+        dWs = [synth.palette_update(n, tensor=i) for i, n in enumerate(sizes)]
+        check_round(run, dWs, [np.zeros(n, np.float32) for n in sizes], p)
