@@ -25,7 +25,7 @@ constexpr int kPackedMaxB = 15;               // up to 16 states fit one 64-bit 
 struct DecDesc {
     float* out;
     uint32_t n;
-    uint32_t pad;
+    uint32_t wide;        // 1: decoded by the tile kernels below, not by k_decode_accumulate
 };
 
 constexpr int kTileWords = 2 * kDecThreads;   // stream words covered by one tile of segments
@@ -81,6 +81,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
     const int t = blockIdx.x;
     SBC_TS(2, 0);
     if (t == 0 && tid == 0) { next_result->err = 0u; next_result->pad = 0u; next_result->msg_bytes = 0ull; }
+    if (dd[t].wide) return;
 
     // ---- header and table entry (validated by every workgroup; all threads agree).  The host has
     // checked that the message holds the header and T table entries, so all loads go out together.
@@ -275,6 +276,292 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
         SBC_TS(2, 7);                                 // placed
     }
     if (carry_T != nnz) bad = true;           // identical in every thread
+    if (bad) atomicOr(&result->err, kErrCorrupt);
+}
+
+// --------------------------------------------------------------------------
+// One long stream decoded by many workgroups, a tile of kDecThreads segments each (streams of
+// tensors that keep very many entries; needs b <= kPackedMaxB).  The dependence between tiles is
+// what k_decode_accumulate carries from tile to tile in registers; here it goes through memory:
+//   k_dec_tile_fn      per tile: every segment's transition function composed with those before
+//                      it in the tile (seg_fn), and the tile's total (tile_fn)
+//   k_dec_tile_entry   per stream: the state in which each tile is entered (tile_entry)
+//   k_dec_tile_sums    per tile: with the entry states known, the unary ones, codes and
+//                      remainder sum before each segment within the tile (seg_pack) and the
+//                      tile's totals (tile_sum)
+//   k_dec_tile_offsets per stream: exclusive sums of the tile totals (tile_off); the code count
+//                      must equal nnz
+//   k_dec_tile_place   per tile: positions, checks, out[j] += fl32(scale * mu)
+// --------------------------------------------------------------------------
+struct DecWide {
+    uint32_t t;           // tensor
+    uint32_t tile0;       // first tile of this stream in the tile arrays
+    uint32_t max_tiles;   // tiles reserved for it (from the worst-case stream length)
+    uint32_t pad;
+    uint64_t seg0;        // first segment of this stream in the segment arrays
+};
+
+struct StreamInfo {
+    bool ok;
+    float mu;
+    uint32_t nnz, n;
+    unsigned long long bit_len, word_off, n_words, n_seg;
+    const uint32_t* words;
+};
+
+// Header and table entry of tensor t, validated as in k_decode_accumulate.
+__device__ __forceinline__ StreamInfo stream_info(const uint8_t* __restrict__ msg, unsigned long long msg_bytes,
+                                                  const DecDesc* __restrict__ dd, int T, int b, int t) {
+    StreamInfo si;
+    const uint32_t* h = reinterpret_cast<const uint32_t*>(msg);
+    const unsigned long long table_end = 32ull + 24ull * (unsigned)T;
+    const uint8_t* e = msg + 32 + 24ull * (unsigned)t;
+    const uint32_t h0 = h[0], h1 = h[1], h2 = h[2], h3 = h[3];
+    const unsigned long long payload_words = *reinterpret_cast<const unsigned long long*>(msg + 16);
+    si.mu = *reinterpret_cast<const float*>(e);
+    si.nnz = *reinterpret_cast<const uint32_t*>(e + 4);
+    si.bit_len = *reinterpret_cast<const unsigned long long*>(e + 8);
+    si.word_off = *reinterpret_cast<const unsigned long long*>(e + 16);
+    si.n = dd[t].n;
+    si.ok = msg_bytes >= table_end && h0 == 0x31434253u && h1 == 1u && h2 == (uint32_t)T && h3 == (uint32_t)b;
+    si.n_words = (si.bit_len + 31ull) >> 5;
+    si.n_seg = (si.bit_len + 63ull) >> 6;
+    if (si.ok) {
+        const unsigned long long max_words = (msg_bytes - table_end) >> 2;
+        si.ok = payload_words <= max_words && si.bit_len <= (max_words << 5) &&
+                si.word_off <= payload_words && si.n_words <= payload_words - si.word_off &&
+                si.nnz <= si.n && (unsigned long long)si.nnz * (unsigned)(b + 1) <= si.bit_len &&
+                (si.nnz != 0u || si.bit_len == 0ull);
+    }
+    si.words = reinterpret_cast<const uint32_t*>(msg + table_end) + si.word_off;
+    return si;
+}
+
+// Which stream and tile a workgroup of a tile kernel works on; false if it has nothing to do.
+__device__ __forceinline__ bool tile_of_block(const DecWide* __restrict__ dw, int n_wide, uint32_t blk,
+                                              int* which, uint32_t* tile) {
+    for (int i = 0; i < n_wide; ++i) {
+        if (blk >= dw[i].tile0 && blk < dw[i].tile0 + dw[i].max_tiles) { *which = i; *tile = blk - dw[i].tile0; return true; }
+    }
+    return false;
+}
+
+// Stages the words of tile `tile` in LDS (bits at or past bit_len read as ones) and returns the
+// calling thread's 64-bit segment.  Contains barriers.
+__device__ __forceinline__ unsigned long long stage_tile(const StreamInfo& si, uint32_t tile, uint32_t* lds_tile) {
+    const int tid = threadIdx.x;
+    const unsigned long long w0 = 2ull * kDecThreads * tile;
+    __syncthreads();
+    for (int i = tid; i < kTileWords + kTileSlack; i += kDecThreads) {
+        const unsigned long long w = w0 + (unsigned)i;
+        uint32_t v = 0xFFFFFFFFu;
+        if (w < si.n_words) {
+            v = si.words[w];
+            const unsigned long long valid = si.bit_len - 32ull * w;
+            if (valid < 32ull) v |= (0xFFFFFFFFu >> valid);
+        }
+        lds_tile[i] = v;
+    }
+    __syncthreads();
+    return ((unsigned long long)lds_tile[2 * tid] << 32) | lds_tile[2 * tid + 1];
+}
+
+__global__ __launch_bounds__(kDecThreads) void k_dec_tile_fn(
+        const uint8_t* __restrict__ msg, unsigned long long msg_bytes, const DecDesc* __restrict__ dd,
+        const DecWide* __restrict__ dw, int n_wide, int T, int b,
+        unsigned long long* __restrict__ seg_fn, unsigned long long* __restrict__ tile_fn,
+        ResultBlock* __restrict__ result) {
+    __shared__ uint32_t tile_words[kTileWords + kTileSlack];
+    __shared__ unsigned long long wave_fn[kDecThreads / 64];
+    int which; uint32_t tile;
+    if (!tile_of_block(dw, n_wide, blockIdx.x, &which, &tile)) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const StreamInfo si = stream_info(msg, msg_bytes, dd, T, b, (int)dw[which].t);
+    const unsigned long long n_tiles = (si.n_seg + kDecThreads - 1) / kDecThreads;
+    if (!si.ok || n_tiles > dw[which].max_tiles) {        // a valid stream never exceeds its worst case
+        if (tile == 0 && tid == 0) atomicOr(&result->err, kErrCorrupt);
+        return;
+    }
+    if (tile >= n_tiles) return;
+    const int S = b + 1;
+    const unsigned long long w64 = stage_tile(si, tile, tile_words);
+    int ex = exit_state_of(w64, 0, b);
+    unsigned long long f = (unsigned long long)ex;
+    for (int s = 1; s < S; ++s) {
+        if (!((w64 >> (64 - s)) & 1ull)) ex = exit_state_of(w64, s, b);
+        f |= (unsigned long long)ex << (4 * s);
+    }
+#pragma unroll
+    for (int dlt = 1; dlt < 64; dlt <<= 1) {
+        const unsigned long long o = __shfl_up(f, dlt, 64);
+        if (lane >= dlt) f = compose_packed(f, o, S);
+    }
+    if (lane == 63) wave_fn[wave] = f;
+    __syncthreads();
+    // everything before this wavefront, as one function
+    unsigned long long before = 0ull;
+    for (int s = 0; s < S; ++s) before |= (unsigned long long)s << (4 * s);      // identity
+    for (int w = 0; w < wave; ++w) before = compose_packed(wave_fn[w], before, S);
+    f = compose_packed(f, before, S);
+    seg_fn[dw[which].seg0 + (unsigned long long)tile * kDecThreads + tid] = f;
+    if (tid == kDecThreads - 1) tile_fn[dw[which].tile0 + tile] = f;
+}
+
+__global__ __launch_bounds__(1024) void k_dec_tile_entry(
+        const uint8_t* __restrict__ msg, unsigned long long msg_bytes, const DecDesc* __restrict__ dd,
+        const DecWide* __restrict__ dw, int T, int b,
+        const unsigned long long* __restrict__ tile_fn, uint32_t* __restrict__ tile_entry) {
+    constexpr int kBatch = 4096;
+    __shared__ unsigned long long fns[kBatch];
+    __shared__ uint32_t states[kBatch];
+    __shared__ uint32_t s_carry;
+    const int which = blockIdx.x, tid = threadIdx.x;
+    const StreamInfo si = stream_info(msg, msg_bytes, dd, T, b, (int)dw[which].t);
+    const unsigned long long n_tiles = (si.n_seg + kDecThreads - 1) / kDecThreads;
+    if (!si.ok || n_tiles > dw[which].max_tiles) return;   // reported by k_dec_tile_fn
+    if (tid == 0) s_carry = 0u;
+    for (unsigned long long t0 = 0; t0 < n_tiles; t0 += kBatch) {
+        const uint32_t m = (uint32_t)((n_tiles - t0 < (unsigned long long)kBatch) ? n_tiles - t0 : kBatch);
+        __syncthreads();
+        for (uint32_t i = tid; i < m; i += 1024) fns[i] = tile_fn[dw[which].tile0 + t0 + i];
+        __syncthreads();
+        if (tid == 0) {
+            int st = (int)s_carry;
+            for (uint32_t i = 0; i < m; ++i) { states[i] = (uint32_t)st; st = apply_packed(fns[i], st); }
+            s_carry = (uint32_t)st;
+        }
+        __syncthreads();
+        for (uint32_t i = tid; i < m; i += 1024) tile_entry[dw[which].tile0 + t0 + i] = states[i];
+    }
+}
+
+__global__ __launch_bounds__(kDecThreads) void k_dec_tile_sums(
+        const uint8_t* __restrict__ msg, unsigned long long msg_bytes, const DecDesc* __restrict__ dd,
+        const DecWide* __restrict__ dw, int n_wide, int T, int b,
+        const unsigned long long* __restrict__ seg_fn, const uint32_t* __restrict__ tile_entry,
+        unsigned long long* __restrict__ seg_pack, unsigned long long* __restrict__ tile_sum,
+        ResultBlock* __restrict__ result) {
+    __shared__ uint32_t tile_words[kTileWords + kTileSlack];
+    __shared__ unsigned long long scratch64[kDecThreads / 64];
+    int which; uint32_t tile;
+    if (!tile_of_block(dw, n_wide, blockIdx.x, &which, &tile)) return;
+    const int tid = threadIdx.x;
+    const StreamInfo si = stream_info(msg, msg_bytes, dd, T, b, (int)dw[which].t);
+    const unsigned long long n_tiles = (si.n_seg + kDecThreads - 1) / kDecThreads;
+    if (!si.ok || n_tiles > dw[which].max_tiles || tile >= n_tiles) return;
+    const unsigned long long w64 = stage_tile(si, tile, tile_words);
+    const unsigned long long seg = (unsigned long long)tile * kDecThreads + tid;
+    const int tile_in = (int)tile_entry[dw[which].tile0 + tile];
+    const int entry = tid == 0 ? tile_in : apply_packed(seg_fn[dw[which].seg0 + seg - 1], tile_in);
+    uint32_t nU = 0u, nT = 0u;
+    unsigned long long sR = 0ull;
+    bool bad = false;
+    if (seg < si.n_seg) {
+        int x = entry;
+        while (x < 64) {
+            const int z = first_zero_from(w64, x);
+            nU += (uint32_t)(z - x);
+            if (z == 64) break;
+            const unsigned long long zpos = seg * 64ull + (unsigned)z;
+            if (zpos + 1ull + (unsigned)b > si.bit_len) { bad = true; break; }
+            ++nT;
+            sR += read_bits(tile_words, (uint32_t)(tid * 64 + z + 1), b);
+            x = z + b + 1;
+        }
+    }
+    if (bad) atomicOr(&result->err, kErrCorrupt);
+    unsigned long long tot;
+    const unsigned long long ex = block_excl_sum<unsigned long long, kDecThreads>(
+        (unsigned long long)nU | ((unsigned long long)nT << 16) | (sR << 32), &tot, scratch64);
+    seg_pack[dw[which].seg0 + seg] = ex;
+    if (tid == 0) tile_sum[dw[which].tile0 + tile] = tot;
+}
+
+__global__ __launch_bounds__(1024) void k_dec_tile_offsets(
+        const uint8_t* __restrict__ msg, unsigned long long msg_bytes, const DecDesc* __restrict__ dd,
+        const DecWide* __restrict__ dw, int T, int b,
+        const unsigned long long* __restrict__ tile_sum, unsigned long long* __restrict__ tile_off,
+        ResultBlock* __restrict__ result) {
+    __shared__ unsigned long long scratch64[1024 / 64];
+    const int which = blockIdx.x, tid = threadIdx.x;
+    const StreamInfo si = stream_info(msg, msg_bytes, dd, T, b, (int)dw[which].t);
+    const unsigned long long n_tiles = (si.n_seg + kDecThreads - 1) / kDecThreads;
+    if (!si.ok || n_tiles > dw[which].max_tiles) return;
+    unsigned long long cU = 0ull, cT = 0ull, cR = 0ull;
+    for (unsigned long long t0 = 0; t0 < n_tiles; t0 += 1024) {
+        const unsigned long long i = t0 + tid;
+        const unsigned long long v = i < n_tiles ? tile_sum[dw[which].tile0 + i] : 0ull;
+        unsigned long long tU, tT, tR;
+        const unsigned long long eU = block_excl_sum<unsigned long long, 1024>(v & 0xFFFFull, &tU, scratch64);
+        const unsigned long long eT = block_excl_sum<unsigned long long, 1024>((v >> 16) & 0xFFFFull, &tT, scratch64);
+        const unsigned long long eR = block_excl_sum<unsigned long long, 1024>(v >> 32, &tR, scratch64);
+        if (i < n_tiles) {
+            unsigned long long* o = tile_off + 3ull * (dw[which].tile0 + i);
+            o[0] = cU + eU; o[1] = cT + eT; o[2] = cR + eR;
+        }
+        cU += tU; cT += tT; cR += tR;
+    }
+    if (tid == 0 && cT != si.nnz) atomicOr(&result->err, kErrCorrupt);
+}
+
+__global__ __launch_bounds__(kDecThreads) void k_dec_tile_place(
+        const uint8_t* __restrict__ msg, unsigned long long msg_bytes, const DecDesc* __restrict__ dd,
+        const DecWide* __restrict__ dw, int n_wide, int T, int b, float scale,
+        const unsigned long long* __restrict__ seg_fn, const uint32_t* __restrict__ tile_entry,
+        const unsigned long long* __restrict__ seg_pack, const unsigned long long* __restrict__ tile_off,
+        ResultBlock* __restrict__ result) {
+    __shared__ uint32_t tile_words[kTileWords + kTileSlack];
+    int which; uint32_t tile;
+    if (!tile_of_block(dw, n_wide, blockIdx.x, &which, &tile)) return;
+    const int tid = threadIdx.x;
+    const int t = (int)dw[which].t;
+    const StreamInfo si = stream_info(msg, msg_bytes, dd, T, b, t);
+    const unsigned long long n_tiles = (si.n_seg + kDecThreads - 1) / kDecThreads;
+    if (!si.ok || n_tiles > dw[which].max_tiles || tile >= n_tiles) return;
+    const unsigned long long w64 = stage_tile(si, tile, tile_words);
+    const unsigned long long seg = (unsigned long long)tile * kDecThreads + tid;
+    if (seg >= si.n_seg) return;
+    const int tile_in = (int)tile_entry[dw[which].tile0 + tile];
+    const int entry = tid == 0 ? tile_in : apply_packed(seg_fn[dw[which].seg0 + seg - 1], tile_in);
+    const unsigned long long pk = seg_pack[dw[which].seg0 + seg];
+    const unsigned long long* o = tile_off + 3ull * (dw[which].tile0 + tile);
+    unsigned long long U = o[0] + (pk & 0xFFFFull), Tn = o[1] + ((pk >> 16) & 0xFFFFull), R = o[2] + (pk >> 32);
+    const gfloat_ptr out = as_global(dd[t].out);
+    const float addend = scale * si.mu;
+    const uint32_t n = si.n, nnz = si.nnz;
+    bool bad = false;
+    int x = entry;
+    uint32_t pend[8];
+    int np = 0;
+    while (x < 64) {
+        const int z = first_zero_from(w64, x);
+        U += (unsigned)(z - x);
+        if (z == 64) break;
+        const unsigned long long zpos = seg * 64ull + (unsigned)z;
+        if (zpos + 1ull + (unsigned)b > si.bit_len) { bad = true; break; }
+        R += read_bits(tile_words, (uint32_t)(tid * 64 + z + 1), b);
+        const unsigned long long pos = (U << b) + R + Tn;
+        if (pos >= n || Tn >= nnz) { bad = true; break; }
+        if (Tn == (unsigned long long)nnz - 1ull && zpos + 1ull + (unsigned)b != si.bit_len) bad = true;
+        pend[np++] = (uint32_t)pos;
+        if (np == 8) {
+            float v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = out[pend[i]];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) out[pend[i]] = v[i] + addend;
+            np = 0;
+        }
+        ++Tn;
+        x = z + b + 1;
+    }
+    if (np) {
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = i < np ? out[pend[i]] : 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) if (i < np) out[pend[i]] = v[i] + addend;
+    }
     if (bad) atomicOr(&result->err, kErrCorrupt);
 }
 

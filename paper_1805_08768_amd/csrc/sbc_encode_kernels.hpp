@@ -49,39 +49,62 @@ __global__ __launch_bounds__(kChunkWords) void k_chunk_summary(
     }
 }
 
-__global__ __launch_bounds__(256) void k_tensor_scan(const TensorDesc* __restrict__ desc,
-                                                     const ChunkSummary* __restrict__ sum,
-                                                     uint32_t* __restrict__ chunk_prev_end,
-                                                     uint64_t* __restrict__ chunk_bitoff,
-                                                     TensorState* __restrict__ st, int b) {
-    __shared__ uint32_t scratch32[4];
-    __shared__ unsigned long long scratch64[4];
+constexpr int kScanThreads = 1024;
+constexpr int kScanPer = 4;              // consecutive chunks per thread and round
+
+__global__ __launch_bounds__(kScanThreads) void k_tensor_scan(const TensorDesc* __restrict__ desc,
+                                                              const ChunkSummary* __restrict__ sum,
+                                                              uint32_t* __restrict__ chunk_prev_end,
+                                                              uint64_t* __restrict__ chunk_bitoff,
+                                                              TensorState* __restrict__ st, int b) {
+    __shared__ uint32_t scratch32[kScanThreads / 64];
+    __shared__ unsigned long long scratch64[kScanThreads / 64];
     const int t = blockIdx.x, tid = threadIdx.x;
     const TensorDesc d = desc[t];
     if (d.flags & kDescFused) return;
     uint32_t carry_end = 0u;             // position+1 of the last kept entry so far (0: none)
     unsigned long long carry_bits = 0ull;
     uint32_t carry_cnt = 0u;
-    for (uint32_t base = 0; base < d.nchunks; base += 256) {
-        const uint32_t cc = base + tid;
-        ChunkSummary s; s.cnt = 0u; s.first = 0u; s.last_end = 0u; s.inner_bits = 0u;
-        if (cc < d.nchunks) s = sum[d.chunk0 + cc];
-        const uint32_t gend = s.cnt ? cc * (uint32_t)kChunk + s.last_end : 0u;
+    for (uint32_t base = 0; base < d.nchunks; base += kScanThreads * kScanPer) {
+        const uint32_t c0 = base + (uint32_t)tid * kScanPer;
+        ChunkSummary s[kScanPer];
+        uint32_t gend[kScanPer], my_end = 0u, my_cnt = 0u;
+#pragma unroll
+        for (int j = 0; j < kScanPer; ++j) {
+            s[j].cnt = 0u; s[j].first = 0u; s[j].last_end = 0u; s[j].inner_bits = 0u;
+            if (c0 + j < d.nchunks) s[j] = sum[d.chunk0 + c0 + j];
+            gend[j] = s[j].cnt ? (c0 + j) * (uint32_t)kChunk + s[j].last_end : 0u;
+            if (gend[j] > my_end) my_end = gend[j];
+            my_cnt += s[j].cnt;
+        }
         uint32_t tile_end;
-        uint32_t pe = block_excl_max<uint32_t, 256>(gend, &tile_end, scratch32);
+        uint32_t pe = block_excl_max<uint32_t, kScanThreads>(my_end, &tile_end, scratch32);
         if (carry_end > pe) pe = carry_end;
-        unsigned long long bits = 0ull;
-        if (s.cnt) {
-            const uint32_t gap = cc * (uint32_t)kChunk + s.first - pe;
-            bits = (unsigned long long)s.inner_bits + (unsigned long long)(gap >> b) + 1ull + (unsigned long long)b;
+        // predecessor end and code bits of every chunk's first kept entry
+        uint32_t pes[kScanPer];
+        unsigned long long bits[kScanPer], my_bits = 0ull;
+#pragma unroll
+        for (int j = 0; j < kScanPer; ++j) {
+            pes[j] = pe;
+            bits[j] = 0ull;
+            if (s[j].cnt) {
+                const uint32_t gap = (c0 + j) * (uint32_t)kChunk + s[j].first - pe;
+                bits[j] = (unsigned long long)s[j].inner_bits + (unsigned long long)(gap >> b) + 1ull + (unsigned long long)b;
+                pe = gend[j];
+            }
+            my_bits += bits[j];
         }
         unsigned long long tile_bits;
-        const unsigned long long off = block_excl_sum<unsigned long long, 256>(bits, &tile_bits, scratch64);
+        unsigned long long off = carry_bits + block_excl_sum<unsigned long long, kScanThreads>(my_bits, &tile_bits, scratch64);
         uint32_t tile_cnt;
-        (void)block_excl_sum<uint32_t, 256>(s.cnt, &tile_cnt, scratch32);
-        if (cc < d.nchunks) {
-            chunk_prev_end[d.chunk0 + cc] = pe;
-            chunk_bitoff[d.chunk0 + cc] = carry_bits + off;
+        (void)block_excl_sum<uint32_t, kScanThreads>(my_cnt, &tile_cnt, scratch32);
+#pragma unroll
+        for (int j = 0; j < kScanPer; ++j) {
+            if (c0 + j < d.nchunks) {
+                chunk_prev_end[d.chunk0 + c0 + j] = pes[j];
+                chunk_bitoff[d.chunk0 + c0 + j] = off;
+            }
+            off += bits[j];
         }
         if (tile_end > carry_end) carry_end = tile_end;
         carry_bits += tile_bits;

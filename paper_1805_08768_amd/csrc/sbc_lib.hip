@@ -58,6 +58,20 @@ struct sbc_ctx {
     uint64_t slot_clock = 0;
     uint64_t cache_total = 0, cache_chunks = 0, cache_stage_words = 0, cache_kept_total = 0, cache_max_bound = 0;
     bool cache_any_bitmap = false;
+    // long streams decoded tile by tile
+    static constexpr int kMaxWideDec = 16;
+    int n_dec_wide = 0;
+    uint32_t dec_tiles = 0;
+    double dec_p = 0.0;
+    uint64_t dec_seg_cap = 0, dec_tile_cap = 0;
+    DecWide* d_dec_wide = nullptr;
+    DecWide* h_dec_wide = nullptr;
+    unsigned long long* d_seg_fn = nullptr;
+    unsigned long long* d_seg_pack = nullptr;
+    unsigned long long* d_tile_fn = nullptr;
+    unsigned long long* d_tile_sum = nullptr;
+    unsigned long long* d_tile_off = nullptr;
+    uint32_t* d_tile_entry = nullptr;
     // grid-wide selection
     uint32_t wide_min_kept = kWideMinKept;
     int n_wide = 0;
@@ -167,6 +181,9 @@ void free_all(sbc_ctx* c) {
     (void)hipFree(c->d_state); (void)hipFree(c->d_cand); (void)hipFree(c->d_bitmap); (void)hipFree(c->d_stage);
     (void)hipFree(c->d_kept); (void)hipFree(c->d_sum); (void)hipFree(c->d_prev_end); (void)hipFree(c->d_bitoff);
     (void)hipFree(c->d_result); (void)hipFree(c->d_dec);
+    (void)hipFree(c->d_dec_wide); (void)hipFree(c->d_seg_fn); (void)hipFree(c->d_seg_pack); (void)hipFree(c->d_tile_fn);
+    (void)hipFree(c->d_tile_sum); (void)hipFree(c->d_tile_off); (void)hipFree(c->d_tile_entry);
+    if (c->h_dec_wide) (void)hipHostFree(c->h_dec_wide);
     (void)hipFree(c->d_wide_ids); (void)hipFree(c->d_wide_state); (void)hipFree(c->d_wide_hist);
     (void)hipFree(c->d_wide_acc); (void)hipFree(c->d_wide_tie);
     if (c->h_wide_ids) (void)hipHostFree(c->h_wide_ids);
@@ -268,6 +285,17 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     ok = ok && dev_alloc(&c->d_bitoff, (size_t)c->max_chunks) == hipSuccess;
     ok = ok && dev_alloc(&c->d_result, 4) == hipSuccess;      // two for compress, two for decode, used in turn
     ok = ok && dev_alloc(&c->d_dec, T) == hipSuccess;
+    // tile decode: a stream of w words has w/2 segments; every stream is rounded up to whole tiles
+    c->dec_seg_cap = c->stage_cap / 2 + (uint64_t)(sbc_ctx::kMaxWideDec + 1) * kDecThreads;
+    c->dec_tile_cap = c->dec_seg_cap / kDecThreads + sbc_ctx::kMaxWideDec;
+    ok = ok && dev_alloc(&c->d_dec_wide, (size_t)sbc_ctx::kMaxWideDec) == hipSuccess;
+    ok = ok && host_alloc(&c->h_dec_wide, (size_t)sbc_ctx::kMaxWideDec) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_seg_fn, (size_t)c->dec_seg_cap) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_seg_pack, (size_t)c->dec_seg_cap) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_tile_fn, (size_t)c->dec_tile_cap) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_tile_sum, (size_t)c->dec_tile_cap) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_tile_off, (size_t)c->dec_tile_cap * 3) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_tile_entry, (size_t)c->dec_tile_cap) == hipSuccess;
     ok = ok && dev_alloc(&c->d_wide_ids, (size_t)kMaxWide) == hipSuccess;
     ok = ok && dev_alloc(&c->d_wide_state, (size_t)kMaxWide) == hipSuccess;
     ok = ok && dev_alloc(&c->d_wide_hist, (size_t)kMaxWide * 2 * kWindow) == hipSuccess;
@@ -501,7 +529,7 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
         if (any_bitmap) {
             SBC_LAUNCH(kStChunkSummary, profile, k_chunk_summary, dim3(n_chunks), dim3(kChunkWords), d_desc,
                        c->d_chunk_tensor, c->d_bitmap, c->d_sum, b);
-            SBC_LAUNCH(kStTensorScan, profile, k_tensor_scan, dim3(T), dim3(256), d_desc, c->d_sum, c->d_prev_end,
+            SBC_LAUNCH(kStTensorScan, profile, k_tensor_scan, dim3(T), dim3(kScanThreads), d_desc, c->d_sum, c->d_prev_end,
                        c->d_bitoff, c->d_state, b);
             SBC_LAUNCH(kStPack, profile, k_pack, dim3(n_chunks), dim3(kChunkWords), d_desc, c->d_chunk_tensor,
                        c->d_bitmap, c->d_sum, c->d_prev_end, c->d_bitoff, b, c->d_stage, res_now);
@@ -638,7 +666,7 @@ int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, siz
     if (b > kMaxB) return SBC_EINVAL;
     SBC_HOST_TS(8);
     if (msg_bytes < 32 + 24ull * (unsigned)T) return SBC_ECORRUPT;
-    bool same = c->dev_dec_valid && c->dev_dec_T == T;
+    bool same = c->dev_dec_valid && c->dev_dec_T == T && c->dec_p == p;
     for (int t = 0; t < T; ++t) {
         if (numel[t] < 1 || numel[t] >= (int64_t)1 << 32 || !out[t] || ((uintptr_t)out[t] & 3u)) return SBC_EINVAL;
         if (same && (c->h_dec[t].out != out[t] || c->h_dec[t].n != (uint32_t)numel[t])) same = false;
@@ -646,9 +674,28 @@ int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, siz
     DeviceGuard guard(c->device);
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     if (!same) {
-        for (int t = 0; t < T; ++t) { c->h_dec[t].out = out[t]; c->h_dec[t].n = (uint32_t)numel[t]; c->h_dec[t].pad = 0; }
+        // Streams of tensors that keep very many entries are decoded tile by tile by many
+        // workgroups, as far as the scratch arrays reach; all others by one workgroup each.
+        int n_wide = 0;
+        uint64_t segs = 0, tiles = 0;
+        for (int t = 0; t < T; ++t) {
+            c->h_dec[t].out = out[t]; c->h_dec[t].n = (uint32_t)numel[t]; c->h_dec[t].wide = 0u;
+            const int64_t k = kept_of(numel[t], p);
+            if (b > kPackedMaxB || (uint64_t)k < (uint64_t)c->wide_min_kept || n_wide >= sbc_ctx::kMaxWideDec) continue;
+            const uint64_t max_seg = (bound_words_of(numel[t], (uint32_t)k, b) + 1) / 2;
+            const uint64_t max_tiles = (max_seg + kDecThreads - 1) / kDecThreads;
+            if (max_tiles == 0 || max_tiles >= (1ull << 31) || segs + max_tiles * kDecThreads > c->dec_seg_cap ||
+                tiles + max_tiles > c->dec_tile_cap)
+                continue;
+            DecWide& w = c->h_dec_wide[n_wide++];
+            w.t = (uint32_t)t; w.tile0 = (uint32_t)tiles; w.max_tiles = (uint32_t)max_tiles; w.pad = 0u; w.seg0 = segs;
+            c->h_dec[t].wide = 1u;
+            segs += max_tiles * kDecThreads; tiles += max_tiles;
+        }
+        c->n_dec_wide = n_wide; c->dec_tiles = (uint32_t)tiles; c->dec_p = p;
         c->dev_dec_valid = false;
-        if (hipMemcpyAsync(c->d_dec, c->h_dec, sizeof(DecDesc) * T, hipMemcpyHostToDevice, stream) != hipSuccess) {
+        if (hipMemcpyAsync(c->d_dec, c->h_dec, sizeof(DecDesc) * T, hipMemcpyHostToDevice, stream) != hipSuccess ||
+            (n_wide > 0 && hipMemcpyAsync(c->d_dec_wide, c->h_dec_wide, sizeof(DecWide) * n_wide, hipMemcpyHostToDevice, stream) != hipSuccess)) {
             (void)hipGetLastError();
             return SBC_EHIP;
         }
@@ -667,6 +714,22 @@ int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, siz
     hipLaunchKernelGGL(k_decode_accumulate, dim3(T), dim3(kDecThreads), 0, stream,
                        static_cast<const uint8_t*>(msg), (unsigned long long)msg_bytes, c->d_dec, T, b, scale,
                        res_dec, res_dec_next);
+    if (c->n_dec_wide > 0) {
+        const uint8_t* m8 = static_cast<const uint8_t*>(msg);
+        const unsigned long long mb = (unsigned long long)msg_bytes;
+        const dim3 tiles(c->dec_tiles), streams((unsigned)c->n_dec_wide);
+        hipLaunchKernelGGL(k_dec_tile_fn, tiles, dim3(kDecThreads), 0, stream, m8, mb, c->d_dec, c->d_dec_wide,
+                           c->n_dec_wide, T, b, c->d_seg_fn, c->d_tile_fn, res_dec);
+        hipLaunchKernelGGL(k_dec_tile_entry, streams, dim3(1024), 0, stream, m8, mb, c->d_dec, c->d_dec_wide, T, b,
+                           c->d_tile_fn, c->d_tile_entry);
+        hipLaunchKernelGGL(k_dec_tile_sums, tiles, dim3(kDecThreads), 0, stream, m8, mb, c->d_dec, c->d_dec_wide,
+                           c->n_dec_wide, T, b, c->d_seg_fn, c->d_tile_entry, c->d_seg_pack, c->d_tile_sum, res_dec);
+        hipLaunchKernelGGL(k_dec_tile_offsets, streams, dim3(1024), 0, stream, m8, mb, c->d_dec, c->d_dec_wide, T, b,
+                           c->d_tile_sum, c->d_tile_off, res_dec);
+        hipLaunchKernelGGL(k_dec_tile_place, tiles, dim3(kDecThreads), 0, stream, m8, mb, c->d_dec, c->d_dec_wide,
+                           c->n_dec_wide, T, b, scale, c->d_seg_fn, c->d_tile_entry, c->d_seg_pack, c->d_tile_off,
+                           res_dec);
+    }
     SBC_HOST_TS(10);
     if (hipGetLastError() != hipSuccess) return SBC_EHIP;
     if (hipMemcpyAsync(c->h_result, res_dec, sizeof(ResultBlock), hipMemcpyDeviceToHost, stream) != hipSuccess ||

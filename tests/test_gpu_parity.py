@@ -350,10 +350,13 @@ def test_same_input_twice_gives_identical_bytes():
     assert outs[0] == outs[1] == outs[2]
 
 
-def test_error_paths():
+@pytest.mark.parametrize("tiled_decode", [False, True])
+def test_error_paths(tiled_decode):
     sizes = [5000, 64]
     dWs = synth.small_model_update(sizes)
     with DeviceRun(sizes) as run:
+        if tiled_decode:       # tensor 0 goes through the grid-wide selection and the tile decoder
+            sbc.sbc_set_option(run.ctx, sbc.SBC_OPT_WIDE_MIN_KEPT, 10)
         d_dW = [torch.from_numpy(x).cuda() for x in dWs]
         bound = sbc.sbc_msg_bound(sizes, 0.01)
         msg = torch.zeros(bound, dtype=torch.uint8, device="cuda:0")
