@@ -70,7 +70,8 @@ typedef struct sbc_ctx sbc_ctx;
 
 /* Scratch memory for problems of up to max_total_elems entries in up to max_tensors
  * tensors per call, on HIP device `device`.  Device memory taken: about
- * 16.3 bytes per entry of max_total_elems plus 5 KiB per tensor.  *out receives the
+ * 17 bytes per entry of max_total_elems plus 50 KiB per tensor, and 2.4 MiB whatever
+ * the sizes.  The context also owns a few HIP events.  *out receives the
  * context.  SBC_EINVAL for non-positive sizes or a bad device, SBC_EHIP if an
  * allocation fails (nothing is leaked). */
 int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tensors);
