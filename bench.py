@@ -44,6 +44,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--breakdown", action="store_true", help="also print per-kernel times to stderr")
+    ap.add_argument("--carry-keys", action="store_true",
+                    help="set SBC_OPT_CARRY_FILTER_KEYS (filter keys from the previous round instead of sampling)")
     ap.add_argument("--workload", default="resnet50", choices=["resnet50", "lstm", "gauss2p20", "student4m", "flat1p5e9"],
                     help="resnet50 (default) is the benchmark workload; the others are reported for reference")
     args = ap.parse_args()
@@ -105,6 +107,8 @@ def main() -> int:
     bound = sbc.sbc_msg_bound(sizes, P)
     msg = torch.zeros(bound, dtype=torch.uint8, device=dev)
     ctx = sbc.sbc_create(0, N, T)
+    if args.carry_keys:
+        sbc.sbc_set_option(ctx, sbc.SBC_OPT_CARRY_FILTER_KEYS, 1)
     scale = 1.0 / 32.0
 
     def step(i):
