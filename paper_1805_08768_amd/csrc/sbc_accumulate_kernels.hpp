@@ -53,7 +53,7 @@ __device__ __forceinline__ uint32_t mix32(uint32_t x) {
 // bits); larger ones contribute 256 runs of 64 consecutive entries, one run at a pseudo-random
 // place in each of 256 equal strata.  With m sampled entries out of n, lambda = k*m/n of them
 // are expected among the tensor's k most extreme; the filter key is the lower edge of the
-// 16-bit key bucket holding the sample's r-th most extreme entry, r = lambda + 5*sqrt(lambda)
+// 16-bit key bucket holding the sample's r-th most extreme entry, r = lambda + 4*sqrt(lambda)
 // + 3, so that the chance of cutting into the true top k is negligible (and harmless: the
 // histogram path then redoes the tensor).  Both sides are selected together, the negative side
 // on complemented keys.  The kernel also clears the per-tensor state and the result block.
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
     uint32_t rs = d.k;
     if (n > (uint32_t)kSampleMax) {
         const double lambda = (double)d.k * (double)m / (double)n;
-        rs = (uint32_t)ceil(lambda + 5.0 * sqrt(lambda) + 3.0);
+        rs = (uint32_t)ceil(lambda + 4.0 * sqrt(lambda) + 3.0);
     }
     if (rs >= m) return;                              // keep the all-pass keys (0, 0)
 
@@ -250,6 +250,10 @@ __device__ __forceinline__ void filter_entry(float a, uint32_t idx, uint32_t lo_
     }
 }
 
+// STREAM: the update is loaded with the nontemporal hint.  It is read exactly once, and when a
+// call's footprint is well beyond the last-level cache, keeping it out of that cache leaves more
+// of it to the residual, which is read and written.
+template <bool STREAM>
 __global__ __launch_bounds__(kStreamThreads) void k_accumulate_filter(
         const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ chunk_tensor,
         TensorState* __restrict__ st, uint2* __restrict__ cand, uint32_t* __restrict__ bitmap,
@@ -285,7 +289,7 @@ __global__ __launch_bounds__(kStreamThreads) void k_accumulate_filter(
         f32x4 dv[IT], rv[IT];
 #pragma unroll
         for (int i = 0; i < IT; ++i) {
-            dv[i] = dw4[i * kStreamThreads + tid];
+            dv[i] = STREAM ? __builtin_nontemporal_load(&dw4[i * kStreamThreads + tid]) : dw4[i * kStreamThreads + tid];
             rv[i] = r4[i * kStreamThreads + tid];
         }
 #pragma unroll

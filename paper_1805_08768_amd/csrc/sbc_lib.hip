@@ -561,8 +561,15 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
         SBC_LAUNCH(kStSample, true, k_sample_thresholds, dim3(T), dim3(kSampleThreads), d_desc, c->d_state,
                    res_now, c->force_exact);
     }
-    SBC_LAUNCH(kStAccumulate, true, k_accumulate_filter, dim3(n_chunks), dim3(kStreamThreads), d_desc,
-               c->d_chunk_tensor, c->d_state, c->d_cand, c->d_bitmap, c->d_stage, res_now);
+    // 12 bytes per entry pass through; beyond about twice the 256 MiB last-level cache the update
+    // is loaded with the nontemporal hint
+    if (total * 12ull > (512ull << 20)) {
+        SBC_LAUNCH(kStAccumulate, true, k_accumulate_filter<true>, dim3(n_chunks), dim3(kStreamThreads), d_desc,
+                   c->d_chunk_tensor, c->d_state, c->d_cand, c->d_bitmap, c->d_stage, res_now);
+    } else {
+        SBC_LAUNCH(kStAccumulate, true, k_accumulate_filter<false>, dim3(n_chunks), dim3(kStreamThreads), d_desc,
+                   c->d_chunk_tensor, c->d_state, c->d_cand, c->d_bitmap, c->d_stage, res_now);
+    }
     if (c->n_wide > 0) {
         // tensors that keep very many entries: Alg. 2 as grid-wide sweeps over their candidate lists
         const dim3 sweep(c->wide_blocks, (unsigned)c->n_wide), one((unsigned)c->n_wide);

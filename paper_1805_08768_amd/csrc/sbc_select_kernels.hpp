@@ -50,15 +50,15 @@ __device__ __forceinline__ void put_ones(uint32_t* words, unsigned long long pos
 
 constexpr uint32_t kSelLds = 8192;                       // candidates per side staged in LDS
 constexpr int kWindow = 2048;                            // bins of the leading-bits histogram
-constexpr int kWinShift = 13;                            // it counts key >> kWinShift: 2^10 steps per octave, two octaves
-constexpr uint32_t kRankMax = 256;                       // threshold buckets up to this size are ranked directly
+constexpr int kWinShift = 11;                            // it counts key >> kWinShift: 2^12 steps per octave, half an octave
+constexpr uint32_t kRankMax = 512;                       // threshold buckets up to this size are ranked directly
 static_assert(2 * kFusedMaxK * 4 <= kSelLds * 8, "sort arrays reuse one side's candidate space");
 static_assert(kFusedMaxWords <= kFusedMaxK, "stream words reuse the grouping array");
 
 struct SelectShared {
     uint2 cand[2][kSelLds];                              // both sides' lists when they fit
     union {
-        uint32_t whist[2][kWindow];                     // leading 19 key bits, as an offset from the filter key
+        uint32_t whist[2][kWindow];                     // leading 21 key bits, as an offset from the filter key
         struct {
             uint32_t hist[4][2][256];                    // byte histograms: [pass][side][byte]
             long long acc[2][256];                       // per-exponent integer sums
@@ -224,7 +224,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     list.g[1] = cand + d.cand_off + n; list.cnt[1] = cnt_n;
     list.staged = cnt_p <= kSelLds && cnt_n <= kSelLds;
 
-    // Leading 19 key bits of the k-th most extreme entry of each side.  Every candidate's key is at
+    // Leading 21 key bits of the k-th most extreme entry of each side.  Every candidate's key is at
     // or above the side's filter key, and the k-th lies close above it, so a window of kWindow
     // values of (key >> kWinShift) starting at the filter key's is histogrammed in the same sweep
     // that stages the lists in LDS; the top bin collects everything beyond the window.
@@ -292,12 +292,20 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
             const uint32_t M = m > 1u ? 1u << (32 - __clz((int)(m - 1u))) : 1u;
             const uint32_t parts = (uint32_t)kSelThreads / M, i = (uint32_t)tid & (M - 1u), part = (uint32_t)tid / M;
             if (i < m) {
-                const uint2 me = sh.bucket[sd][i];
+                // one 64-bit comparison per pair: key descending, then index ascending
+                const uint2 me2 = sh.bucket[sd][i];
+                const unsigned long long me = ((unsigned long long)me2.x << 32) | (uint32_t)~me2.y;
                 uint32_t ahead = 0u;
-#pragma unroll 8
-                for (uint32_t j = part; j < m; j += parts) {
-                    const uint2 o = sh.bucket[sd][j];
-                    ahead += (o.x > me.x || (o.x == me.x && o.y < me.y)) ? 1u : 0u;
+                // this thread's share of the others: a contiguous range, eight LDS reads in flight
+                const uint32_t len = (m + parts - 1u) / parts;
+                const uint32_t j_end = min(m, (part + 1u) * len);
+                for (uint32_t j0 = part * len; j0 < j_end; j0 += 8u) {
+                    uint2 o[8];
+#pragma unroll
+                    for (uint32_t u = 0; u < 8u; ++u) o[u] = sh.bucket[sd][min(j0 + u, kRankMax - 1u)];
+#pragma unroll
+                    for (uint32_t u = 0; u < 8u; ++u)
+                        ahead += (j0 + u < j_end && (((unsigned long long)o[u].x << 32) | (uint32_t)~o[u].y) > me) ? 1u : 0u;
                 }
                 if (ahead) atomicAdd(&sh.ahead[sd][i], ahead);
             }

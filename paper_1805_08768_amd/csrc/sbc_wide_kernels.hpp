@@ -4,8 +4,8 @@
 // over the tensor's two candidate lists with a one-workgroup step in between.
 //
 //   k_wide_count (pass 0,1,2)  histogram of the next key digit over the entries that match the
-//                              digits fixed so far: 19 leading bits in a window above the filter
-//                              key, then 8 bits, then the last 5
+//                              digits fixed so far: 21 leading bits in a window above the filter
+//                              key, then 8 bits, then the last 3
 //   k_wide_pick  (pass 0,1,2)  the digit that holds the k-th entry of each side; after pass 2 the
 //                              threshold key tau, the number of entries equal to it and how many
 //                              of those are kept
@@ -26,6 +26,8 @@ namespace sbc {
 
 constexpr int kWideThreads = 256;        // sweep kernels
 constexpr uint32_t kWideTieMax = 1024;   // tied entries whose indices can be ranked
+constexpr int kWideLastBits = kWinShift - 8;   // key bits left for the third pass (the second takes 8)
+static_assert(kWideLastBits >= 1 && kWideLastBits <= 11, "the last two digits fit the histogram");
 
 struct WideState {
     uint32_t ok;          // 1 while every step so far applied
@@ -65,9 +67,9 @@ __global__ __launch_bounds__(kWideThreads) void k_wide_count(
                 const uint32_t o = v >= base ? v - base : 0u;
                 atomicAdd(&hist[s][o < (uint32_t)(kWindow - 1) ? o : (uint32_t)(kWindow - 1)], 1u);
             } else if (pass == 1) {
-                if ((key >> kWinShift) == prefix) atomicAdd(&hist[s][(key >> 5) & 255u], 1u);
+                if ((key >> kWinShift) == prefix) atomicAdd(&hist[s][(key >> kWideLastBits) & 255u], 1u);
             } else {
-                if ((key >> 5) == prefix) atomicAdd(&hist[s][key & 31u], 1u);
+                if ((key >> kWideLastBits) == prefix) atomicAdd(&hist[s][key & ((1u << kWideLastBits) - 1u)], 1u);
             }
         }
     }
@@ -121,7 +123,7 @@ __global__ __launch_bounds__(kSelThreads) void k_wide_pick(
                 for (int s = 0; s < 2; ++s) ws[w].prefix[s] = (st[t].lo_key[s] >> kWinShift) + digit[s];
             }
         } else if (ok) {
-            const int bits = pass == 1 ? 8 : 5;
+            const int bits = pass == 1 ? 8 : kWideLastBits;
 #pragma unroll
             for (int s = 0; s < 2; ++s) ws[w].prefix[s] = (ws[w].prefix[s] << bits) | digit[s];
         }
