@@ -55,7 +55,7 @@ def main() -> int:
         return 2
 
     import torch
-    from paper_1805_08768_amd import binding as sbc, synth
+    from paper_1805_08768_amd import accounting, binding as sbc, synth
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -164,8 +164,10 @@ def main() -> int:
     ev1.record()
     torch.cuda.synchronize()
     copy_gbs = 2 * 4 * N * 10 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
-    bits = sum(sbc.sbc_last_tensor_stats(ctx, t)[4] for t in range(T))
+    stats = [sbc.sbc_last_tensor_stats(ctx, t) for t in range(T)]
+    bits = sum(s[4] for s in stats)
     ratio = 32.0 * N / (bits + 32.0 * T)
+    bit_accounting = accounting.message_bits(sizes, [s[3] for s in stats], [s[4] for s in stats])
     if args.breakdown:
         print("per-kernel us (event-bracketed):", breakdown, file=sys.stderr)
 
@@ -220,6 +222,8 @@ def main() -> int:
                    "histogram_fallback": sum(v for k, v in routes.items() if k & 2),
                    "grid_wide_selection": sum(v for k, v in routes.items() if k & 4)},
         "compression_ratio_paper_accounting": ratio,
+        "bit_accounting": {k: round(v, 3) for k, v in bit_accounting.items() if k.startswith("gain_")
+                           or k == "position_bits_per_kept_entry"},
     }
     print(json.dumps(line))
     return 0

@@ -7,8 +7,10 @@
 //     tau and the highest index kept among entries equal to tau (equal values go to the lowest
 //     index).  Tie-heavy data falls back to a byte-wise radix select (four passes) for tau and
 //     a second one over the tied indices;
-//   * S, the sum of the k kept values of a side, is accumulated as exact integers per fp32
-//     exponent (independent of the order of the list) and combined in a fixed order in fp64.
+//   * S, the sum of the k kept values of a side, is accumulated as exact integers (mantissas
+//     shifted to the threshold's scale in one 64-bit integer, or one integer per fp32 exponent
+//     where that does not apply), so it does not depend on the order of the list, and is
+//     rounded to fp64 in a fixed order.
 // It then decides the side (positive iff mu+ >= mu-, which for equal counts is S+ >= S-)
 // and applies it:
 //   * residual update R[j] = A[j] - mu_signed at the k kept entries;
