@@ -142,7 +142,7 @@ int sbc_decompress_accumulate(sbc_ctx* ctx, void* hip_stream,
  *       are unchanged (successive rounds of one training run) and skips the sampling kernel;
  *       it pays off when the thresholds move by less than a few percent from round to round,
  *       and costs time when they move more (a flood of candidates, then a sampled round).
- *   SBC_OPT_WIDE_MIN_KEPT      (default 0 = 65536)  a tensor that keeps at least this many entries
+ *   SBC_OPT_WIDE_MIN_KEPT      (default 0 = 8192)  a tensor that keeps at least this many entries
  *       per side is selected by grid-wide kernels instead of one workgroup (a 1.5e9-entry tensor
  *       at p = 0.001 keeps 1.5e6); tests lower it to send small tensors that way. */
 enum { SBC_OPT_FORCE_EXACT_PATH = 1, SBC_OPT_CARRY_FILTER_KEYS = 2, SBC_OPT_WIDE_MIN_KEPT = 3 };

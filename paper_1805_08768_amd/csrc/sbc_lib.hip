@@ -33,7 +33,7 @@ const char* const kStageNames[kNumStages] = {
 
 constexpr int kDescSlots = 4;
 constexpr int kMaxWide = 64;             // tensors per call that the grid-wide selection kernels can take
-constexpr uint32_t kWideMinKept = 65536; // ... and how many entries a tensor must keep to be given to them
+constexpr uint32_t kWideMinKept = 8192;  // ... and how many entries a tensor must keep to be given to them
 struct DescSlot {
     bool valid = false;
     uint64_t stamp = 0;

@@ -488,3 +488,17 @@ def test_grid_wide_selection():
         sbc.sbc_set_option(run.ctx, sbc.SBC_OPT_WIDE_MIN_KEPT, 6500)
         dWs = [synth.palette_update(n, tensor=i) for i, n in enumerate(sizes)]
         check_round(run, dWs, [np.zeros(n, np.float32) for n in sizes], p)
+
+
+def test_tensor_of_many_chunks():
+    """A tensor of more than 1024 chunks (several rounds of every per-tensor scan over chunks),
+    plain and tie-heavy (LDS queues overflow, chunks are read a second time)."""
+    n = 8192 * 1100 + 5
+    with DeviceRun([n, 70000]) as run:
+        R = [np.zeros(n, np.float32), np.zeros(70000, np.float32)]
+        for r in range(2):
+            dWs = [synth.gaussian_update(n, round_=r), synth.gaussian_update(70000, round_=r, tensor=1)]
+            res = check_round(run, dWs, R, 0.001, check_decode=(r == 0))
+            R = [x.R_new for x in res]
+        dWs = [synth.palette_update(n), synth.palette_update(70000, tensor=1)]
+        check_round(run, dWs, R, 0.001, check_decode=False)
