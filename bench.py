@@ -105,15 +105,16 @@ def main() -> int:
     R = sbc.TensorList(views(flat_R))
     out = sbc.TensorList(views(flat_out))
     bound = sbc.sbc_msg_bound(sizes, P)
-    msg = torch.zeros(bound, dtype=torch.uint8, device=dev)
+    msg = sbc.MessageBuffer(torch.zeros(bound, dtype=torch.uint8, device=dev))
+    stream = torch.cuda.current_stream().cuda_stream      # raw handle, looked up once
     ctx = sbc.sbc_create(0, N, T)
     if args.carry_keys:
         sbc.sbc_set_option(ctx, sbc.SBC_OPT_CARRY_FILTER_KEYS, 1)
     scale = 1.0 / 32.0
 
     def step(i):
-        nbytes = sbc.sbc_compress(ctx, dW_sets[i % n_sets], R, P, msg)
-        sbc.sbc_decompress_accumulate(ctx, msg, nbytes, P, scale, out)
+        nbytes = sbc.sbc_compress(ctx, dW_sets[i % n_sets], R, P, msg, stream)
+        sbc.sbc_decompress_accumulate(ctx, msg, nbytes, P, scale, out, stream)
         return nbytes
 
     for i in range(args.warmup):
@@ -132,9 +133,9 @@ def main() -> int:
     for i in range(args.steps):
         sbc.sbc_profile_level(ctx, 1 if i % PROFILE_EVERY == 0 else 0)
         ta = time.perf_counter()
-        nbytes = sbc.sbc_compress(ctx, dW_sets[(args.warmup + i) % n_sets], R, P, msg)
+        nbytes = sbc.sbc_compress(ctx, dW_sets[(args.warmup + i) % n_sets], R, P, msg, stream)
         t_compress += time.perf_counter() - ta
-        sbc.sbc_decompress_accumulate(ctx, msg, nbytes, P, scale, out)
+        sbc.sbc_decompress_accumulate(ctx, msg, nbytes, P, scale, out, stream)
         msg_bytes += nbytes
         rt = sbc.sbc_last_route(ctx)
         routes[rt] = routes.get(rt, 0) + 1
@@ -150,7 +151,7 @@ def main() -> int:
     # untimed extras: per-kernel breakdown, copy yardstick, paper-accounted compression ratio
     sbc.sbc_profile_enable(ctx, 2)
     for i in range(10):
-        sbc.sbc_compress(ctx, dW_sets[i % n_sets], R, P, msg)
+        sbc.sbc_compress(ctx, dW_sets[i % n_sets], R, P, msg, stream)
     breakdown = {name: round(ms / max(1, calls) * 1e3, 2) for name, ms, calls in sbc.sbc_profile_read(ctx)}
     sbc.sbc_profile_enable(ctx, 0)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -124,6 +124,7 @@ class TensorList:
         self.tensors = list(tensors)
         self.ptrs = _ptr_array(self.tensors, torch.float32)
         self.numel = [t.numel() for t in self.tensors]
+        self.numel_key = tuple(self.numel)
         self.numel_arr = _i64_array(self.numel)
 
     def __len__(self):
@@ -135,9 +136,27 @@ def _as_list(x) -> "TensorList":
 
 
 def _stream_handle(stream) -> Optional[int]:
+    """stream: None (torch's current stream), a torch stream, or a raw hipStream_t as an int."""
     if stream is None:
         stream = torch.cuda.current_stream()
     return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+class MessageBuffer:
+    """A contiguous uint8 device tensor checked and marshalled once, for callers that reuse one
+    message buffer call after call.  Keeps the tensor alive."""
+
+    def __init__(self, tensor: torch.Tensor):
+        _check_device(tensor)
+        if tensor.dtype != torch.uint8 or not tensor.is_contiguous():
+            raise ValueError("msg must be a contiguous uint8 tensor")
+        self.tensor = tensor
+        self.ptr = ctypes.c_void_p(tensor.data_ptr())
+        self.capacity = tensor.numel()
+
+
+def _as_msg(x) -> "MessageBuffer":
+    return x if isinstance(x, MessageBuffer) else MessageBuffer(x)
 
 
 # ------------------------------------------------------------------ scalars
@@ -177,15 +196,12 @@ def sbc_compress(ctx, dW, residual, p: float,
     """Runs the client step on the given fp32 device tensors (lists of tensors or TensorList);
     returns the message size in bytes.  `residual` is updated in place, `msg` (uint8 device
     tensor) receives the message."""
-    dW, residual = _as_list(dW), _as_list(residual)
-    if dW.numel != residual.numel:
+    dW, residual, msg = _as_list(dW), _as_list(residual), _as_msg(msg)
+    if dW.numel_key != residual.numel_key:
         raise ValueError("dW and residual must list tensors of the same sizes")
-    _check_device(msg)
-    if msg.dtype != torch.uint8 or not msg.is_contiguous():
-        raise ValueError("msg must be a contiguous uint8 tensor")
     out_bytes = ctypes.c_size_t(0)
-    rc = load().sbc_compress(ctx, _stream_handle(stream), dW.ptrs, residual.ptrs, dW.numel_arr, len(dW),
-                             float(p), ctypes.c_void_p(msg.data_ptr()), msg.numel(), ctypes.byref(out_bytes))
+    rc = load().sbc_compress(ctx, _stream_handle(stream), dW.ptrs, residual.ptrs, dW.numel_arr, len(dW.tensors),
+                             p, msg.ptr, msg.capacity, ctypes.byref(out_bytes))
     if rc != SBC_OK:
         raise SbcError(rc, "sbc_compress")
     return int(out_bytes.value)
@@ -194,13 +210,12 @@ def sbc_compress(ctx, dW, residual, p: float,
 def sbc_decompress_accumulate(ctx, msg: torch.Tensor, msg_bytes: int, p: float, scale: float,
                               out, stream=None) -> None:
     """Adds scale * (decoded sparse binary update) of one client message into `out`."""
-    _check_device(msg)
-    if msg.dtype != torch.uint8 or not msg.is_contiguous() or msg_bytes > msg.numel():
+    msg = _as_msg(msg)
+    if msg_bytes > msg.capacity:
         raise ValueError("msg must be a contiguous uint8 tensor holding msg_bytes bytes")
     out = _as_list(out)
-    rc = load().sbc_decompress_accumulate(ctx, _stream_handle(stream), ctypes.c_void_p(msg.data_ptr()),
-                                          int(msg_bytes), out.numel_arr, len(out), float(p),
-                                          ctypes.c_float(scale), out.ptrs)
+    rc = load().sbc_decompress_accumulate(ctx, _stream_handle(stream), msg.ptr, msg_bytes, out.numel_arr,
+                                          len(out.tensors), p, scale, out.ptrs)
     if rc != SBC_OK:
         raise SbcError(rc, "sbc_decompress_accumulate")
 
