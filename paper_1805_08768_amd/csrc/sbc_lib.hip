@@ -31,9 +31,11 @@ const char* const kStageNames[kNumStages] = {
     "k_chunk_summary", "k_tensor_scan", "k_pack", "k_gather"};
 }  // namespace
 
-constexpr int kDescSlots = 4;
-constexpr int kMaxWide = 64;             // tensors per call that the grid-wide selection kernels can take
-constexpr uint32_t kWideMinKept = 8192;  // ... and how many entries a tensor must keep to be given to them
+constexpr int kDescSlots = 4;             // device copies of the tensor table, keyed by the pointer lists
+constexpr int kMaxWide = 64;              // tensors per call that the grid-wide selection kernels can take
+constexpr int kMaxWideDec = 16;           // streams per call that the tile decoder can take
+constexpr uint32_t kWideMinKept = 8192;   // kept entries per side from which a tensor takes those routes
+
 struct DescSlot {
     bool valid = false;
     uint64_t stamp = 0;
@@ -49,39 +51,8 @@ struct sbc_ctx {
     uint64_t kept_cap = 0;
     uint64_t stage_cap = 0;
 
-    // device scratch
-    TensorDesc* d_desc = nullptr;
-    // sizes and totals of the last planned call, and the device copies of the tensor table
-    bool cache_valid = false; int cache_T = 0; double cache_p = 0.0;
-    std::vector<int64_t> cache_numel;
-    DescSlot slot[kDescSlots];
-    uint64_t slot_clock = 0;
-    uint64_t cache_total = 0, cache_chunks = 0, cache_stage_words = 0, cache_kept_total = 0, cache_max_bound = 0;
-    bool cache_any_bitmap = false;
-    // long streams decoded tile by tile
-    static constexpr int kMaxWideDec = 16;
-    int n_dec_wide = 0;
-    uint32_t dec_tiles = 0;
-    double dec_p = 0.0;
-    uint64_t dec_seg_cap = 0, dec_tile_cap = 0;
-    DecWide* d_dec_wide = nullptr;
-    DecWide* h_dec_wide = nullptr;
-    unsigned long long* d_seg_fn = nullptr;
-    unsigned long long* d_seg_pack = nullptr;
-    unsigned long long* d_tile_fn = nullptr;
-    unsigned long long* d_tile_sum = nullptr;
-    unsigned long long* d_tile_off = nullptr;
-    uint32_t* d_tile_entry = nullptr;
-    // grid-wide selection
-    uint32_t wide_min_kept = kWideMinKept;
-    int n_wide = 0;
-    uint32_t wide_blocks = 0;
-    uint32_t* d_wide_ids = nullptr;
-    uint32_t* h_wide_ids = nullptr;
-    WideState* d_wide_state = nullptr;
-    uint32_t* d_wide_hist = nullptr;
-    long long* d_wide_acc = nullptr;
-    uint32_t* d_wide_tie = nullptr;
+    // ---- device scratch of sbc_compress ----
+    TensorDesc* d_desc = nullptr;         // kDescSlots tables of max_tensors entries
     uint32_t* d_chunk_tensor = nullptr;
     uint32_t* d_order = nullptr;
     uint32_t* d_hist = nullptr;
@@ -93,35 +64,71 @@ struct sbc_ctx {
     ChunkSummary* d_sum = nullptr;
     uint32_t* d_prev_end = nullptr;
     uint64_t* d_bitoff = nullptr;
-    ResultBlock* d_result = nullptr;
-    DecDesc* d_dec = nullptr;
+    ResultBlock* d_result = nullptr;      // two for compress, two for decode, used in turn
+    // grid-wide selection
+    uint32_t* d_wide_ids = nullptr;
+    WideState* d_wide_state = nullptr;
+    uint32_t* d_wide_hist = nullptr;
+    long long* d_wide_acc = nullptr;
+    uint32_t* d_wide_tie = nullptr;
 
-    // pinned host staging
+    // ---- device scratch of sbc_decompress_accumulate ----
+    DecDesc* d_dec = nullptr;
+    DecWide* d_dec_wide = nullptr;        // long streams decoded tile by tile
+    unsigned long long* d_seg_fn = nullptr;
+    unsigned long long* d_seg_pack = nullptr;
+    unsigned long long* d_tile_fn = nullptr;
+    unsigned long long* d_tile_sum = nullptr;
+    unsigned long long* d_tile_off = nullptr;
+    uint32_t* d_tile_entry = nullptr;
+    uint64_t dec_seg_cap = 0, dec_tile_cap = 0;
+
+    // ---- pinned host staging ----
     TensorDesc* h_desc = nullptr;
     uint32_t* h_chunk_tensor = nullptr;
     uint32_t* h_order = nullptr;
+    uint32_t* h_wide_ids = nullptr;
     ResultBlock* h_result = nullptr;
     DecDesc* h_dec = nullptr;
+    DecWide* h_dec_wide = nullptr;
     TensorState* h_state = nullptr;
 
-    // what the device tables currently hold
+    // ---- plan of the last compress call: everything that depends on sizes and p only ----
+    bool cache_valid = false; int cache_T = 0; double cache_p = 0.0;
+    std::vector<int64_t> cache_numel;
+    uint64_t cache_total = 0, cache_chunks = 0, cache_stage_words = 0, cache_kept_total = 0, cache_max_bound = 0;
+    bool cache_any_bitmap = false;
+    std::vector<TensorDesc> plan;         // without the pointers
+    std::vector<uint32_t> plan_order;
+    int n_wide = 0;                       // tensors given to the grid-wide selection
+    uint32_t wide_blocks = 0;
+    DescSlot slot[kDescSlots];            // which pointer lists the device tables hold
+    uint64_t slot_clock = 0;
+
+    // ---- what the decode tables currently hold ----
     int dev_dec_T = 0;
     bool dev_dec_valid = false;
+    double dec_p = 0.0;
+    int n_dec_wide = 0;
+    uint32_t dec_tiles = 0;
 
-    // options
+    // ---- options ----
     int force_exact = 0;
     int carry_keys = 0;
+    uint32_t wide_min_kept = kWideMinKept;
 
     // filter keys carried over from the previous successful call (same tensor sizes, same p)
     bool hist_valid = false;
     double hist_p = 0.0;
     std::vector<uint32_t> hist_n;
-    int result_idx = 0;           // compress calls alternate between result blocks 0 and 1; decode uses 2
-    bool result_dirty = true;     // the next compress call must clear its result blocks itself
-    bool dec_result_dirty = true; // same for decode
-    int dec_result_idx = 0;
 
-    // optional per-kernel timing with HIP events on the caller's stream
+    // result blocks: calls alternate between two, and a kernel of each call clears the other one
+    int result_idx = 0;
+    bool result_dirty = true;             // the next compress call must clear its result blocks itself
+    int dec_result_idx = 0;
+    bool dec_result_dirty = true;
+
+    // optional per-kernel timing: start/stop events of the dispatches
     int profile_level = 0;
     hipEvent_t ev[2 * kNumStages] = {};
     bool ev_ok = false;
@@ -134,8 +141,6 @@ struct sbc_ctx {
     bool last_used_exact_path = false;
     bool last_used_history = false;
     bool last_used_wide = false;
-    std::vector<TensorDesc> plan;
-    std::vector<uint32_t> plan_order;
 };
 
 namespace {
@@ -286,10 +291,10 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     ok = ok && dev_alloc(&c->d_result, 4) == hipSuccess;      // two for compress, two for decode, used in turn
     ok = ok && dev_alloc(&c->d_dec, T) == hipSuccess;
     // tile decode: a stream of w words has w/2 segments; every stream is rounded up to whole tiles
-    c->dec_seg_cap = c->stage_cap / 2 + (uint64_t)(sbc_ctx::kMaxWideDec + 1) * kDecThreads;
-    c->dec_tile_cap = c->dec_seg_cap / kDecThreads + sbc_ctx::kMaxWideDec;
-    ok = ok && dev_alloc(&c->d_dec_wide, (size_t)sbc_ctx::kMaxWideDec) == hipSuccess;
-    ok = ok && host_alloc(&c->h_dec_wide, (size_t)sbc_ctx::kMaxWideDec) == hipSuccess;
+    c->dec_seg_cap = c->stage_cap / 2 + (uint64_t)(kMaxWideDec + 1) * kDecThreads;
+    c->dec_tile_cap = c->dec_seg_cap / kDecThreads + kMaxWideDec;
+    ok = ok && dev_alloc(&c->d_dec_wide, (size_t)kMaxWideDec) == hipSuccess;
+    ok = ok && host_alloc(&c->h_dec_wide, (size_t)kMaxWideDec) == hipSuccess;
     ok = ok && dev_alloc(&c->d_seg_fn, (size_t)c->dec_seg_cap) == hipSuccess;
     ok = ok && dev_alloc(&c->d_seg_pack, (size_t)c->dec_seg_cap) == hipSuccess;
     ok = ok && dev_alloc(&c->d_tile_fn, (size_t)c->dec_tile_cap) == hipSuccess;
@@ -688,7 +693,7 @@ int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, siz
         for (int t = 0; t < T; ++t) {
             c->h_dec[t].out = out[t]; c->h_dec[t].n = (uint32_t)numel[t]; c->h_dec[t].wide = 0u;
             const int64_t k = kept_of(numel[t], p);
-            if (b > kPackedMaxB || (uint64_t)k < (uint64_t)c->wide_min_kept || n_wide >= sbc_ctx::kMaxWideDec) continue;
+            if (b > kPackedMaxB || (uint64_t)k < (uint64_t)c->wide_min_kept || n_wide >= kMaxWideDec) continue;
             const uint64_t max_seg = (bound_words_of(numel[t], (uint32_t)k, b) + 1) / 2;
             const uint64_t max_tiles = (max_seg + kDecThreads - 1) / kDecThreads;
             if (max_tiles == 0 || max_tiles >= (1ull << 31) || segs + max_tiles * kDecThreads > c->dec_seg_cap ||
