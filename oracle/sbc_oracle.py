@@ -31,6 +31,15 @@ it is used):
 * binary_b*(r) is written most significant bit first; stream bit i lives in
   32-bit word i // 32 at bit 31 - i % 32; padding bits are zero.
 * b* = max(0, 1 + floor(log2(log(phi-1)/log(1-p)))).
+* The subsampled variant mentioned in "Sparse Binarization" (threshold from a
+  random subsample, noisy amount of sparsity) is read as: per tensor, a
+  stratified sample of at most 16384 entries of A (256 runs of 64 consecutive
+  entries, one run at a hashed place in each of 256 equal strata; the whole
+  tensor if it has no more than 16384 entries); a side's threshold is the r-th
+  most extreme sampled value, r = max(1, floor(p*m)) for m sampled entries;
+  the side keeps every entry at or beyond its threshold, at most
+  min(n, 2k + 64) of them (the most extreme ones, ties to the lowest index, if
+  more qualify); each side's mean is over its own count.
 
 Pins: every function below is pinned by tests/test_oracle_*.py (closed forms,
 brute force on tiny inputs, exact rational arithmetic, invariants, special
@@ -166,6 +175,87 @@ def residual_update(A: np.ndarray, kept: np.ndarray, mu_signed: np.float32) -> n
 
 
 # --------------------------------------------------------------------------
+# Subsampled variant of Alg. 2 ("Sparse Binarization": the threshold comes from a
+# random subsample, which makes the amount of sparsity noisy)
+# --------------------------------------------------------------------------
+
+SAMPLE_MAX = 16384   # entries sampled per tensor
+SAMPLE_RUN = 64      # consecutive entries per run
+SAMPLE_RUNS = SAMPLE_MAX // SAMPLE_RUN
+
+
+def mix32(x: int) -> int:
+    """Counter-based generator of the sample: a bijective 32-bit mixing function
+    (xor-shift 16, multiply 0x7FEB352D, xor-shift 15, multiply 0x846CA68B,
+    xor-shift 16).  Both implementations of the method use this function, so
+    the random numbers the method draws are the same on both."""
+    x &= 0xFFFFFFFF
+    x ^= x >> 16
+    x = (x * 0x7FEB352D) & 0xFFFFFFFF
+    x ^= x >> 15
+    x = (x * 0x846CA68B) & 0xFFFFFFFF
+    x ^= x >> 16
+    return x
+
+
+def sample_positions(n: int, tensor_index: int) -> np.ndarray:
+    """Positions of the subsample of tensor number tensor_index (its place in the
+    model's tensor list) with n entries.  Up to SAMPLE_MAX entries: all of them.
+    Otherwise the n // 64 aligned slots of 64 entries are cut into SAMPLE_RUNS
+    equal strata (stratum r holds slots floor(r*slots/256) .. floor((r+1)*slots/256)-1)
+    and stratum r contributes the slot at offset floor(h * size / 2^32) where
+    h = mix32(r * 0x9E3779B9 + tensor_index * 0x85EBCA6B + 1 mod 2^32)."""
+    if n <= SAMPLE_MAX:
+        return np.arange(n, dtype=np.int64)
+    slots = n // SAMPLE_RUN
+    pos = []
+    for r in range(SAMPLE_RUNS):
+        h = mix32((r * 0x9E3779B9 + tensor_index * 0x85EBCA6B + 1) & 0xFFFFFFFF)
+        lo = (r * slots) // SAMPLE_RUNS
+        hi = ((r + 1) * slots) // SAMPLE_RUNS
+        slot = lo + ((h * (hi - lo)) >> 32)
+        pos.extend(range(slot * SAMPLE_RUN, (slot + 1) * SAMPLE_RUN))
+    return np.asarray(pos, dtype=np.int64)
+
+
+def sampled_thresholds(A: np.ndarray, p: float, tensor_index: int):
+    """(t+, t-): the r-th largest sampled value of A and of -A, r = max(1, floor(p*m))
+    for m sampled entries."""
+    sample = A[sample_positions(A.shape[0], tensor_index)]
+    r = num_kept(sample.shape[0], p)
+    ascending = np.sort(sample.astype(np.float64))
+    return np.float32(ascending[-r]), np.float32(-ascending[r - 1])
+
+
+def sampled_cap(n: int, k: int) -> int:
+    """Most entries a side may keep in the subsampled variant."""
+    return min(n, 2 * k + 64)
+
+
+def sparse_binary_compress_sampled(A: np.ndarray, p: float, tensor_index: int):
+    """Alg. 2 with thresholds from the subsample.  Same return value as
+    sparse_binary_compress; idx_pos / idx_neg hold c+ / c- entries in rank order."""
+    assert A.dtype == np.float32 and A.ndim == 1
+    if not np.all(np.isfinite(A)):
+        raise ValueError("non-finite entry")
+    n = A.shape[0]
+    k = num_kept(n, p)
+    cap = sampled_cap(n, k)
+    t_pos, t_neg = sampled_thresholds(A, p, tensor_index)
+    c_pos = min(cap, int(np.count_nonzero(A >= t_pos)))
+    c_neg = min(cap, int(np.count_nonzero(-A >= t_neg)))
+    idx_pos = top_fraction(A, c_pos)             # every entry >= t+, or the cap most extreme
+    idx_neg = top_fraction(-A, c_neg)
+    mu_pos = side_mean(A[idx_pos])
+    mu_neg = side_mean(-A[idx_neg])
+    if mu_pos >= mu_neg:
+        side, mu_signed, kept = +1, np.float32(mu_pos), idx_pos
+    else:
+        side, mu_signed, kept = -1, np.float32(-np.float32(mu_neg)), idx_neg
+    return k, idx_pos, idx_neg, mu_pos, mu_neg, side, np.float32(mu_signed), np.sort(kept)
+
+
+# --------------------------------------------------------------------------
 # Alg. 3 (encode) and Alg. 4 (decode), bit by bit
 # --------------------------------------------------------------------------
 
@@ -241,13 +331,17 @@ def unpack_bits(words: np.ndarray, bit_len: int) -> List[int]:
 # One tensor, one round; a model (list of tensors); the message container
 # --------------------------------------------------------------------------
 
-def compress_tensor(dW: np.ndarray, R: np.ndarray, p: float) -> TensorResult:
+def compress_tensor(dW: np.ndarray, R: np.ndarray, p: float, sampled_index: int = None) -> TensorResult:
     """Client lines of Alg. 1 for one tensor: accumulate, Alg. 2, residual
-    update, Alg. 3."""
+    update, Alg. 3.  With sampled_index (the tensor's place in the model's list)
+    the subsampled variant of Alg. 2 is used."""
     dW = np.ascontiguousarray(dW, dtype=np.float32).reshape(-1)
     R = np.ascontiguousarray(R, dtype=np.float32).reshape(-1)
     A = accumulate(R, dW)
-    k, idx_pos, idx_neg, mu_pos, mu_neg, side, mu_signed, kept = sparse_binary_compress(A, p)
+    if sampled_index is None:
+        k, idx_pos, idx_neg, mu_pos, mu_neg, side, mu_signed, kept = sparse_binary_compress(A, p)
+    else:
+        k, idx_pos, idx_neg, mu_pos, mu_neg, side, mu_signed, kept = sparse_binary_compress_sampled(A, p, sampled_index)
     R_new = residual_update(A, kept, mu_signed)
     b = golomb_bstar(p)
     bits = golomb_encode(kept, b)
@@ -257,9 +351,9 @@ def compress_tensor(dW: np.ndarray, R: np.ndarray, p: float) -> TensorResult:
         R_new=R_new, bstar=b, gaps=golomb_gaps(kept), bits=bits, words=pack_bits(bits))
 
 
-def compress_model(dWs: Sequence[np.ndarray], Rs: Sequence[np.ndarray], p: float) -> List[TensorResult]:
+def compress_model(dWs: Sequence[np.ndarray], Rs: Sequence[np.ndarray], p: float, sampled: bool = False) -> List[TensorResult]:
     """Per-tensor SBC over the list of weight tensors of a model (W in script-W)."""
-    return [compress_tensor(dW, R, p) for dW, R in zip(dWs, Rs)]
+    return [compress_tensor(dW, R, p, t if sampled else None) for t, (dW, R) in enumerate(zip(dWs, Rs))]
 
 
 def build_message(results: Sequence[TensorResult]) -> bytes:
