@@ -46,6 +46,9 @@ def main() -> int:
     ap.add_argument("--breakdown", action="store_true", help="also print per-kernel times to stderr")
     ap.add_argument("--carry-keys", action="store_true",
                     help="set SBC_OPT_CARRY_FILTER_KEYS (filter keys from the previous round instead of sampling)")
+    ap.add_argument("--sampled-threshold", action="store_true",
+                    help="set SBC_OPT_SAMPLED_THRESHOLD (the subsampled variant with a noisy amount of sparsity; "
+                         "reported for reference, not the benchmark's mode)")
     ap.add_argument("--workload", default="resnet50", choices=["resnet50", "lstm", "gauss2p20", "student4m", "flat1p5e9"],
                     help="resnet50 (default) is the benchmark workload; the others are reported for reference")
     args = ap.parse_args()
@@ -104,12 +107,14 @@ def main() -> int:
     dW_sets = [sbc.TensorList(views(f)) for f in flat_sets]
     R = sbc.TensorList(views(flat_R))
     out = sbc.TensorList(views(flat_out))
-    bound = sbc.sbc_msg_bound(sizes, P)
+    bound = (sbc.sbc_msg_bound_sampled if args.sampled_threshold else sbc.sbc_msg_bound)(sizes, P)
     msg = sbc.MessageBuffer(torch.zeros(bound, dtype=torch.uint8, device=dev))
     stream = torch.cuda.current_stream().cuda_stream      # raw handle, looked up once
     ctx = sbc.sbc_create(0, N, T)
     if args.carry_keys:
         sbc.sbc_set_option(ctx, sbc.SBC_OPT_CARRY_FILTER_KEYS, 1)
+    if args.sampled_threshold:
+        sbc.sbc_set_option(ctx, sbc.SBC_OPT_SAMPLED_THRESHOLD, 1)
     scale = 1.0 / 32.0
 
     def step(i):
@@ -202,7 +207,8 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": name, "p": P, "tensors": T, "entries": N,
-                   "step": "sbc_compress + sbc_decompress_accumulate (one client, one round)"},
+                   "step": "sbc_compress + sbc_decompress_accumulate (one client, one round)",
+                   "selection": "subsampled threshold (noisy count)" if args.sampled_threshold else "exact top-k"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES if args.workload == "resnet50" else None,

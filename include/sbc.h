@@ -95,10 +95,16 @@ int64_t sbc_num_kept(int64_t numel, double p);
  * numel is a host array. */
 size_t sbc_msg_bound(const int64_t* numel, int n_tensors, double p);
 
+/* Same for a context with SBC_OPT_SAMPLED_THRESHOLD set, where a tensor sends up to
+ * min(numel, 2k + 64) positions. */
+size_t sbc_msg_bound_sampled(const int64_t* numel, int n_tensors, double p);
+
 /* Client step (Alg. 1 client lines, Alg. 2, Alg. 3) for n_tensors tensors:
  *     A_t   = residual_t + dW_t                     (fp32, one rounding)
  *     dW*_t = SBC(A_t, p)                           (exactly k_t kept entries on one side;
- *                                                    equal values resolved to the lowest index)
+ *                                                    equal values resolved to the lowest index;
+ *                                                    see SBC_OPT_SAMPLED_THRESHOLD for the
+ *                                                    variant with a noisy count)
  *     residual_t <- A_t - dW*_t                     (in place)
  *     msg   <- container of { mu_signed_t, Golomb(kept positions of t) }
  * dW[t]        device, read only, numel[t] floats, 4-byte aligned (16 is faster)
@@ -130,8 +136,8 @@ int sbc_decompress_accumulate(sbc_ctx* ctx, void* hip_stream,
                               const int64_t* numel, int n_tensors, double p,
                               float scale, float* const* out);
 
-/* Options of a context.  None of them changes a result: sbc_compress is exact on every route.
- * It finds each tensor's top-k candidates with a filter key per sign side and, for a tensor
+/* Options of a context.  Except for SBC_OPT_SAMPLED_THRESHOLD none of them changes a result:
+ * sbc_compress is exact on every route.  It finds each tensor's top-k candidates with a filter key per sign side and, for a tensor
  * whose filter turns out to have kept fewer than k entries, falls back to an exact histogram
  * of a second read of that tensor.
  *   SBC_OPT_FORCE_EXACT_PATH   (0/1, default 0)  1 makes every tensor take the histogram route
@@ -144,8 +150,23 @@ int sbc_decompress_accumulate(sbc_ctx* ctx, void* hip_stream,
  *       and costs time when they move more (a flood of candidates, then a sampled round).
  *   SBC_OPT_WIDE_MIN_KEPT      (default 0 = 8192)  a tensor that keeps at least this many entries
  *       per side is selected by grid-wide kernels instead of one workgroup (a 1.5e9-entry tensor
- *       at p = 0.001 keeps 1.5e6); tests lower it to send small tensors that way. */
-enum { SBC_OPT_FORCE_EXACT_PATH = 1, SBC_OPT_CARRY_FILTER_KEYS = 2, SBC_OPT_WIDE_MIN_KEPT = 3 };
+ *       at p = 0.001 keeps 1.5e6); tests lower it to send small tensors that way.
+ *   SBC_OPT_SAMPLED_THRESHOLD  (0/1, default 0)  1 selects the subsampled variant of
+ *       "Sparse Binarization" (the threshold is estimated from a random subsample, which makes
+ *       the amount of sparsity noisy).  Per tensor t of the call a stratified sample of at most
+ *       16384 entries of A_t is drawn: the whole tensor if it is no larger, else 256 aligned runs
+ *       of 64 consecutive entries, run r at slot floor(r*S/256) + floor(h*w/2^32) of the S =
+ *       floor(numel/64) slots, w the width of stratum r and h = mix32(r*0x9E3779B9 +
+ *       t*0x85EBCA6B + 1 mod 2^32), mix32(x): x ^= x>>16; x *= 0x7FEB352D; x ^= x>>15;
+ *       x *= 0x846CA68B; x ^= x>>16.  With m sampled entries and r = max(1, floor(p*m)) a
+ *       side's threshold is its r-th most extreme sampled value; the side keeps every entry at or
+ *       beyond it, at most min(numel, 2k + 64) of them (the most extreme, equal values to the
+ *       lowest index); mu+ and mu- are means over each side's own count.  The message buffer
+ *       must hold sbc_msg_bound_sampled() bytes; set the option on a decoding context as well,
+ *       so that it reserves for the longer streams.  The options FORCE_EXACT_PATH and
+ *       CARRY_FILTER_KEYS are ignored while it is set. */
+enum { SBC_OPT_FORCE_EXACT_PATH = 1, SBC_OPT_CARRY_FILTER_KEYS = 2, SBC_OPT_WIDE_MIN_KEPT = 3,
+       SBC_OPT_SAMPLED_THRESHOLD = 4 };
 int sbc_set_option(sbc_ctx* ctx, int option, int value);
 
 /* Which routes the most recent successful sbc_compress() took: a bit set of

@@ -26,12 +26,13 @@ SBC_EINTERNAL = -6
 SBC_OPT_FORCE_EXACT_PATH = 1
 SBC_OPT_CARRY_FILTER_KEYS = 2
 SBC_OPT_WIDE_MIN_KEPT = 3
+SBC_OPT_SAMPLED_THRESHOLD = 4
 SBC_ROUTE_CARRIED_KEYS = 1
 SBC_ROUTE_HISTOGRAM = 2
 SBC_ROUTE_WIDE = 4
 
 EXPORTS = (
-    "sbc_create", "sbc_destroy", "sbc_golomb_bstar", "sbc_num_kept", "sbc_msg_bound",
+    "sbc_create", "sbc_destroy", "sbc_golomb_bstar", "sbc_num_kept", "sbc_msg_bound", "sbc_msg_bound_sampled",
     "sbc_compress", "sbc_decompress_accumulate", "sbc_last_tensor_stats", "sbc_last_mask",
     "sbc_profile_enable", "sbc_profile_level", "sbc_profile_read", "sbc_copy_baseline", "sbc_set_option",
     "sbc_last_route", "sbc_strerror",
@@ -64,6 +65,8 @@ def load() -> ctypes.CDLL:
     lib.sbc_num_kept.restype = i64
     lib.sbc_msg_bound.argtypes = [ctypes.POINTER(i64), ctypes.c_int, ctypes.c_double]
     lib.sbc_msg_bound.restype = sz
+    lib.sbc_msg_bound_sampled.argtypes = [ctypes.POINTER(i64), ctypes.c_int, ctypes.c_double]
+    lib.sbc_msg_bound_sampled.restype = sz
     lib.sbc_compress.argtypes = [vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(i64),
                                  ctypes.c_int, ctypes.c_double, vp, sz, ctypes.POINTER(sz)]
     lib.sbc_compress.restype = ctypes.c_int
@@ -175,6 +178,10 @@ def sbc_num_kept(numel: int, p: float) -> int:
 
 def sbc_msg_bound(numel: Sequence[int], p: float) -> int:
     return int(load().sbc_msg_bound(_i64_array(numel), len(numel), float(p)))
+
+
+def sbc_msg_bound_sampled(numel: Sequence[int], p: float) -> int:
+    return int(load().sbc_msg_bound_sampled(_i64_array(numel), len(numel), float(p)))
 
 
 # ------------------------------------------------------------------ context

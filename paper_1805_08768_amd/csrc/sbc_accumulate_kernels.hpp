@@ -57,16 +57,19 @@ __device__ __forceinline__ uint32_t mix32(uint32_t x) {
 // + 3, so that the chance of cutting into the true top k is negligible (and harmless: the
 // histogram path then redoes the tensor).  Both sides are selected together, the negative side
 // on complemented keys.  The kernel also clears the per-tensor state and the result block.
+// For tensors flagged kDescSampled ("Sparse Binarization": the threshold is estimated from a
+// random subsample, which makes the amount of sparsity noisy) the key is instead the full 32-bit
+// key of the sample's r-th most extreme entry, r = max(1, floor(p*m)): the threshold itself.
 // --------------------------------------------------------------------------
 __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
         const TensorDesc* __restrict__ desc, TensorState* __restrict__ st,
-        ResultBlock* __restrict__ result, int force_exact) {
+        ResultBlock* __restrict__ result, int force_exact, double sampled_p) {
     constexpr int RUNS = kSampleMax / 64;             // 256
     constexpr int COPIES = 16;
     __shared__ uint32_t skey[kSampleMax];             // the sample, as keys (loops stay rolled: small code)
     __shared__ uint32_t hist0[2][256][COPIES];        // first byte: lane-private copies, one bank each
-    __shared__ uint32_t hist[2][2][256];
-    __shared__ uint32_t res[2][8];
+    __shared__ uint32_t hist[4][2][256];
+    __shared__ uint32_t res[4][8];
     __shared__ unsigned long long scratch[kSampleThreads / 64];
     SBC_TS(0, 0);
     const int t = blockIdx.x, tid = threadIdx.x;
@@ -79,6 +82,7 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
         z.bin[0] = z.bin[1] = 0u;
         z.tau[0] = z.tau[1] = 0u;
         z.itau[0] = z.itau[1] = 0u;
+        z.kc[0] = z.kc[1] = 0u;
         z.S[0] = z.S[1] = 0.0;
         z.side = 0; z.mu_signed = 0.f; z.nnz = 0u; z.flags = 0u; z.bit_len = 0ull;
         st[t] = z;
@@ -87,14 +91,21 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
 
     const uint32_t n = d.n;
     const uint32_t m = n < (uint32_t)kSampleMax ? n : (uint32_t)kSampleMax;
+    const bool sampled = (d.flags & kDescSampled) != 0u;
     uint32_t rs = d.k;
-    if (n > (uint32_t)kSampleMax) {
+    if (sampled) {
+        // "Sparse Binarization", subsampled variant: the r-th most extreme sampled value itself is
+        // the threshold, r = max(1, floor(p * m))
+        const double r = floor(sampled_p * (double)m);
+        rs = r < 1.0 ? 1u : (uint32_t)r;
+    } else if (n > (uint32_t)kSampleMax) {
         const double lambda = (double)d.k * (double)m / (double)n;
         rs = (uint32_t)ceil(lambda + 4.0 * sqrt(lambda) + 3.0);
     }
     if (rs >= m) return;                              // keep the all-pass keys (0, 0)
+    const int passes = sampled ? 4 : 2;               // all 32 key bits, or the leading 16
 
-    for (int i = tid; i < 2 * 256; i += kSampleThreads) (&hist[1][0][0])[i] = 0u;
+    for (int i = tid; i < 3 * 2 * 256; i += kSampleThreads) (&hist[1][0][0])[i] = 0u;
     for (int i = tid; i < 2 * 256 * COPIES; i += kSampleThreads) (&hist0[0][0][0])[i] = 0u;
     __syncthreads();
     // The sample: all of a thread's loads are issued before the first key is formed, so that the
@@ -147,19 +158,20 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
         __syncthreads();
     }
     SBC_TS(0, 2);                                     // first-byte histogram done
-    // two bytes of the r-th largest key (positive side) and of the r-th largest complemented
-    // key (negative side)
+    // the leading bytes of the r-th largest key (positive side) and of the r-th largest
+    // complemented key (negative side), one byte per pass
     uint32_t need[2] = {rs, rs};
     const bool active[2] = {true, true};
     uint32_t prefix[2] = {0u, 0u};
 #pragma nounroll
-    for (int pass = 0; pass < 2; ++pass) {
+    for (int pass = 0; pass < passes; ++pass) {
         if (pass > 0) {
+            const int shift = 24 - 8 * pass;
 #pragma unroll 8
             for (uint32_t i = tid; i < m; i += kSampleThreads) {
                 const uint32_t kp = skey[i], kn = ~kp;
-                if ((kp >> 24) == prefix[0]) atomicAdd(&hist[1][0][(kp >> 16) & 255u], 1u);
-                if ((kn >> 24) == prefix[1]) atomicAdd(&hist[1][1][(kn >> 16) & 255u], 1u);
+                if ((kp >> (shift + 8)) == prefix[0]) atomicAdd(&hist[pass][0][(kp >> shift) & 255u], 1u);
+                if ((kn >> (shift + 8)) == prefix[1]) atomicAdd(&hist[pass][1][(kn >> shift) & 255u], 1u);
             }
             __syncthreads();
         }
@@ -170,10 +182,11 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
         prefix[0] = (prefix[0] << 8) | pk.byte[0];
         prefix[1] = (prefix[1] << 8) | pk.byte[1];
     }
-    SBC_TS(0, 9);
+    SBC_TS(0, 11);
     if (tid == 0) {
-        st[t].lo_key[0] = prefix[0] << 16;            // lower edge of the 16-bit bucket
-        st[t].lo_key[1] = prefix[1] << 16;            // same, in the complemented key space
+        const int left = 32 - 8 * passes;             // 16: lower edge of the 16-bit bucket; 0: the key itself
+        st[t].lo_key[0] = prefix[0] << left;
+        st[t].lo_key[1] = prefix[1] << left;          // same, in the complemented key space
     }
 }
 

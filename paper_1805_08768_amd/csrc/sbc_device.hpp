@@ -65,6 +65,7 @@ constexpr uint32_t kErrLoose = 16u;      // not an error: a carried-over filter 
 // TensorDesc::flags
 constexpr uint32_t kDescFused = 1u;      // sorted and encoded inside the select kernel
 constexpr uint32_t kDescWide = 2u;       // keeps so many entries that the grid-wide selection kernels take it
+constexpr uint32_t kDescSampled = 4u;    // subsampled variant: the sampled threshold decides what is kept
 // TensorState::flags
 constexpr uint32_t kStFailed = 1u;       // prefilter kept fewer than k candidates on a side
 constexpr uint32_t kStExact = 2u;        // taken over by the histogram path
@@ -83,7 +84,7 @@ struct TensorDesc {
     uint32_t bound_words; // worst-case stream length in words
     uint32_t kept_off;    // first entry of this tensor in the kept-index scratch
     uint32_t flags;
-    uint32_t pad;
+    uint32_t kcap;        // most entries a side may keep: k, or min(n, 2k + 64) in the subsampled variant
 };
 
 // Per-tensor results, written on the device.
@@ -93,7 +94,8 @@ struct alignas(8) TensorState {
     uint32_t bin[2];       // histogram path: first-digit bin holding the k-th entry of each side
     uint32_t tau[2];       // full 32-bit threshold key per side (side key space)
     uint32_t itau[2];      // ties at tau are kept up to this index
-    double S[2];           // sum of the k kept values per side (negated on the negative side)
+    uint32_t kc[2];        // entries kept per side: k, or the count the sampled threshold gave
+    double S[2];           // sum of the kept values per side (negated on the negative side)
     int32_t side;          // +1 / -1
     float mu_signed;
     uint32_t nnz;

@@ -202,7 +202,7 @@ __global__ __launch_bounds__(256) void k_gather(const TensorDesc* __restrict__ d
         *reinterpret_cast<uint32_t*>(e + 4) = st[t].nnz;
         *reinterpret_cast<uint64_t*>(e + 8) = bit_len;
         *reinterpret_cast<uint64_t*>(e + 16) = word_off;
-        if (st[t].nnz != d.k) atomicOr(&result->err, kErrInternal);
+        if (st[t].nnz != st[t].kc[st[t].side < 0 ? 1 : 0] || st[t].nnz > d.kcap) atomicOr(&result->err, kErrInternal);
         st[t].cand_cnt[0] = 0u; st[t].cand_cnt[1] = 0u; st[t].flags = 0u;
         if (t == 0) {
             uint32_t* h = reinterpret_cast<uint32_t*>(msg);

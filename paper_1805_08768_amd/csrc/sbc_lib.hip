@@ -115,6 +115,7 @@ struct sbc_ctx {
     // ---- options ----
     int force_exact = 0;
     int carry_keys = 0;
+    int sampled = 0;                      // subsampled variant: the sampled threshold decides what is kept
     uint32_t wide_min_kept = kWideMinKept;
 
     // filter keys carried over from the previous successful call (same tensor sizes, same p)
@@ -169,6 +170,11 @@ int64_t kept_of(int64_t n, double p) {
     if (k < 1) k = 1;
     if (k > n) k = n;
     return k;
+}
+
+// Most entries a side may keep: k, or in the subsampled variant min(n, 2k + 64).
+int64_t cap_of(int64_t n, int64_t k, bool sampled) {
+    return sampled ? std::min<int64_t>(n, 2 * k + 64) : k;
 }
 
 uint64_t bound_words_of(int64_t n, int64_t k, int b) {
@@ -244,17 +250,21 @@ int64_t sbc_num_kept(int64_t numel, double p) {
     return kept_of(numel, p);
 }
 
-size_t sbc_msg_bound(const int64_t* numel, int n_tensors, double p) {
+static size_t msg_bound(const int64_t* numel, int n_tensors, double p, bool sampled) {
     if (!numel || n_tensors <= 0 || !valid_p(p)) return 0;
     const int b = bstar_of(p);
     if (b > kMaxB) return 0;
     uint64_t words = 0;
     for (int t = 0; t < n_tensors; ++t) {
         if (numel[t] < 1 || numel[t] >= (int64_t)1 << 32) return 0;
-        words += bound_words_of(numel[t], kept_of(numel[t], p), b);
+        words += bound_words_of(numel[t], cap_of(numel[t], kept_of(numel[t], p), sampled), b);
     }
     return (size_t)(32 + 24ull * (unsigned)n_tensors + 4ull * words);
 }
+
+size_t sbc_msg_bound(const int64_t* numel, int n_tensors, double p) { return msg_bound(numel, n_tensors, p, false); }
+
+size_t sbc_msg_bound_sampled(const int64_t* numel, int n_tensors, double p) { return msg_bound(numel, n_tensors, p, true); }
 
 int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tensors) {
     if (!out || max_total_elems < 1 || max_tensors < 1) return SBC_EINVAL;
@@ -272,7 +282,7 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     // A tensor's stream is at most k(1+b*) + (n-k)/2^b* bits, which stays below 1.3 n for every p
     // (b* shrinks as p grows); n/16 words plus rounding per tensor is ample, and sbc_compress
     // checks the actual need against this capacity.
-    c->stage_cap = (uint64_t)max_total_elems / 16 + 2ull * (uint64_t)max_tensors + 64ull;
+    c->stage_cap = (uint64_t)max_total_elems / 16 + 64ull * (uint64_t)max_tensors + 64ull;
     DeviceGuard guard(device);
     const size_t T = (size_t)max_tensors;
     bool ok = true;
@@ -349,6 +359,12 @@ int sbc_set_option(sbc_ctx* c, int option, int value) {
     switch (option) {
         case SBC_OPT_FORCE_EXACT_PATH: c->force_exact = value ? 1 : 0; c->hist_valid = false; return SBC_OK;
         case SBC_OPT_CARRY_FILTER_KEYS: c->carry_keys = value ? 1 : 0; c->hist_valid = false; return SBC_OK;
+        case SBC_OPT_SAMPLED_THRESHOLD:
+            c->sampled = value ? 1 : 0;
+            c->cache_valid = false;                    // the capacities of the plan depend on it
+            c->dev_dec_valid = false;
+            c->hist_valid = false;
+            return SBC_OK;
         case SBC_OPT_WIDE_MIN_KEPT:
             if (value < 0) return SBC_EINVAL;
             c->wide_min_kept = value ? (uint32_t)value : kWideMinKept;
@@ -378,7 +394,10 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
     // that alternates between a few sets of buffers uploads nothing in the steady state.
     uint64_t total = 0, chunks = 0, stage_words = 0, kept_total = 0, max_bound = 0;
     bool any_bitmap = false;
-    bool use_history = c->hist_valid && !c->force_exact && c->hist_p == p && c->hist_n.size() == (size_t)T;
+    // in the subsampled variant the keys must come from this call's sample
+    const bool sampled = c->sampled != 0;
+    const int force_exact = sampled ? 0 : c->force_exact;
+    bool use_history = !sampled && c->hist_valid && !force_exact && c->hist_p == p && c->hist_n.size() == (size_t)T;
     const bool sizes_same = c->cache_valid && c->cache_T == T && c->cache_p == p &&
                             std::memcmp(c->cache_numel.data(), numel, sizeof(int64_t) * T) == 0;
     auto pointers_ok = [&](int t) -> bool {
@@ -415,22 +434,23 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
             std::memset(&d, 0, sizeof(d));
             d.n = (uint32_t)n;
             d.k = (uint32_t)kept_of(n, p);
+            d.kcap = (uint32_t)cap_of(n, d.k, sampled);
             d.chunk0 = (uint32_t)chunks;
             d.nchunks = (uint32_t)((n + kChunk - 1) / kChunk);
             d.cand_off = 2 * total;
             d.stage_off = stage_words;
-            const uint64_t bw = bound_words_of(n, d.k, b);
+            const uint64_t bw = bound_words_of(n, d.kcap, b);
             if (bw >= (1ull << 32)) return SBC_ECAPACITY;
             d.bound_words = (uint32_t)bw;
-            const bool fused = d.k <= kFusedMaxK && bw <= kFusedMaxWords;
-            d.flags = fused ? kDescFused : 0u;
-            if (!fused && d.k >= c->wide_min_kept && n_wide < kMaxWide) {
+            const bool fused = d.kcap <= kFusedMaxK && bw <= kFusedMaxWords;
+            d.flags = (fused ? kDescFused : 0u) | (sampled ? kDescSampled : 0u);
+            if (!fused && d.kcap >= c->wide_min_kept && n_wide < kMaxWide) {
                 d.flags |= kDescWide;
                 c->h_wide_ids[n_wide++] = (uint32_t)t;
                 wide_max_n = std::max<uint64_t>(wide_max_n, (uint64_t)n);
             }
             d.kept_off = (uint32_t)kept_total;
-            if (fused) kept_total += d.k; else any_bitmap = true;
+            if (fused) kept_total += d.kcap; else any_bitmap = true;
             if (use_history && c->hist_n[t] != d.n) use_history = false;
             total += (uint64_t)n;
             chunks += d.nchunks;
@@ -564,7 +584,7 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
     // sizes and sparsity (its select kernel derives them from the exact thresholds it found).
     if (!use_history) {
         SBC_LAUNCH(kStSample, true, k_sample_thresholds, dim3(T), dim3(kSampleThreads), d_desc, c->d_state,
-                   res_now, c->force_exact);
+                   res_now, force_exact, sampled ? p : 0.0);
     }
     // 12 bytes per entry pass through; beyond about twice the 256 MiB last-level cache the update
     // is loaded with the nontemporal hint
@@ -658,7 +678,7 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
     c->last_used_history = use_history;
     c->result_dirty = false;
     // the next call may start from this call's thresholds unless they proved unhelpful
-    c->hist_valid = c->carry_keys && !c->force_exact && !c->last_used_exact_path && !(err & kErrLoose);
+    c->hist_valid = c->carry_keys && !sampled && !force_exact && !c->last_used_exact_path && !(err & kErrLoose);
     if (c->hist_valid) {
         c->hist_p = p;
         c->hist_n.resize(T);
@@ -692,7 +712,8 @@ int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, siz
         uint64_t segs = 0, tiles = 0;
         for (int t = 0; t < T; ++t) {
             c->h_dec[t].out = out[t]; c->h_dec[t].n = (uint32_t)numel[t]; c->h_dec[t].wide = 0u;
-            const int64_t k = kept_of(numel[t], p);
+            // (a context that expects messages of the subsampled variant reserves for its cap)
+            const int64_t k = cap_of(numel[t], kept_of(numel[t], p), c->sampled != 0);
             if (b > kPackedMaxB || (uint64_t)k < (uint64_t)c->wide_min_kept || n_wide >= kMaxWideDec) continue;
             const uint64_t max_seg = (bound_words_of(numel[t], (uint32_t)k, b) + 1) / 2;
             const uint64_t max_tiles = (max_seg + kDecThreads - 1) / kDecThreads;
@@ -796,9 +817,9 @@ int sbc_last_tensor_stats(sbc_ctx* c, int tensor, double* mu_pos, double* mu_neg
         return SBC_EHIP;
     }
     const TensorState& s = c->h_state[0];
-    const double k = (double)c->plan[tensor].k;
-    if (mu_pos) *mu_pos = s.S[0] / k;
-    if (mu_neg) *mu_neg = s.S[1] / k;
+    if (s.kc[0] == 0u || s.kc[1] == 0u) return SBC_EINTERNAL;
+    if (mu_pos) *mu_pos = s.S[0] / (double)s.kc[0];
+    if (mu_neg) *mu_neg = s.S[1] / (double)s.kc[1];
     if (side) *side = s.side;
     if (nnz) *nnz = (int64_t)s.nnz;
     if (bit_len) *bit_len = (int64_t)s.bit_len;
@@ -812,8 +833,14 @@ int sbc_last_mask(sbc_ctx* c, int tensor, uint32_t* mask_words, size_t n_words) 
     DeviceGuard guard(c->device);
     if (d.flags & kDescFused) {
         // the select kernel left the sorted kept indices in scratch
-        std::vector<uint32_t> idx(d.k);
-        if (hipMemcpy(idx.data(), c->d_kept + d.kept_off, (size_t)d.k * 4, hipMemcpyDeviceToHost) != hipSuccess) {
+        if (hipMemcpy(c->h_state, c->d_state + tensor, sizeof(TensorState), hipMemcpyDeviceToHost) != hipSuccess) {
+            (void)hipGetLastError();
+            return SBC_EHIP;
+        }
+        const uint32_t nnz = c->h_state[0].nnz;
+        if (nnz > d.kcap) return SBC_EINTERNAL;
+        std::vector<uint32_t> idx(nnz);
+        if (hipMemcpy(idx.data(), c->d_kept + d.kept_off, (size_t)nnz * 4, hipMemcpyDeviceToHost) != hipSuccess) {
             (void)hipGetLastError();
             return SBC_EHIP;
         }

@@ -205,13 +205,15 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     const TensorDesc d = desc[t];
     if (pass == 0 && (d.flags & kDescWide) && (st[t].flags & kStWideDone)) return;   // done by the grid-wide kernels
     const uint32_t k = d.k, n = d.n;
+    const bool sampled = (d.flags & kDescSampled) != 0u;
     const uint32_t cnt_p = __builtin_amdgcn_readfirstlane(st[t].cand_cnt[0]);
     const uint32_t cnt_n = __builtin_amdgcn_readfirstlane(st[t].cand_cnt[1]);
-    if (cnt_p > n || cnt_n > n) {
+    if (cnt_p > n || cnt_n > n || (sampled && (cnt_p == 0u || cnt_n == 0u))) {
+        // (a sampled threshold is the key of an entry of the tensor, so that entry is a candidate)
         if (tid == 0) atomicOr(&result->err, kErrInternal);
         return;
     }
-    if (cnt_p < k || cnt_n < k) {
+    if (!sampled && (cnt_p < k || cnt_n < k)) {
         // the filter kept too few entries on a side: the histogram path redoes this tensor
         if (tid == 0) {
             st[t].flags = kStFailed;
@@ -230,7 +232,11 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     // or above the side's filter key, and the k-th lies close above it, so a window of kWindow
     // values of (key >> kWinShift) starting at the filter key's is histogrammed in the same sweep
     // that stages the lists in LDS; the top bin collects everything beyond the window.
-    uint32_t need[2] = {k, k}, tau[2] = {0u, 0u};
+    // Entries kept per side: k; in the subsampled variant every candidate (all entries at or beyond
+    // the sampled threshold), up to the cap.  If no side exceeds the cap there is nothing to select.
+    const uint32_t kc[2] = {sampled ? min(cnt_p, d.kcap) : k, sampled ? min(cnt_n, d.kcap) : k};
+    const bool pick = !sampled || cnt_p > d.kcap || cnt_n > d.kcap;
+    uint32_t need[2] = {kc[0], kc[1]}, tau[2] = {0u, 0u};
     const bool both[2] = {true, true};
     const uint32_t wbase[2] = {st[t].lo_key[0] >> kWinShift, st[t].lo_key[1] >> kWinShift};
     bool ok = true;
@@ -248,7 +254,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         if (list.staged) {
             const uint2* __restrict__ g = list.g[s];
 #pragma unroll 4
-            for (uint32_t i = tid; i < list.cnt[s]; i += kSelThreads) { const uint2 e = g[i]; sh.cand[s][i] = e; count(e); }
+            for (uint32_t i = tid; i < list.cnt[s]; i += kSelThreads) { const uint2 e = g[i]; sh.cand[s][i] = e; if (pick) count(e); }
+        } else if (!pick) {
+            // nothing to count
         } else if (s == 0) {
             sweep<0>(sh, list, count);
         } else {
@@ -257,19 +265,24 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     }
     __syncthreads();
     SBC_TS(1, 2);                                     // staged, leading bits counted
-    uint32_t digit[2];
-    bool found[2];
-    pick_wide_both<kWindow, kSelThreads>(sh.whist, need, both, sh.res[0], sh.scratch64, digit, found);
-    // entries in each side's threshold bucket (same leading 16 bits as the k-th entry)
-    uint32_t bsize[2];
+    uint32_t digit[2] = {0u, 0u};
+    bool found[2] = {false, false};
+    uint32_t bsize[2] = {0u, 0u};
+    if (pick) {
+        pick_wide_both<kWindow, kSelThreads>(sh.whist, need, both, sh.res[0], sh.scratch64, digit, found);
+        // entries in each side's threshold bucket (same leading key bits as the k-th entry)
 #pragma unroll
-    for (int s = 0; s < 2; ++s) bsize[s] = found[s] ? sh.whist[s][digit[s]] : 0u;
+        for (int s = 0; s < 2; ++s) bsize[s] = found[s] ? sh.whist[s][digit[s]] : 0u;
+    }
     __syncthreads();                                  // whist shares its space with what follows
     SBC_TS(1, 3);
     uint32_t itau[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};
     const bool rankable = found[0] && found[1] && digit[0] != (uint32_t)(kWindow - 1) &&
                           digit[1] != (uint32_t)(kWindow - 1) && bsize[0] <= kRankMax && bsize[1] <= kRankMax;
-    if (rankable) {
+    if (!pick) {
+        // every candidate is kept: the filter key serves as the threshold (no candidate lies below it)
+        tau[0] = st[t].lo_key[0]; tau[1] = st[t].lo_key[1];
+    } else if (rankable) {
         // The usual case: few entries share the threshold's leading bits.  They are copied out,
         // and every thread ranks one of them against the others by (key descending, index
         // ascending); the entry of rank need - 1 is the k-th of its side, ties included.
@@ -336,7 +349,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         uint32_t prefix[2], tie_key[2] = {0u, 0u};
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
-            first_pass[s] = 0; prefix[s] = 0u; need[s] = k;
+            first_pass[s] = 0; prefix[s] = 0u; need[s] = kc[s];
         }
 #pragma nounroll
         for (int mode = 0; mode < 2; ++mode) {
@@ -367,7 +380,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     for (int i = tid; i < 512; i += kSelThreads) (&sh.acc[0][0])[i] = 0ll;
     __syncthreads();
     // common-scale path: the k-th entry of a side has the side's sign (so have all kept ones)
-    const bool common[2] = {k <= 32768u && tau[0] > 0x80000000u, k <= 32768u && tau[1] >= 0x80000000u};
+    const bool common[2] = {kc[0] <= 32768u && tau[0] > 0x80000000u, kc[1] <= 32768u && tau[1] >= 0x80000000u};
     uint32_t e_ref[2];
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
@@ -408,12 +421,15 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     __syncthreads();
     SBC_TS(1, 5);                                     // sums done
     const double Sp = sh.S[0], Sn = sh.S[1];
-    const int chosen = (Sp >= Sn) ? 0 : 1;            // mu+ >= mu-  <=>  S+ >= S-  (equal counts)
-    const float mu32 = (float)((chosen ? Sn : Sp) / (double)k);
+    // mu+ >= mu-; with equal counts that is S+ >= S-
+    const int chosen = sampled ? ((Sp / (double)kc[0] >= Sn / (double)kc[1]) ? 0 : 1) : ((Sp >= Sn) ? 0 : 1);
+    const uint32_t kk = kc[chosen];                   // entries this tensor sends
+    const float mu32 = (float)((chosen ? Sn : Sp) / (double)kk);
     const float mu_signed = chosen ? -mu32 : mu32;
     if (tid == 0) {
         st[t].tau[0] = tau[0]; st[t].tau[1] = tau[1];
         st[t].itau[0] = itau[0]; st[t].itau[1] = itau[1];
+        st[t].kc[0] = kc[0]; st[t].kc[1] = kc[1];
         st[t].S[0] = Sp; st[t].S[1] = Sn;
         st[t].side = chosen ? -1 : 1;
         st[t].mu_signed = mu_signed;
@@ -481,7 +497,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         uint32_t ex = block_excl_sum<uint32_t, kSelThreads>(sum, &total, sh.scratch);
 #pragma unroll
         for (int j = 0; j < PB; ++j) { sh.bucket_cnt[tid * PB + j] = ex; ex += loc[j]; }
-        if (total != k) {                             // uniform: every thread sees the same total
+        if (total != kk) {                            // uniform: every thread sees the same total
             if (tid == 0) atomicOr(&result->err, kErrInternal);
             return;
         }
@@ -497,7 +513,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     });
     __syncthreads();
     SBC_TS(1, 8);                                     // grouped, residual updated
-    for (uint32_t i = tid; i < k; i += kSelThreads) {
+    for (uint32_t i = tid; i < kk; i += kSelThreads) {
         const uint32_t v = grp[i];
         const uint32_t bk = v >> shift;
         const uint32_t lo = sh.bucket_cnt[bk], hi = lo + sh.bucket_fill[bk];
@@ -509,9 +525,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
 
     SBC_TS(1, 9);                                     // sorted
     // Golomb code lengths of E consecutive entries per thread, then their bit offsets
-    const uint32_t E = (k + kSelThreads - 1) / kSelThreads;
-    const uint32_t i0 = tid * E < k ? tid * E : k;
-    const uint32_t i1 = i0 + E < k ? i0 + E : k;
+    const uint32_t E = (kk + kSelThreads - 1) / kSelThreads;
+    const uint32_t i0 = tid * E < kk ? tid * E : kk;
+    const uint32_t i1 = i0 + E < kk ? i0 + E : kk;
     unsigned long long bits = 0ull;
     {
         uint32_t pe = i0 ? sorted[i0 - 1] + 1u : 0u;
@@ -550,8 +566,8 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     uint32_t* __restrict__ out = stage + d.stage_off;
     for (uint32_t w = tid; w < n_words; w += kSelThreads) out[w] = words[w];
     uint32_t* __restrict__ ki = kept_idx + d.kept_off;
-    for (uint32_t i = tid; i < k; i += kSelThreads) ki[i] = sorted[i];
-    if (tid == 0) { st[t].bit_len = total_bits; st[t].nnz = k; }
+    for (uint32_t i = tid; i < kk; i += kSelThreads) ki[i] = sorted[i];
+    if (tid == 0) { st[t].bit_len = total_bits; st[t].nnz = kk; }
     SBC_TS(1, 12);
 }
 

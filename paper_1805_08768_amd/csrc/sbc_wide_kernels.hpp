@@ -37,8 +37,23 @@ struct WideState {
     uint32_t itau[2];     // ties at tau are kept up to this index
     uint32_t ties[2];     // entries equal to tau
     uint32_t tie_cnt[2];  // indices collected by k_wide_ties
-    uint32_t pad;
+    uint32_t kc[2];       // entries kept per side: k, or (subsampled variant) the candidates up to the cap
+    uint32_t all;         // 1: every candidate is kept (subsampled variant), tau is the filter key
 };
+
+// Entries kept per side of a tensor, from its candidate counts.
+__device__ __forceinline__ void wide_kept(const TensorDesc& d, const TensorState& s, uint32_t (&kc)[2], bool& enough, bool& all) {
+    const uint32_t cp = s.cand_cnt[0], cn = s.cand_cnt[1];
+    if (d.flags & kDescSampled) {
+        kc[0] = min(cp, d.kcap); kc[1] = min(cn, d.kcap);
+        enough = cp >= 1u && cn >= 1u && cp <= d.n && cn <= d.n;
+        all = cp <= d.kcap && cn <= d.kcap;
+    } else {
+        kc[0] = kc[1] = d.k;
+        enough = cp >= d.k && cn >= d.k && cp <= d.n && cn <= d.n;
+        all = false;
+    }
+}
 
 __global__ __launch_bounds__(kWideThreads) void k_wide_count(
         const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ wide_ids,
@@ -50,7 +65,12 @@ __global__ __launch_bounds__(kWideThreads) void k_wide_count(
     if (pass > 0 && !ws[w].ok) return;
     const TensorDesc d = desc[t];
     const uint32_t cnt[2] = {min(st[t].cand_cnt[0], d.n), min(st[t].cand_cnt[1], d.n)};
-    if (cnt[0] < d.k || cnt[1] < d.k) return;          // k_wide_pick reports it
+    {
+        uint32_t kc[2];
+        bool enough, all;
+        wide_kept(d, st[t], kc, enough, all);
+        if (!enough || all) return;                    // k_wide_pick reports it / nothing to select
+    }
     for (int i = tid; i < 2 * kWindow; i += kWideThreads) (&hist[0][0])[i] = 0u;
     __syncthreads();
 #pragma unroll
@@ -91,24 +111,28 @@ __global__ __launch_bounds__(kSelThreads) void k_wide_pick(
     const int t = (int)wide_ids[w];
     const TensorDesc d = desc[t];
     uint32_t* __restrict__ g = whist + (size_t)w * 2 * kWindow;
+    uint32_t kc[2];
+    bool enough, all;
+    wide_kept(d, st[t], kc, enough, all);
     if (pass == 0) {
-        const uint32_t cp = st[t].cand_cnt[0], cn = st[t].cand_cnt[1];
-        const bool enough = cp >= d.k && cn >= d.k && cp <= d.n && cn <= d.n;
         if (tid == 0) {
             WideState z;
             z.ok = enough ? 1u : 0u;
-            z.prefix[0] = z.prefix[1] = 0u; z.need[0] = z.need[1] = d.k;
-            z.tau[0] = z.tau[1] = 0u; z.itau[0] = z.itau[1] = 0xFFFFFFFFu;
-            z.ties[0] = z.ties[1] = 0u; z.tie_cnt[0] = z.tie_cnt[1] = 0u; z.pad = 0u;
+            z.prefix[0] = z.prefix[1] = 0u; z.need[0] = kc[0]; z.need[1] = kc[1];
+            z.tau[0] = all ? st[t].lo_key[0] : 0u; z.tau[1] = all ? st[t].lo_key[1] : 0u;
+            z.itau[0] = z.itau[1] = 0xFFFFFFFFu;
+            z.ties[0] = z.ties[1] = 0u; z.tie_cnt[0] = z.tie_cnt[1] = 0u;
+            z.kc[0] = kc[0]; z.kc[1] = kc[1]; z.all = all ? 1u : 0u;
             ws[w] = z;
         }
         if (!enough) return;                           // k_select flags the tensor for the histogram path
     } else if (!ws[w].ok) {
         return;
     }
+    if (all) return;                                   // nothing to select: no histogram was counted
     for (int i = tid; i < 2 * kWindow; i += kSelThreads) { (&hist[0][0])[i] = g[i]; g[i] = 0u; }
     __syncthreads();
-    uint32_t need[2] = {d.k, d.k};
+    uint32_t need[2] = {kc[0], kc[1]};
     if (pass > 0) { need[0] = ws[w].need[0]; need[1] = ws[w].need[1]; }
     const bool both[2] = {true, true};
     uint32_t digit[2];
@@ -148,7 +172,7 @@ __global__ __launch_bounds__(kWideThreads) void k_wide_ties(
         WideState* __restrict__ ws, uint32_t* __restrict__ wtie) {
     const int w = blockIdx.y, tid = threadIdx.x;
     const int t = (int)wide_ids[w];
-    if (!ws[w].ok) return;
+    if (!ws[w].ok || ws[w].all) return;
     const TensorDesc d = desc[t];
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
@@ -177,7 +201,7 @@ __global__ __launch_bounds__(kSelThreads) void k_wide_rank(const uint32_t* __res
     __shared__ uint32_t hit[2];
     const int w = blockIdx.x, tid = threadIdx.x;
     (void)wide_ids;
-    if (!ws[w].ok) return;
+    if (!ws[w].ok || ws[w].all) return;
     bool ok = true;
     for (int s = 0; s < 2; ++s) {
         const uint32_t need = ws[w].need[s], ties = ws[w].ties[s];
@@ -274,8 +298,12 @@ __global__ __launch_bounds__(128) void k_wide_decide(
     if (!ok || tid != 0) return;
     const uint32_t k = desc[t].k;
     const double Sp = S[0], Sn = S[1];
-    const int chosen = (Sp >= Sn) ? 0 : 1;
-    const float mu32 = (float)((chosen ? Sn : Sp) / (double)k);
+    const uint32_t kc[2] = {ws[w].kc[0], ws[w].kc[1]};
+    // mu+ >= mu-; with equal counts that is S+ >= S-
+    const int chosen = (desc[t].flags & kDescSampled) ? ((Sp / (double)kc[0] >= Sn / (double)kc[1]) ? 0 : 1)
+                                                      : ((Sp >= Sn) ? 0 : 1);
+    const float mu32 = (float)((chosen ? Sn : Sp) / (double)kc[chosen]);
+    st[t].kc[0] = kc[0]; st[t].kc[1] = kc[1];
     st[t].tau[0] = ws[w].tau[0]; st[t].tau[1] = ws[w].tau[1];
     st[t].itau[0] = ws[w].itau[0]; st[t].itau[1] = ws[w].itau[1];
     st[t].S[0] = Sp; st[t].S[1] = Sn;

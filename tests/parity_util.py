@@ -23,11 +23,14 @@ def mask_to_positions(words: torch.Tensor, n: int) -> np.ndarray:
 class DeviceRun:
     """One sbc context plus device copies of a model's update and residual."""
 
-    def __init__(self, sizes: Sequence[int], device: str = "cuda:0", slack: int = 0):
+    def __init__(self, sizes: Sequence[int], device: str = "cuda:0", slack: int = 0, sampled: bool = False):
         self.sizes = [int(s) for s in sizes]
         self.device = device
+        self.sampled = sampled
         dev_index = 0 if device == "cpu" else torch.device(device).index or 0
         self.ctx = sbc.sbc_create(dev_index, sum(self.sizes) + slack, len(self.sizes))
+        if sampled:
+            sbc.sbc_set_option(self.ctx, sbc.SBC_OPT_SAMPLED_THRESHOLD, 1)
         self.R = [torch.zeros(n, dtype=torch.float32, device=device) for n in self.sizes]
 
     def close(self):
@@ -41,9 +44,12 @@ class DeviceRun:
     def __exit__(self, *exc):
         self.close()
 
+    def msg_bound(self, p: float) -> int:
+        return (sbc.sbc_msg_bound_sampled if self.sampled else sbc.sbc_msg_bound)(self.sizes, p)
+
     def compress(self, dWs: Sequence[np.ndarray], p: float):
         d_dW = [torch.from_numpy(np.ascontiguousarray(x)).to(self.device) for x in dWs]
-        bound = sbc.sbc_msg_bound(self.sizes, p)
+        bound = self.msg_bound(p)
         assert bound > 0
         msg = torch.full((bound + 64,), 0xAB, dtype=torch.uint8, device=self.device)
         nbytes = sbc.sbc_compress(self.ctx, d_dW, self.R, p, msg)
@@ -53,14 +59,14 @@ class DeviceRun:
 def check_round(run: DeviceRun, dWs: Sequence[np.ndarray], R_before: Sequence[np.ndarray], p: float,
                 check_decode: bool = True) -> List[o.TensorResult]:
     """One round: HIP compress vs oracle compress.  Returns the oracle results."""
-    results = o.compress_model(dWs, R_before, p)
+    results = o.compress_model(dWs, R_before, p, sampled=run.sampled)
     want_msg = o.build_message(results)
     msg, nbytes = run.compress(dWs, p)
     got_msg = bytes(msg[:nbytes].cpu().numpy().tobytes())
     T = len(results)
 
     # --- per-tensor table and statistics
-    assert nbytes <= sbc.sbc_msg_bound(run.sizes, p)
+    assert nbytes <= run.msg_bound(p)
     assert got_msg[:32] == want_msg[:32], "message header differs"
     for t, res in enumerate(results):
         mu_g, nnz_g, bl_g, wo_g = struct.unpack_from("<fIQQ", got_msg, 32 + 24 * t)
@@ -69,7 +75,8 @@ def check_round(run: DeviceRun, dWs: Sequence[np.ndarray], R_before: Sequence[np
         assert side == res.side, "tensor %d: side %d, oracle %d (mu+ %r mu- %r)" % (t, side, res.side, res.mu_pos, res.mu_neg)
         assert abs(mu_pos - res.mu_pos) <= REL_TOL * abs(res.mu_pos), (t, mu_pos, res.mu_pos)
         assert abs(mu_neg - res.mu_neg) <= REL_TOL * abs(res.mu_neg), (t, mu_neg, res.mu_neg)
-        assert nnz == nnz_g == res.k, (t, nnz, nnz_g, res.k)
+        assert nnz == nnz_g == len(res.kept), (t, nnz, nnz_g, len(res.kept))
+        assert run.sampled or nnz == res.k
         # mask (bit exact)
         kept = mask_to_positions(sbc.sbc_last_mask(run.ctx, t, res.n), res.n)
         assert np.array_equal(kept, res.kept), "tensor %d: mask differs" % t
@@ -88,7 +95,6 @@ def check_round(run: DeviceRun, dWs: Sequence[np.ndarray], R_before: Sequence[np
     # --- bitstream and whole message (bit exact)
     assert got_msg == want_msg, "message bytes differ"
     # the cleared-but-unused tail of the payload and the guard bytes behind the bound
-    bound = sbc.sbc_msg_bound(run.sizes, p)
     assert (msg[nbytes:].cpu().numpy() == 0xAB).all(), "wrote past the message"
 
     if check_decode:

@@ -87,3 +87,22 @@ def test_strerror_and_null_arguments():
     ctx = ctypes.c_void_p()
     assert lib.sbc_create(ctypes.byref(ctx), 0, 0, 1) == sbc.SBC_EINVAL
     lib.sbc_destroy(None)
+
+
+def test_msg_bound_sampled_covers_the_cap():
+    rng = np.random.default_rng(2)
+    for p in (0.3, 0.05, 0.01, 0.001):
+        sizes = [int(v) for v in rng.integers(1, 5000, 6)] + [40000]
+        bound = sbc.sbc_msg_bound_sampled(sizes, p)
+        assert bound >= sbc.sbc_msg_bound(sizes, p)
+        b = o.golomb_bstar(p)
+        worst = 32 + 24 * len(sizes)
+        for n in sizes:
+            cap = o.sampled_cap(n, o.num_kept(n, p))
+            worst += 4 * ((len(o.golomb_encode(np.arange(n - cap, n), b)) + 31) // 32)
+        assert worst <= bound
+        # tie-heavy data reaches the cap
+        dWs = [synth.palette_update(n, tensor=i) for i, n in enumerate(sizes)]
+        msg = o.build_message(o.compress_model(dWs, [np.zeros_like(d) for d in dWs], p, sampled=True))
+        assert len(msg) <= bound
+    assert sbc.sbc_msg_bound_sampled([10], 0.0) == 0 and sbc.sbc_msg_bound_sampled([0], 0.1) == 0
