@@ -164,10 +164,22 @@ int sbc_decompress_accumulate(sbc_ctx* ctx, void* hip_stream,
  *       lowest index); mu+ and mu- are means over each side's own count.  The message buffer
  *       must hold sbc_msg_bound_sampled() bytes; set the option on a decoding context as well,
  *       so that it reserves for the longer streams.  The options FORCE_EXACT_PATH and
- *       CARRY_FILTER_KEYS are ignored while it is set. */
+ *       CARRY_FILTER_KEYS are ignored while it is set.
+ *   SBC_OPT_DEFER_DECODE_STATUS (0/1, default 0)  1 makes sbc_decompress_accumulate return as
+ *       soon as its kernels are enqueued (SBC_OK unless an argument is bad), so that a server can
+ *       decode the messages of all clients back to back without waiting for each; validation
+ *       failures of those calls are collected on the device and reported by sbc_decode_status().
+ *       Every message buffer must stay unchanged until the stream has passed its call.  The
+ *       option cannot be changed while a status is outstanding (SBC_EINVAL). */
 enum { SBC_OPT_FORCE_EXACT_PATH = 1, SBC_OPT_CARRY_FILTER_KEYS = 2, SBC_OPT_WIDE_MIN_KEPT = 3,
-       SBC_OPT_SAMPLED_THRESHOLD = 4 };
+       SBC_OPT_SAMPLED_THRESHOLD = 4, SBC_OPT_DEFER_DECODE_STATUS = 5 };
 int sbc_set_option(sbc_ctx* ctx, int option, int value);
+
+/* With SBC_OPT_DEFER_DECODE_STATUS: waits for hip_stream (the stream the deferred
+ * sbc_decompress_accumulate calls were enqueued on) and returns SBC_OK if every such call since
+ * the previous sbc_decode_status passed validation, else the error (SBC_ECORRUPT, SBC_EHIP); the
+ * collected status starts afresh.  SBC_OK at once if nothing is outstanding. */
+int sbc_decode_status(sbc_ctx* ctx, void* hip_stream);
 
 /* Which routes the most recent successful sbc_compress() took: a bit set of
  * SBC_ROUTE_CARRIED_KEYS (filter keys came from the previous call, no sampling) and

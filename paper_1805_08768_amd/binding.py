@@ -27,6 +27,7 @@ SBC_OPT_FORCE_EXACT_PATH = 1
 SBC_OPT_CARRY_FILTER_KEYS = 2
 SBC_OPT_WIDE_MIN_KEPT = 3
 SBC_OPT_SAMPLED_THRESHOLD = 4
+SBC_OPT_DEFER_DECODE_STATUS = 5
 SBC_ROUTE_CARRIED_KEYS = 1
 SBC_ROUTE_HISTOGRAM = 2
 SBC_ROUTE_WIDE = 4
@@ -35,7 +36,7 @@ EXPORTS = (
     "sbc_create", "sbc_destroy", "sbc_golomb_bstar", "sbc_num_kept", "sbc_msg_bound", "sbc_msg_bound_sampled",
     "sbc_compress", "sbc_decompress_accumulate", "sbc_last_tensor_stats", "sbc_last_mask",
     "sbc_profile_enable", "sbc_profile_level", "sbc_profile_read", "sbc_copy_baseline", "sbc_set_option",
-    "sbc_last_route", "sbc_strerror",
+    "sbc_last_route", "sbc_strerror", "sbc_decode_status",
 )
 
 
@@ -92,6 +93,8 @@ def load() -> ctypes.CDLL:
     lib.sbc_set_option.restype = ctypes.c_int
     lib.sbc_last_route.argtypes = [vp]
     lib.sbc_last_route.restype = ctypes.c_int
+    lib.sbc_decode_status.argtypes = [vp, vp]
+    lib.sbc_decode_status.restype = ctypes.c_int
     lib.sbc_strerror.argtypes = [ctypes.c_int]
     lib.sbc_strerror.restype = ctypes.c_char_p
     _lib = lib
@@ -225,6 +228,14 @@ def sbc_decompress_accumulate(ctx, msg: torch.Tensor, msg_bytes: int, p: float, 
                                           len(out.tensors), p, scale, out.ptrs)
     if rc != SBC_OK:
         raise SbcError(rc, "sbc_decompress_accumulate")
+
+
+def sbc_decode_status(ctx, stream=None) -> None:
+    """With SBC_OPT_DEFER_DECODE_STATUS: waits for the stream and raises if any deferred
+    sbc_decompress_accumulate call since the previous check failed validation."""
+    rc = load().sbc_decode_status(ctx, _stream_handle(stream))
+    if rc != SBC_OK:
+        raise SbcError(rc, "sbc_decode_status")
 
 
 def sbc_last_tensor_stats(ctx, tensor: int) -> Tuple[float, float, int, int, int]:

@@ -64,7 +64,8 @@ struct sbc_ctx {
     ChunkSummary* d_sum = nullptr;
     uint32_t* d_prev_end = nullptr;
     uint64_t* d_bitoff = nullptr;
-    ResultBlock* d_result = nullptr;      // two for compress, two for decode, used in turn
+    ResultBlock* d_result = nullptr;      // two for compress, two for decode, used in turn; [4] collects the
+                                          // errors of decode calls whose status is deferred, [5] is a spare
     // grid-wide selection
     uint32_t* d_wide_ids = nullptr;
     WideState* d_wide_state = nullptr;
@@ -116,6 +117,9 @@ struct sbc_ctx {
     int force_exact = 0;
     int carry_keys = 0;
     int sampled = 0;                      // subsampled variant: the sampled threshold decides what is kept
+    int defer_decode = 0;                 // decode calls return once enqueued; sbc_decode_status reports
+    bool deferred_pending = false;        // some deferred decode has not been waited for yet
+    bool deferred_dirty = true;           // block [4] must be cleared before the next deferred decode
     uint32_t wide_min_kept = kWideMinKept;
 
     // filter keys carried over from the previous successful call (same tensor sizes, same p)
@@ -298,7 +302,7 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     ok = ok && dev_alloc(&c->d_sum, (size_t)c->max_chunks) == hipSuccess;
     ok = ok && dev_alloc(&c->d_prev_end, (size_t)c->max_chunks) == hipSuccess;
     ok = ok && dev_alloc(&c->d_bitoff, (size_t)c->max_chunks) == hipSuccess;
-    ok = ok && dev_alloc(&c->d_result, 4) == hipSuccess;      // two for compress, two for decode, used in turn
+    ok = ok && dev_alloc(&c->d_result, 6) == hipSuccess;
     ok = ok && dev_alloc(&c->d_dec, T) == hipSuccess;
     // tile decode: a stream of w words has w/2 segments; every stream is rounded up to whole tiles
     c->dec_seg_cap = c->stage_cap / 2 + (uint64_t)(kMaxWideDec + 1) * kDecThreads;
@@ -364,6 +368,10 @@ int sbc_set_option(sbc_ctx* c, int option, int value) {
             c->cache_valid = false;                    // the capacities of the plan depend on it
             c->dev_dec_valid = false;
             c->hist_valid = false;
+            return SBC_OK;
+        case SBC_OPT_DEFER_DECODE_STATUS:
+            if (c->deferred_pending) return SBC_EINVAL;    // collect the outstanding status first
+            c->defer_decode = value ? 1 : 0;
             return SBC_OK;
         case SBC_OPT_WIDE_MIN_KEPT:
             if (value < 0) return SBC_EINVAL;
@@ -705,6 +713,11 @@ int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, siz
     }
     DeviceGuard guard(c->device);
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    const bool deferred = c->defer_decode != 0;
+    if (!same && c->deferred_pending) {
+        // the pinned tables below may still be read by an upload of an earlier deferred call
+        if (hipStreamSynchronize(stream) != hipSuccess) { (void)hipGetLastError(); return SBC_EHIP; }
+    }
     if (!same) {
         // Streams of tensors that keep very many entries are decoded tile by tile by many
         // workgroups, as far as the scratch arrays reach; all others by one workgroup each.
@@ -734,15 +747,28 @@ int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, siz
         }
         c->dev_dec_T = T;
     }
-    // the decode kernel leaves the other of its two result blocks clean for the next call
-    if (c->dec_result_dirty) {                        // after an error, or on the first call
-        hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(c->d_result + 2),
-                           (uint64_t)(2 * sizeof(ResultBlock) / 4));
+    // the decode kernel leaves the other of its two result blocks clean for the next call; calls
+    // whose status is deferred all raise their error bits in block [4] and clear the spare
+    ResultBlock* res_dec;
+    ResultBlock* res_dec_next;
+    if (deferred) {
+        if (c->deferred_dirty) {
+            hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(c->d_result + 4),
+                               (uint64_t)(sizeof(ResultBlock) / 4));
+            c->deferred_dirty = false;
+        }
+        res_dec = c->d_result + 4;
+        res_dec_next = c->d_result + 5;
+    } else {
+        if (c->dec_result_dirty) {                    // after an error, or on the first call
+            hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(c->d_result + 2),
+                               (uint64_t)(2 * sizeof(ResultBlock) / 4));
+        }
+        c->dec_result_dirty = true;                   // until this call has completed normally
+        res_dec = c->d_result + 2 + c->dec_result_idx;
+        res_dec_next = c->d_result + 2 + (c->dec_result_idx ^ 1);
+        c->dec_result_idx ^= 1;
     }
-    c->dec_result_dirty = true;                       // until this call has completed normally
-    ResultBlock* const res_dec = c->d_result + 2 + c->dec_result_idx;
-    ResultBlock* const res_dec_next = c->d_result + 2 + (c->dec_result_idx ^ 1);
-    c->dec_result_idx ^= 1;
     SBC_HOST_TS(9);
     hipLaunchKernelGGL(k_decode_accumulate, dim3(T), dim3(kDecThreads), 0, stream,
                        static_cast<const uint8_t*>(msg), (unsigned long long)msg_bytes, c->d_dec, T, b, scale,
@@ -765,6 +791,12 @@ int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, siz
     }
     SBC_HOST_TS(10);
     if (hipGetLastError() != hipSuccess) return SBC_EHIP;
+    if (deferred) {
+        // (the uploads above precede every later kernel on this stream)
+        c->deferred_pending = true;
+        c->dev_dec_valid = true;
+        return SBC_OK;
+    }
     if (hipMemcpyAsync(c->h_result, res_dec, sizeof(ResultBlock), hipMemcpyDeviceToHost, stream) != hipSuccess ||
         hipStreamSynchronize(stream) != hipSuccess) {
         (void)hipGetLastError();
@@ -773,6 +805,21 @@ int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, siz
     SBC_HOST_TS(11);
     c->dev_dec_valid = true;
     if (c->h_result->err == 0u) c->dec_result_dirty = false;
+    return status_of_err(c->h_result->err);
+}
+
+int sbc_decode_status(sbc_ctx* c, void* hip_stream) {
+    if (!c) return SBC_EINVAL;
+    if (!c->deferred_pending) return SBC_OK;
+    DeviceGuard guard(c->device);
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    c->deferred_pending = false;
+    c->deferred_dirty = true;
+    if (hipMemcpyAsync(c->h_result, c->d_result + 4, sizeof(ResultBlock), hipMemcpyDeviceToHost, stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess) {
+        (void)hipGetLastError();
+        return SBC_EHIP;
+    }
     return status_of_err(c->h_result->err);
 }
 

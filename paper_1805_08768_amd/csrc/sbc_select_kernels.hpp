@@ -78,6 +78,7 @@ struct SelectShared {
     uint32_t scratch[kSelThreads / 64];
     unsigned long long scratch64[kSelThreads / 64];
     long long fast_sum[2][kSelThreads / 64];             // per-wavefront partial sums of the common-scale path
+    uint32_t any_slow;                                   // some kept entry does not fit the common-scale sum
     double S[2];
 };
 
@@ -160,10 +161,11 @@ __device__ __forceinline__ bool select_both(SelectShared& sh, const CandLists& l
 // `common` is set, every kept entry has the sign of its side and a biased exponent of at least
 // e_ref, and there are at most 2^15 of them: an entry whose exponent exceeds e_ref by at most
 // 24 is added, shifted to the scale of e_ref, to a 64-bit integer the thread keeps in a
-// register (24 + 24 + 15 bits at most); the function returns that integer.  Every other entry
-// goes to acc[S][exponent], exact integers per fp32 exponent in LDS; a thread first adds up
-// runs of equal exponent in a register.
-template <int S>
+// register (24 + 24 + 15 bits at most).  Every other entry goes to acc[S][exponent], exact
+// integers per fp32 exponent in LDS; a thread first adds up runs of equal exponent in a
+// register.  SLOW = false: only the first part; returns the integer and raises sh.any_slow if
+// an entry belongs to the second part.  SLOW = true: only the second part.
+template <int S, bool SLOW>
 __device__ __forceinline__ long long exponent_sums(SelectShared& sh, const CandLists& l, uint32_t tk, uint32_t ti,
                                                    bool common, uint32_t e_ref) {
     uint32_t cur_ex = 0u;
@@ -174,10 +176,13 @@ __device__ __forceinline__ long long exponent_sums(SelectShared& sh, const CandL
             uint32_t ex = (u >> 23) & 0xFFu;
             long long m = (long long)(ex ? ((u & 0x7FFFFFu) | 0x800000u) : (u & 0x7FFFFFu));
             if (ex == 0u) ex = 1u;
-            if (common && ex >= e_ref && ex - e_ref <= 24u) {
-                scaled += m << (ex - e_ref);
+            const bool fits = common && ex >= e_ref && ex - e_ref <= 24u;
+            if (!SLOW) {
+                if (fits) scaled += m << (ex - e_ref);
+                else sh.any_slow = 1u;
                 return;
             }
+            if (fits) return;
             if (((u >> 31) != 0u) != (S != 0)) m = -m;           // the negative side sums -A
             if (ex != cur_ex) {
                 if (cur != 0ll) atomicAdd(reinterpret_cast<unsigned long long*>(&sh.acc[S][cur_ex]), (unsigned long long)cur);
@@ -201,6 +206,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     __shared__ SelectShared sh;
     SBC_TS(1, 0);
     const int t = (int)order[blockIdx.x], tid = threadIdx.x;
+    if (tid == 0) sh.any_slow = 0u;
     if (pass == 1 && !(st[t].flags & kStExact)) return;
     const TensorDesc d = desc[t];
     if (pass == 0 && (d.flags & kDescWide) && (st[t].flags & kStWideDone)) return;   // done by the grid-wide kernels
@@ -242,26 +248,36 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     bool ok = true;
     for (int i = tid; i < 2 * kWindow; i += kSelThreads) (&sh.whist[0][0])[i] = 0u;
     __syncthreads();
+    auto count = [&](int s, const uint2& e) {
+        const uint32_t v = e.x >> kWinShift;
+        const uint32_t o = v >= wbase[s] ? v - wbase[s] : 0u;   // (no candidate lies below its filter key)
+        atomicAdd(&sh.whist[s][o < (uint32_t)(kWindow - 1) ? o : (uint32_t)(kWindow - 1)], 1u);
+    };
+    if (list.staged) {
+        // every load of both lists is issued before the first entry is used: the lists were written
+        // by other compute units a moment ago, and each dependent round trip costs a microsecond
+        constexpr int PER = kSelLds / kSelThreads;      // 8
+        uint2 e[2][PER];
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        const uint32_t wb = wbase[s];
-        uint32_t* h = sh.whist[s];
-        auto count = [&](const uint2& e) {
-            const uint32_t v = e.x >> kWinShift;
-            const uint32_t o = v >= wb ? v - wb : 0u;   // (no candidate lies below its filter key)
-            atomicAdd(&h[o < (uint32_t)(kWindow - 1) ? o : (uint32_t)(kWindow - 1)], 1u);
-        };
-        if (list.staged) {
+        for (int s = 0; s < 2; ++s) {
             const uint2* __restrict__ g = list.g[s];
-#pragma unroll 4
-            for (uint32_t i = tid; i < list.cnt[s]; i += kSelThreads) { const uint2 e = g[i]; sh.cand[s][i] = e; if (pick) count(e); }
-        } else if (!pick) {
-            // nothing to count
-        } else if (s == 0) {
-            sweep<0>(sh, list, count);
-        } else {
-            sweep<1>(sh, list, count);
+#pragma unroll
+            for (int j = 0; j < PER; ++j) {
+                const uint32_t i = (uint32_t)j * kSelThreads + tid;
+                e[s][j] = g[i < list.cnt[s] ? i : 0u];
+            }
         }
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+#pragma unroll
+            for (int j = 0; j < PER; ++j) {
+                const uint32_t i = (uint32_t)j * kSelThreads + tid;
+                if (i < list.cnt[s]) { sh.cand[s][i] = e[s][j]; if (pick) count(s, e[s][j]); }
+            }
+        }
+    } else if (pick) {
+        sweep<0>(sh, list, [&](const uint2& e) { count(0, e); });
+        sweep<1>(sh, list, [&](const uint2& e) { count(1, e); });
     }
     __syncthreads();
     SBC_TS(1, 2);                                     // staged, leading bits counted
@@ -375,10 +391,8 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     }
 
     SBC_TS(1, 4);                                     // tau and tie index known
-    // S+ and S-: exact integer accumulation per fp32 exponent; a thread first adds up runs of
-    // equal exponent in a register
-    for (int i = tid; i < 512; i += kSelThreads) (&sh.acc[0][0])[i] = 0ll;
-    __syncthreads();
+    // S+ and S-.  Usual case: every kept entry of a side fits one common-scale 64-bit integer sum;
+    // the per-exponent accumulators are brought in only for what does not.
     // common-scale path: the k-th entry of a side has the side's sign (so have all kept ones)
     const bool common[2] = {kc[0] <= 32768u && tau[0] > 0x80000000u, kc[1] <= 32768u && tau[1] >= 0x80000000u};
     uint32_t e_ref[2];
@@ -389,8 +403,8 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     }
     {
         long long part[2];
-        part[0] = exponent_sums<0>(sh, list, tau[0], itau[0], common[0], e_ref[0]);
-        part[1] = exponent_sums<1>(sh, list, tau[1], itau[1], common[1], e_ref[1]);
+        part[0] = common[0] ? exponent_sums<0, false>(sh, list, tau[0], itau[0], true, e_ref[0]) : 0ll;
+        part[1] = common[1] ? exponent_sums<1, false>(sh, list, tau[1], itau[1], true, e_ref[1]) : 0ll;
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
 #pragma unroll
@@ -399,28 +413,40 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         }
     }
     __syncthreads();
-    if (tid < 128) {
-        // fixed order: lane l of wavefront s adds exponents 4l..4l+3 ascending, then a fixed shuffle
-        // tree; the common-scale integer is added last
-        const int s = tid >> 6, lane = tid & 63;
-        double v = 0.0;
+    double Ssum[2];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int ex = 4 * lane + j;
-            v += ldexp((double)sh.acc[s][ex], ex - 150);
-        }
+    for (int s = 0; s < 2; ++s) {
+        long long total = 0ll;
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
-        if (lane == 0) {
-            long long total = 0ll;
-#pragma unroll
-            for (int w = 0; w < kSelThreads / 64; ++w) total += sh.fast_sum[s][w];
-            sh.S[s] = v + ldexp((double)total, (int)e_ref[s] - 150);
-        }
+        for (int w = 0; w < kSelThreads / 64; ++w) total += sh.fast_sum[s][w];
+        Ssum[s] = ldexp((double)total, (int)e_ref[s] - 150);
     }
-    __syncthreads();
+    if (!common[0] || !common[1] || sh.any_slow) {       // uniform
+        for (int i = tid; i < 512; i += kSelThreads) (&sh.acc[0][0])[i] = 0ll;
+        __syncthreads();
+        (void)exponent_sums<0, true>(sh, list, tau[0], itau[0], common[0], e_ref[0]);
+        (void)exponent_sums<1, true>(sh, list, tau[1], itau[1], common[1], e_ref[1]);
+        __syncthreads();
+        if (tid < 128) {
+            // fixed order: lane l of wavefront s adds exponents 4l..4l+3 ascending, then a fixed
+            // shuffle tree; the common-scale integer is added last
+            const int s = tid >> 6, lane = tid & 63;
+            double v = 0.0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int ex = 4 * lane + j;
+                v += ldexp((double)sh.acc[s][ex], ex - 150);
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
+            if (lane == 0) sh.S[s] = v;
+        }
+        __syncthreads();
+        Ssum[0] = sh.S[0] + Ssum[0];
+        Ssum[1] = sh.S[1] + Ssum[1];
+    }
     SBC_TS(1, 5);                                     // sums done
-    const double Sp = sh.S[0], Sn = sh.S[1];
+    const double Sp = Ssum[0], Sn = Ssum[1];
     // mu+ >= mu-; with equal counts that is S+ >= S-
     const int chosen = sampled ? ((Sp / (double)kc[0] >= Sn / (double)kc[1]) ? 0 : 1) : ((Sp >= Sn) ? 0 : 1);
     const uint32_t kk = kc[chosen];                   // entries this tensor sends

@@ -63,6 +63,8 @@ class Server:
         self.p = float(p)
         index = torch.device(device).index or 0
         self.ctx = sbc.sbc_create(index, sum(self.sizes), len(self.sizes))
+        # the messages of a round are decoded back to back; one status check at the end
+        sbc.sbc_set_option(self.ctx, sbc.SBC_OPT_DEFER_DECODE_STATUS, 1)
         self.acc = [torch.zeros(n, dtype=torch.float32, device=device) for n in self.sizes]
         self._acc_list = sbc.TensorList(self.acc)
 
@@ -73,6 +75,7 @@ class Server:
         scale = 1.0 / len(messages)
         for msg, nbytes in messages:
             sbc.sbc_decompress_accumulate(self.ctx, msg, nbytes, self.p, scale, self._acc_list)
+        sbc.sbc_decode_status(self.ctx)
         return self.acc
 
     def close(self):

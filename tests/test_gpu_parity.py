@@ -502,3 +502,53 @@ def test_tensor_of_many_chunks():
             R = [x.R_new for x in res]
         dWs = [synth.palette_update(n), synth.palette_update(70000, tensor=1)]
         check_round(run, dWs, R, 0.001, check_decode=False)
+
+
+def test_deferred_decode_status():
+    """SBC_OPT_DEFER_DECODE_STATUS: decode calls only enqueue; results equal the waiting calls', a
+    corrupt message among good ones is reported by sbc_decode_status, and the status starts afresh."""
+    sizes = [40000, 64, 9000]
+    p = 0.01
+    clients = 4
+    msgs, want = [], [np.zeros(n, np.float32) for n in sizes]
+    with DeviceRun(sizes) as run:
+        for c in range(clients):
+            for r in run.R:
+                r.zero_()
+            dWs = synth.small_model_update(sizes, client=c)
+            msg, nbytes = run.compress(dWs, p)
+            msgs.append((msg, nbytes))
+            res = o.compress_model(dWs, [np.zeros_like(d) for d in dWs], p)
+            o.decode_accumulate(o.build_message(res), sizes, 1.0 / clients, want)
+        sbc.sbc_set_option(run.ctx, sbc.SBC_OPT_DEFER_DECODE_STATUS, 1)
+        sbc.sbc_decode_status(run.ctx)                                   # nothing outstanding: fine
+        outs = [torch.zeros(n, dtype=torch.float32, device="cuda:0") for n in sizes]
+        for msg, nbytes in msgs:
+            sbc.sbc_decompress_accumulate(run.ctx, msg, nbytes, p, 1.0 / clients, outs)
+        with pytest.raises(sbc.SbcError):                                # not while a status is outstanding
+            sbc.sbc_set_option(run.ctx, sbc.SBC_OPT_DEFER_DECODE_STATUS, 0)
+        sbc.sbc_decode_status(run.ctx)
+        for t in range(len(sizes)):
+            assert np.array_equal(outs[t].cpu().numpy(), want[t]), "tensor %d: deferred decode" % t
+        # one corrupt message between good ones
+        bad = msgs[1][0].clone()
+        bad[32 + 4] += 1                                                 # nnz off by one
+        guard = [torch.zeros(n + 64, dtype=torch.float32, device="cuda:0") for n in sizes]
+        outs = [g[32:32 + n] for g, n in zip(guard, sizes)]
+        sbc.sbc_decompress_accumulate(run.ctx, msgs[0][0], msgs[0][1], p, 1.0, outs)
+        sbc.sbc_decompress_accumulate(run.ctx, bad, msgs[1][1], p, 1.0, outs)
+        sbc.sbc_decompress_accumulate(run.ctx, msgs[2][0], msgs[2][1], p, 1.0, outs)
+        with pytest.raises(sbc.SbcError) as e:
+            sbc.sbc_decode_status(run.ctx)
+        assert e.value.code == sbc.SBC_ECORRUPT
+        for g, n in zip(guard, sizes):
+            assert not g[:32].any() and not g[32 + n:].any(), "decode wrote out of bounds"
+        # the status starts afresh, and other output buffers are picked up
+        outs2 = [torch.zeros(n, dtype=torch.float32, device="cuda:0") for n in sizes]
+        sbc.sbc_decompress_accumulate(run.ctx, msgs[3][0], msgs[3][1], p, 1.0, outs2)
+        sbc.sbc_decode_status(run.ctx)
+        sbc.sbc_set_option(run.ctx, sbc.SBC_OPT_DEFER_DECODE_STATUS, 0)
+        outs3 = [torch.zeros(n, dtype=torch.float32, device="cuda:0") for n in sizes]
+        sbc.sbc_decompress_accumulate(run.ctx, msgs[3][0], msgs[3][1], p, 1.0, outs3)
+        for a, b in zip(outs2, outs3):
+            assert torch.equal(a, b)
