@@ -58,6 +58,25 @@ __device__ __forceinline__ int exit_state_of(unsigned long long w64, int s, int 
     }
 }
 
+// Exit states of a 64-bit segment for all entry states 0..b at once (b <= 15), as 4-bit fields:
+// field s holds exit_state_of(w64, s, b).  With g(x) the exit state when Alg. 4 is in its unary
+// state at bit x (bit 0 = most significant): g(x) = x - 64 for 64 <= x <= 64 + b, and for x < 64
+// g(x) = g(x + 1) if bit x is a one (one more unary bit), g(x + b + 1) if it is a zero (the code
+// ends b bits later).  The last b + 1 values are kept as the fields of one word while x runs from
+// 63 down to 0: 64 steps without a branch, where walking every entry state separately takes up to
+// b + 1 walks of several steps each.
+__device__ __forceinline__ unsigned long long packed_exits(unsigned long long w64, int b) {
+    unsigned long long g = 0xFEDCBA9876543210ull;           // field j = g(64 + j) = j
+    const int top = 4 * b;
+#pragma unroll
+    for (int i = 0; i < 64; ++i) {                          // x = 63 - i
+        const unsigned long long one = g & 15ull;           // g(x + 1)
+        const unsigned long long zero = (g >> top) & 15ull; // g(x + b + 1)
+        g = (g << 4) | (((w64 >> i) & 1ull) ? one : zero);
+    }
+    return b == 15 ? g : (g & ((1ull << (4 * (b + 1))) - 1ull));
+}
+
 // Transition functions over at most 16 states as 4-bit fields of one word: field s holds f(s).
 __device__ __forceinline__ int apply_packed(unsigned long long f, int s) { return (int)((f >> (4 * s)) & 15ull); }
 // later o earlier
@@ -150,14 +169,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
         if (packed) {
             // ---- exit state per entry state in one word; scan under composition with shuffles
             // inside a wavefront, then the state is walked through the wavefronts' totals ----
-            // (entering with s bits of a remainder left is entering at bit s in the unary state, and
-            // if bit s - 1 is a one that is the same walk as from bit s - 1)
-            int ex = exit_state_of(w64, 0, b);
-            unsigned long long f = (unsigned long long)ex;
-            for (int s = 1; s < S; ++s) {
-                if (!((w64 >> (64 - s)) & 1ull)) ex = exit_state_of(w64, s, b);
-                f |= (unsigned long long)ex << (4 * s);
-            }
+            unsigned long long f = packed_exits(w64, b);
             SBC_TS(2, 3);                             // exit states
 #pragma unroll
             for (int dlt = 1; dlt < 64; dlt <<= 1) {
@@ -385,12 +397,7 @@ __global__ __launch_bounds__(kDecThreads) void k_dec_tile_fn(
     if (tile >= n_tiles) return;
     const int S = b + 1;
     const unsigned long long w64 = stage_tile(si, tile, tile_words);
-    int ex = exit_state_of(w64, 0, b);
-    unsigned long long f = (unsigned long long)ex;
-    for (int s = 1; s < S; ++s) {
-        if (!((w64 >> (64 - s)) & 1ull)) ex = exit_state_of(w64, s, b);
-        f |= (unsigned long long)ex << (4 * s);
-    }
+    unsigned long long f = packed_exits(w64, b);
 #pragma unroll
     for (int dlt = 1; dlt < 64; dlt <<= 1) {
         const unsigned long long o = __shfl_up(f, dlt, 64);
