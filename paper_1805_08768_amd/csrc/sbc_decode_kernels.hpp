@@ -88,8 +88,8 @@ __device__ __forceinline__ unsigned long long compose_packed(unsigned long long 
 
 __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
         const uint8_t* __restrict__ msg, unsigned long long msg_bytes,
-        const DecDesc* __restrict__ dd, int T, int b, float scale, ResultBlock* __restrict__ result,
-        ResultBlock* __restrict__ next_result) {
+        const DecDesc* __restrict__ dd, const uint2* __restrict__ blocks, int T, int b, float scale,
+        ResultBlock* __restrict__ result, ResultBlock* __restrict__ next_result) {
     __shared__ uint8_t fn[2][kStates][kDecThreads];       // transition functions, [state][segment] (b > kPackedMaxB)
     __shared__ unsigned long long wave_fn[kDecThreads / 64];
     __shared__ unsigned long long scratch64[kDecThreads / 64];
@@ -97,9 +97,14 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
     __shared__ uint32_t tile[kTileWords + kTileSlack];   // words past the stream read as ones
 
     const int tid = threadIdx.x;
-    const int t = blockIdx.x;
+    // Workgroup -> (stream, share): every workgroup of a stream decodes all of it, and applies the
+    // updates of the threads whose number is congruent to its share.
+    const uint2 bk = blocks[blockIdx.x];
+    const int t = (int)bk.x;
+    const uint32_t share = bk.y & 0xFFFFu, shares = bk.y >> 16;
+    const bool mine = ((uint32_t)tid % shares) == share;
     SBC_TS(2, 0);
-    if (t == 0 && tid == 0) { next_result->err = 0u; next_result->pad = 0u; next_result->msg_bytes = 0ull; }
+    if (blockIdx.x == 0 && tid == 0) { next_result->err = 0u; next_result->pad = 0u; next_result->msg_bytes = 0ull; }
     if (dd[t].wide) return;
 
     // ---- header and table entry (validated by every workgroup; all threads agree).  The host has
@@ -215,22 +220,37 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
         }
 
         SBC_TS(2, 4);                                 // entry states known
-        // ---- first walk: unary ones, terminators and remainder sum of this segment ----
+        // ---- first walk: unary ones, terminators and remainder sum of this segment.  For the first
+        // eight codes the running counts are kept, so that their positions follow from the scan
+        // below by arithmetic alone and all their loads go out together ----
         uint32_t nU = 0u, nT = 0u;
         unsigned long long sR = 0ull;
-        if (seg < n_seg) {
-            int x = entry;
-            while (x < 64) {
-                const int z = first_zero_from(w64, x);
-                nU += (uint32_t)(z - x);
-                if (z == 64) break;
-                const unsigned long long zpos = seg * 64ull + (unsigned)z;
-                if (zpos + 1ull + (unsigned)b > bit_len) { bad = true; break; }
-                ++nT;
-                sR += read_bits(tile, (uint32_t)(tid * 64 + z + 1), b);
-                x = z + b + 1;
-            }
+        uint32_t lu[8], lr[8];                        // unary ones / remainder sum up to and including code i
+        unsigned long long last_end = 0ull;           // bit after the segment's last code
+        int x = entry;
+        bool open = seg < n_seg;
+        auto walk_code = [&](int& xx) -> bool {       // one step of Alg. 4's outer loop; false: no code ended
+            const int z = first_zero_from(w64, xx);
+            nU += (uint32_t)(z - xx);
+            if (z == 64) { xx = 64; return false; }
+            const unsigned long long zpos = seg * 64ull + (unsigned)z;
+            if (zpos + 1ull + (unsigned)b > bit_len) { bad = true; open = false; return false; }
+            sR += read_bits(tile, (uint32_t)(tid * 64 + z + 1), b);
+            ++nT;
+            last_end = zpos + 1ull + (unsigned)b;
+            xx = z + b + 1;
+            return true;
+        };
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            lu[i] = 0u; lr[i] = 0u;
+            if (open && x < 64 && walk_code(x)) { lu[i] = nU; lr[i] = (uint32_t)sR; }
         }
+        // where the second walk resumes in a segment with more than eight codes (b < 7 only)
+        const int x8 = x;
+        const uint32_t nU8 = nU, nT8 = nT;
+        const unsigned long long sR8 = sR;
+        while (open && x < 64) (void)walk_code(x);
         SBC_TS(2, 5);                                 // first walk
         unsigned long long exU, exT, exR, tile_U, tile_T, tile_R;
         if (packed) {
@@ -247,42 +267,61 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
         }
 
         SBC_TS(2, 6);                                 // offsets known
-        // ---- second walk: place every code whose terminating zero lies in this segment ----
+        // ---- place every code whose terminating zero lies in this segment:
+        //      position = 2^b * (unary ones before its zero) + (remainders up to it) + (codes before it) ----
         if (seg < n_seg && !bad) {
-            unsigned long long U = carry_U + exU, Tn = carry_T + exT, R = carry_R + exR;
-            int x = entry;
-            uint32_t pend[8];                // positions are distinct: update them eight at a time
-            int np = 0;
-            while (x < 64) {
-                const int z = first_zero_from(w64, x);
-                U += (unsigned)(z - x);
-                if (z == 64) break;
-                const unsigned long long zpos = seg * 64ull + (unsigned)z;
-                R += read_bits(tile, (uint32_t)(tid * 64 + z + 1), b);
-                const unsigned long long pos = (U << b) + R + Tn;
-                if (pos >= n || Tn >= nnz) { bad = true; break; }
-                if (Tn == (unsigned long long)nnz - 1ull && zpos + 1ull + (unsigned)b != bit_len) bad = true;
-                pend[np++] = (uint32_t)pos;
-                if (np == 8) {
-                    float v[8];
+            const unsigned long long U0 = carry_U + exU, T0 = carry_T + exT, R0 = carry_R + exR;
+            // the stream's last code ends the stream exactly
+            if (nT > 0u && T0 + nT == (unsigned long long)nnz && last_end != bit_len) bad = true;
+            const uint32_t m = nT < 8u ? nT : 8u;
+            uint32_t pend[8];                         // positions are distinct: update them eight at a time
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) v[i] = out[pend[i]];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) out[pend[i]] = v[i] + addend;
-                    np = 0;
-                }
-                ++Tn;
-                x = z + b + 1;
+            for (int i = 0; i < 8; ++i) {
+                const unsigned long long pos = ((U0 + lu[i]) << b) + R0 + lr[i] + T0 + (unsigned)i;
+                if ((uint32_t)i < m && (pos >= n || T0 + (unsigned)i >= nnz)) bad = true;
+                pend[i] = (uint32_t)pos;
             }
-            SBC_TS(2, 8);
-            if (np) {
+            if (!bad && mine) {
                 float v[8];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) v[i] = i < np ? out[pend[i]] : 0.f;
+                for (int i = 0; i < 8; ++i) v[i] = (uint32_t)i < m ? out[pend[i]] : 0.f;
 #pragma unroll
-                for (int i = 0; i < 8; ++i) if (i < np) out[pend[i]] = v[i] + addend;
-                SBC_TS(2, 9);
+                for (int i = 0; i < 8; ++i) if ((uint32_t)i < m) out[pend[i]] = v[i] + addend;
             }
+            SBC_TS(2, 8);
+            if (nT > 8u && !bad && mine) {
+                // the remaining codes of a segment with more than eight: walked again from the ninth
+                unsigned long long U = U0 + nU8, Tn = T0 + nT8, R = R0 + sR8;
+                int xx = x8;
+                int np = 0;
+                while (xx < 64) {
+                    const int z = first_zero_from(w64, xx);
+                    U += (unsigned)(z - xx);
+                    if (z == 64) break;
+                    R += read_bits(tile, (uint32_t)(tid * 64 + z + 1), b);
+                    const unsigned long long pos = (U << b) + R + Tn;
+                    if (pos >= n || Tn >= nnz) { bad = true; break; }
+                    pend[np++] = (uint32_t)pos;
+                    if (np == 8) {
+                        float v[8];
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) v[i] = out[pend[i]];
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) out[pend[i]] = v[i] + addend;
+                        np = 0;
+                    }
+                    ++Tn;
+                    xx = z + b + 1;
+                }
+                if (np) {
+                    float v[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) v[i] = i < np ? out[pend[i]] : 0.f;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) if (i < np) out[pend[i]] = v[i] + addend;
+                }
+            }
+            SBC_TS(2, 9);
         }
         carry_U += tile_U; carry_T += tile_T; carry_R += tile_R;
         SBC_TS(2, 7);                                 // placed

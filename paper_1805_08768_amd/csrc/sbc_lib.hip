@@ -33,7 +33,10 @@ const char* const kStageNames[kNumStages] = {
 
 constexpr int kDescSlots = 4;             // device copies of the tensor table, keyed by the pointer lists
 constexpr int kMaxWide = 64;              // tensors per call that the grid-wide selection kernels can take
-constexpr int kMaxWideDec = 16;           // streams per call that the tile decoder can take
+constexpr int kMaxWideDec = 16;
+constexpr uint32_t kMaxDecExtra = 512;    // additional decode workgroups that share a stream's scatter
+constexpr uint32_t kDecSharePer = 384;    // kept entries per sharing workgroup
+constexpr uint32_t kDecShareMax = 8;           // streams per call that the tile decoder can take
 constexpr uint32_t kWideMinKept = 8192;   // kept entries per side from which a tensor takes those routes
 
 struct DescSlot {
@@ -75,6 +78,7 @@ struct sbc_ctx {
 
     // ---- device scratch of sbc_decompress_accumulate ----
     DecDesc* d_dec = nullptr;
+    uint2* d_dec_blocks = nullptr;        // workgroup -> (tensor, share | shares << 16) of the decode kernel
     DecWide* d_dec_wide = nullptr;        // long streams decoded tile by tile
     unsigned long long* d_seg_fn = nullptr;
     unsigned long long* d_seg_pack = nullptr;
@@ -91,6 +95,8 @@ struct sbc_ctx {
     uint32_t* h_wide_ids = nullptr;
     ResultBlock* h_result = nullptr;
     DecDesc* h_dec = nullptr;
+    uint2* h_dec_blocks = nullptr;
+    uint32_t n_dec_blocks = 0;
     DecWide* h_dec_wide = nullptr;
     TensorState* h_state = nullptr;
 
@@ -195,7 +201,8 @@ void free_all(sbc_ctx* c) {
     (void)hipFree(c->d_desc); (void)hipFree(c->d_chunk_tensor); (void)hipFree(c->d_order); (void)hipFree(c->d_hist);
     (void)hipFree(c->d_state); (void)hipFree(c->d_cand); (void)hipFree(c->d_bitmap); (void)hipFree(c->d_stage);
     (void)hipFree(c->d_kept); (void)hipFree(c->d_sum); (void)hipFree(c->d_prev_end); (void)hipFree(c->d_bitoff);
-    (void)hipFree(c->d_result); (void)hipFree(c->d_dec);
+    (void)hipFree(c->d_result); (void)hipFree(c->d_dec); (void)hipFree(c->d_dec_blocks);
+    if (c->h_dec_blocks) (void)hipHostFree(c->h_dec_blocks);
     (void)hipFree(c->d_dec_wide); (void)hipFree(c->d_seg_fn); (void)hipFree(c->d_seg_pack); (void)hipFree(c->d_tile_fn);
     (void)hipFree(c->d_tile_sum); (void)hipFree(c->d_tile_off); (void)hipFree(c->d_tile_entry);
     if (c->h_dec_wide) (void)hipHostFree(c->h_dec_wide);
@@ -304,6 +311,8 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     ok = ok && dev_alloc(&c->d_bitoff, (size_t)c->max_chunks) == hipSuccess;
     ok = ok && dev_alloc(&c->d_result, 6) == hipSuccess;
     ok = ok && dev_alloc(&c->d_dec, T) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_dec_blocks, T + kMaxDecExtra) == hipSuccess;
+    ok = ok && host_alloc(&c->h_dec_blocks, T + kMaxDecExtra) == hipSuccess;
     // tile decode: a stream of w words has w/2 segments; every stream is rounded up to whole tiles
     c->dec_seg_cap = c->stage_cap / 2 + (uint64_t)(kMaxWideDec + 1) * kDecThreads;
     c->dec_tile_cap = c->dec_seg_cap / kDecThreads + kMaxWideDec;
@@ -723,10 +732,18 @@ int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, siz
         // workgroups, as far as the scratch arrays reach; all others by one workgroup each.
         int n_wide = 0;
         uint64_t segs = 0, tiles = 0;
+        uint32_t n_blocks = 0, extra = 0;
         for (int t = 0; t < T; ++t) {
             c->h_dec[t].out = out[t]; c->h_dec[t].n = (uint32_t)numel[t]; c->h_dec[t].wide = 0u;
             // (a context that expects messages of the subsampled variant reserves for its cap)
             const int64_t k = cap_of(numel[t], kept_of(numel[t], p), c->sampled != 0);
+            // One workgroup decodes a stream; the scattered updates of a stream with many codes are
+            // shared among several workgroups that each decode it (a compute unit sustains only so
+            // many scattered accesses at a time, and decoding again costs no more time than once).
+            uint32_t shares = (uint32_t)std::min<int64_t>(kDecShareMax, std::max<int64_t>(1, k / kDecSharePer));
+            if (extra + shares - 1u > kMaxDecExtra) shares = 1u;
+            extra += shares - 1u;
+            for (uint32_t sh = 0; sh < shares; ++sh) c->h_dec_blocks[n_blocks++] = make_uint2((uint32_t)t, sh | (shares << 16));
             if (b > kPackedMaxB || (uint64_t)k < (uint64_t)c->wide_min_kept || n_wide >= kMaxWideDec) continue;
             const uint64_t max_seg = (bound_words_of(numel[t], (uint32_t)k, b) + 1) / 2;
             const uint64_t max_tiles = (max_seg + kDecThreads - 1) / kDecThreads;
@@ -736,11 +753,15 @@ int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, siz
             DecWide& w = c->h_dec_wide[n_wide++];
             w.t = (uint32_t)t; w.tile0 = (uint32_t)tiles; w.max_tiles = (uint32_t)max_tiles; w.pad = 0u; w.seg0 = segs;
             c->h_dec[t].wide = 1u;
+            n_blocks -= shares - 1u; extra -= shares - 1u;     // its workgroup of this kernel only returns
+            c->h_dec_blocks[n_blocks - 1u] = make_uint2((uint32_t)t, 1u << 16);
             segs += max_tiles * kDecThreads; tiles += max_tiles;
         }
         c->n_dec_wide = n_wide; c->dec_tiles = (uint32_t)tiles; c->dec_p = p;
+        c->n_dec_blocks = n_blocks;
         c->dev_dec_valid = false;
         if (hipMemcpyAsync(c->d_dec, c->h_dec, sizeof(DecDesc) * T, hipMemcpyHostToDevice, stream) != hipSuccess ||
+            hipMemcpyAsync(c->d_dec_blocks, c->h_dec_blocks, sizeof(uint2) * n_blocks, hipMemcpyHostToDevice, stream) != hipSuccess ||
             (n_wide > 0 && hipMemcpyAsync(c->d_dec_wide, c->h_dec_wide, sizeof(DecWide) * n_wide, hipMemcpyHostToDevice, stream) != hipSuccess)) {
             (void)hipGetLastError();
             return SBC_EHIP;
@@ -770,8 +791,8 @@ int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, siz
         c->dec_result_idx ^= 1;
     }
     SBC_HOST_TS(9);
-    hipLaunchKernelGGL(k_decode_accumulate, dim3(T), dim3(kDecThreads), 0, stream,
-                       static_cast<const uint8_t*>(msg), (unsigned long long)msg_bytes, c->d_dec, T, b, scale,
+    hipLaunchKernelGGL(k_decode_accumulate, dim3(c->n_dec_blocks), dim3(kDecThreads), 0, stream,
+                       static_cast<const uint8_t*>(msg), (unsigned long long)msg_bytes, c->d_dec, c->d_dec_blocks, T, b, scale,
                        res_dec, res_dec_next);
     if (c->n_dec_wide > 0) {
         const uint8_t* m8 = static_cast<const uint8_t*>(msg);
