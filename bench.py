@@ -51,6 +51,9 @@ def main() -> int:
     ap.add_argument("--sampled-threshold", action="store_true",
                     help="set SBC_OPT_SAMPLED_THRESHOLD (the subsampled variant with a noisy amount of sparsity; "
                          "reported for reference, not the benchmark's mode)")
+    ap.add_argument("--clients-in-flight", type=int, default=1,
+                    help="independent clients (own residual, context, stream, message) whose steps overlap; "
+                         "step s belongs to client s mod C")
     ap.add_argument("--workload", default="resnet50", choices=["resnet50", "lstm", "gauss2p20", "student4m", "flat1p5e9"],
                     help="resnet50 (default) is the benchmark workload; the others are reported for reference")
     args = ap.parse_args()
@@ -95,8 +98,7 @@ def main() -> int:
     # a few different updates resident in HBM, used round-robin; the residual carries over
     host_sets = [gen(r) for r in range(n_sets)]
     flat_sets = [torch.from_numpy(np.concatenate(h) if len(h) > 1 else h[0]).to(dev) for h in host_sets]
-    flat_R = torch.zeros(N, dtype=torch.float32, device=dev)
-    flat_out = torch.zeros(N, dtype=torch.float32, device=dev)
+    C = max(1, args.clients_in_flight)
 
     def views(flat):
         out, off = [], 0
@@ -107,55 +109,82 @@ def main() -> int:
 
     # pointer tables are marshalled once, as a training loop with persistent buffers would
     dW_sets = [sbc.TensorList(views(f)) for f in flat_sets]
-    R = sbc.TensorList(views(flat_R))
-    out = sbc.TensorList(views(flat_out))
     bound = (sbc.sbc_msg_bound_sampled if args.sampled_threshold else sbc.sbc_msg_bound)(sizes, P)
-    msg = sbc.MessageBuffer(torch.zeros(bound, dtype=torch.uint8, device=dev))
-    stream = torch.cuda.current_stream().cuda_stream      # raw handle, looked up once
-    ctx = sbc.sbc_create(0, N, T)
-    if args.carry_keys:
-        sbc.sbc_set_option(ctx, sbc.SBC_OPT_CARRY_FILTER_KEYS, 1)
-    if args.sampled_threshold:
-        sbc.sbc_set_option(ctx, sbc.SBC_OPT_SAMPLED_THRESHOLD, 1)
     scale = 1.0 / 32.0
 
-    # The step: the client call (waits for its result: the message size is needed on the host) and
-    # the server call with its status deferred, as a server decodes the messages of a round back to
-    # back; the status of all decodes is collected once, inside the timed region.
-    sbc.sbc_set_option(ctx, sbc.SBC_OPT_DEFER_DECODE_STATUS, 1)
+    class Client:
+        """One client of Alg. 1 with its server-side accumulator: residual, message buffer, context
+        and stream of its own (the updates it compresses are shared, read-only)."""
 
-    def step(i):
-        nbytes = sbc.sbc_compress(ctx, dW_sets[i % n_sets], R, P, msg, stream)
-        sbc.sbc_decompress_accumulate(ctx, msg, nbytes, P, scale, out, stream)
-        return nbytes
+        def __init__(self, index):
+            self.R = sbc.TensorList(views(torch.zeros(N, dtype=torch.float32, device=dev)))
+            self.out = sbc.TensorList(views(torch.zeros(N, dtype=torch.float32, device=dev)))
+            self.msg = sbc.MessageBuffer(torch.zeros(bound, dtype=torch.uint8, device=dev))
+            self.stream_obj = torch.cuda.current_stream() if index == 0 else torch.cuda.Stream()
+            self.stream = self.stream_obj.cuda_stream     # raw handle, looked up once
+            self.ctx = sbc.sbc_create(0, N, T)
+            if args.carry_keys:
+                sbc.sbc_set_option(self.ctx, sbc.SBC_OPT_CARRY_FILTER_KEYS, 1)
+            if args.sampled_threshold:
+                sbc.sbc_set_option(self.ctx, sbc.SBC_OPT_SAMPLED_THRESHOLD, 1)
+            # the server calls only enqueue; their status is collected once, inside the timed region
+            sbc.sbc_set_option(self.ctx, sbc.SBC_OPT_DEFER_DECODE_STATUS, 1)
 
-    for i in range(args.warmup):
-        step(i)
-    sbc.sbc_decode_status(ctx, stream)
+    clients = [Client(i) for i in range(C)]
+    ctx, R, out, msg, stream = clients[0].ctx, clients[0].R, clients[0].out, clients[0].msg, clients[0].stream
+
+    def run_steps(clients, first, count, profile_every=0, routes=None):
+        """Steps first .. first+count-1; step s is client s mod C's next round: the client call
+        (begin ... end: the message size is needed on the host), then the server call on the
+        produced message.  Every client has at most one step in flight.  With profile_every, every
+        profile_every-th step of a client carries the events that time the streaming kernel."""
+        C = len(clients)
+
+        def begin(s):
+            c = clients[s % C]
+            if profile_every:
+                sbc.sbc_profile_level(c.ctx, 1 if (s // C) % profile_every == 0 else 0)
+            sbc.sbc_compress_begin(c.ctx, dW_sets[s % n_sets], c.R, P, c.msg, c.stream)
+
+        total_bytes = 0
+        for s in range(first, min(first + C, first + count)):
+            begin(s)
+        for s in range(first, first + count):
+            c = clients[s % C]
+            nbytes = sbc.sbc_compress_end(c.ctx)
+            sbc.sbc_decompress_accumulate(c.ctx, c.msg, nbytes, P, scale, c.out, c.stream)
+            total_bytes += nbytes
+            if routes is not None:
+                rt = sbc.sbc_last_route(c.ctx)
+                routes[rt] = routes.get(rt, 0) + 1
+            if s + C < first + count:
+                begin(s + C)
+        for c in clients:
+            sbc.sbc_decode_status(c.ctx, c.stream)
+        return total_bytes
+
+    run_steps(clients, 0, max(args.warmup, C))
     torch.cuda.synchronize()
 
     # The streaming kernel's own duration is taken live, inside the timed region, from the
     # start/stop events of its dispatch on every PROFILE_EVERY-th step (events on a dispatch add a
     # few microseconds of idle time around it, so not every step carries them).
-    msg_bytes = 0
     routes = {}
-    sbc.sbc_profile_enable(ctx, 0)
+    for c in clients:
+        sbc.sbc_profile_enable(c.ctx, 0)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        sbc.sbc_profile_level(ctx, 1 if i % PROFILE_EVERY == 0 else 0)
-        nbytes = sbc.sbc_compress(ctx, dW_sets[(args.warmup + i) % n_sets], R, P, msg, stream)
-        sbc.sbc_decompress_accumulate(ctx, msg, nbytes, P, scale, out, stream)
-        msg_bytes += nbytes
-        rt = sbc.sbc_last_route(ctx)
-        routes[rt] = routes.get(rt, 0) + 1
-    sbc.sbc_decode_status(ctx, stream)
+    msg_bytes = run_steps(clients, args.warmup, args.steps, PROFILE_EVERY, routes)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    prof = {name: (ms, calls) for name, ms, calls in sbc.sbc_profile_read(ctx)}
+    prof = {}
+    for c in clients:
+        for kernel, ms, calls in sbc.sbc_profile_read(c.ctx):
+            acc_ms, acc_calls = prof.get(kernel, (0.0, 0))
+            prof[kernel] = (acc_ms + ms, acc_calls + calls)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
-    # untimed extra: latency of each call on its own (every call waited for)
+    # untimed extra: latency of each call on its own (one client, every call waited for)
     sbc.sbc_set_option(ctx, sbc.SBC_OPT_DEFER_DECODE_STATUS, 0)
     sbc.sbc_profile_level(ctx, 0)
     t_compress = t_decode = 0.0
@@ -179,7 +208,7 @@ def main() -> int:
     breakdown = {name: round(ms / max(1, calls) * 1e3, 2) for name, ms, calls in sbc.sbc_profile_read(ctx)}
     sbc.sbc_profile_enable(ctx, 0)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    src, dst = flat_sets[0], (flat_sets[1] if n_sets > 1 else flat_out)
+    src, dst = flat_sets[0], (flat_sets[1] if n_sets > 1 else out.tensors[0])
     for _ in range(3):
         sbc.sbc_copy_baseline(dst, src)
     torch.cuda.synchronize()
@@ -196,6 +225,23 @@ def main() -> int:
     if args.breakdown:
         print("per-kernel us (event-bracketed):", breakdown, file=sys.stderr)
 
+    # untimed extra: the same steps with three independent clients in flight, whose latency-bound
+    # kernels and host round trips overlap one another's streaming pass
+    pipelined = None
+    if C == 1 and args.workload != "flat1p5e9":
+        sbc.sbc_set_option(ctx, sbc.SBC_OPT_DEFER_DECODE_STATUS, 1)
+        three = clients + [Client(1), Client(2)]
+        run_steps(three, 0, 9)
+        torch.cuda.synchronize()
+        tp0 = time.perf_counter()
+        run_steps(three, 9, args.steps)
+        torch.cuda.synchronize()
+        tp = (time.perf_counter() - tp0) / args.steps
+        pipelined = {"clients_in_flight": 3, "ms_per_step": tp * 1e3, "elements_per_s": N / tp,
+                     "streaming_bytes_frac_of_hbm_peak": BYTES_PER_ENTRY * N / tp / 1e9 / HBM_PEAK_GBS}
+        for c in three[1:]:
+            sbc.sbc_destroy(c.ctx)
+
     cpu = None
     if not args.no_cpu_baseline and args.workload == "resnet50":
         from oracle import sbc_oracle as oracle
@@ -210,7 +256,8 @@ def main() -> int:
         cpu = {"value": N / dt, "unit": "elements/s", "cores": 1, "kind": "oracle",
                "sample": "one full step (compress + decode-accumulate) of the same 161-tensor update, "
                          "%d entries, %.1f s" % (N, dt)}
-    sbc.sbc_destroy(ctx)
+    for c in clients:
+        sbc.sbc_destroy(c.ctx)
 
     line = {
         "metric": "SBC compress+encode throughput (elements/s, HBM GB/s, % of peak) per round",
@@ -226,8 +273,9 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": name, "p": P, "tensors": T, "entries": N,
-                   "step": "sbc_compress + sbc_decompress_accumulate (one client, one round); the decode "
-                           "status is collected once for all steps (SBC_OPT_DEFER_DECODE_STATUS)",
+                   "step": "sbc_compress (begin/end) + sbc_decompress_accumulate (one client, one round); the "
+                           "decode status is collected once for all steps (SBC_OPT_DEFER_DECODE_STATUS)",
+                   "clients_in_flight": C,
                    "selection": "subsampled threshold (noisy count)" if args.sampled_threshold else "exact top-k"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
@@ -242,6 +290,7 @@ def main() -> int:
         "compress_algorithmic_GBs": BYTES_PER_ENTRY * N / (compress_ms * 1e-3) / 1e9,
         "compress_frac_of_hbm_peak": BYTES_PER_ENTRY * N / (compress_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernel_us": breakdown,
+        "pipelined": pipelined,
         "copy_kernel_GBs": copy_gbs,
         "message_bytes": msg_bytes / args.steps,
         "routes": {"sampled": sum(v for k, v in routes.items() if not k & 1),

@@ -120,6 +120,20 @@ int sbc_compress(sbc_ctx* ctx, void* hip_stream,
                  const int64_t* numel, int n_tensors, double p,
                  void* msg, size_t msg_capacity, size_t* msg_bytes);
 
+/* The same step in two calls, for callers that keep several independent client steps in flight
+ * (one context, one stream and one set of buffers per client): sbc_compress_begin checks its
+ * arguments (same meaning and errors as above) and enqueues the step on hip_stream without
+ * waiting; sbc_compress_end waits for it, completes the rare tensors that need a second pass,
+ * and returns the status and the message size.  Between the two calls the context accepts
+ * sbc_decompress_accumulate and nothing else (SBC_EINVAL), dW, residual and msg must not be
+ * touched, and the host arrays passed to begin are no longer needed.  sbc_compress_end without
+ * a pending step returns SBC_EINVAL.  sbc_compress is begin followed by end. */
+int sbc_compress_begin(sbc_ctx* ctx, void* hip_stream,
+                       const float* const* dW, float* const* residual,
+                       const int64_t* numel, int n_tensors, double p,
+                       void* msg, size_t msg_capacity);
+int sbc_compress_end(sbc_ctx* ctx, size_t* msg_bytes);
+
 /* Server step for one client message (Alg. 4, then the summand of Alg. 1's average):
  *     out_t[j] += scale * mu_signed_t   for every decoded position j of every tensor t
  * (fp32: the addend fl32(scale*mu) is formed once).  Call once per client with

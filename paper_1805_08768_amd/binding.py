@@ -34,7 +34,7 @@ SBC_ROUTE_WIDE = 4
 
 EXPORTS = (
     "sbc_create", "sbc_destroy", "sbc_golomb_bstar", "sbc_num_kept", "sbc_msg_bound", "sbc_msg_bound_sampled",
-    "sbc_compress", "sbc_decompress_accumulate", "sbc_last_tensor_stats", "sbc_last_mask",
+    "sbc_compress", "sbc_compress_begin", "sbc_compress_end", "sbc_decompress_accumulate", "sbc_last_tensor_stats", "sbc_last_mask",
     "sbc_profile_enable", "sbc_profile_level", "sbc_profile_read", "sbc_copy_baseline", "sbc_set_option",
     "sbc_last_route", "sbc_strerror", "sbc_decode_status",
 )
@@ -71,6 +71,11 @@ def load() -> ctypes.CDLL:
     lib.sbc_compress.argtypes = [vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(i64),
                                  ctypes.c_int, ctypes.c_double, vp, sz, ctypes.POINTER(sz)]
     lib.sbc_compress.restype = ctypes.c_int
+    lib.sbc_compress_begin.argtypes = [vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(i64),
+                                       ctypes.c_int, ctypes.c_double, vp, sz]
+    lib.sbc_compress_begin.restype = ctypes.c_int
+    lib.sbc_compress_end.argtypes = [vp, ctypes.POINTER(sz)]
+    lib.sbc_compress_end.restype = ctypes.c_int
     lib.sbc_decompress_accumulate.argtypes = [vp, vp, vp, sz, ctypes.POINTER(i64), ctypes.c_int,
                                               ctypes.c_double, ctypes.c_float, ctypes.POINTER(vp)]
     lib.sbc_decompress_accumulate.restype = ctypes.c_int
@@ -214,6 +219,27 @@ def sbc_compress(ctx, dW, residual, p: float,
                              p, msg.ptr, msg.capacity, ctypes.byref(out_bytes))
     if rc != SBC_OK:
         raise SbcError(rc, "sbc_compress")
+    return int(out_bytes.value)
+
+
+def sbc_compress_begin(ctx, dW, residual, p: float, msg: torch.Tensor, stream=None) -> None:
+    """Enqueues the client step without waiting; sbc_compress_end(ctx) completes it.  The tensors
+    and `msg` must stay alive and untouched until then."""
+    dW, residual, msg = _as_list(dW), _as_list(residual), _as_msg(msg)
+    if dW.numel_key != residual.numel_key:
+        raise ValueError("dW and residual must list tensors of the same sizes")
+    rc = load().sbc_compress_begin(ctx, _stream_handle(stream), dW.ptrs, residual.ptrs, dW.numel_arr,
+                                   len(dW.tensors), p, msg.ptr, msg.capacity)
+    if rc != SBC_OK:
+        raise SbcError(rc, "sbc_compress_begin")
+
+
+def sbc_compress_end(ctx) -> int:
+    """Waits for the step enqueued by sbc_compress_begin; returns the message size in bytes."""
+    out_bytes = ctypes.c_size_t(0)
+    rc = load().sbc_compress_end(ctx, ctypes.byref(out_bytes))
+    if rc != SBC_OK:
+        raise SbcError(rc, "sbc_compress_end")
     return int(out_bytes.value)
 
 

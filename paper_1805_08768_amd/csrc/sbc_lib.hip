@@ -93,7 +93,8 @@ struct sbc_ctx {
     uint32_t* h_chunk_tensor = nullptr;
     uint32_t* h_order = nullptr;
     uint32_t* h_wide_ids = nullptr;
-    ResultBlock* h_result = nullptr;
+    ResultBlock* h_result = nullptr;      // compress
+    ResultBlock* h_result_dec = nullptr;  // decode (its own block: a decode call may come between begin and end)
     DecDesc* h_dec = nullptr;
     uint2* h_dec_blocks = nullptr;
     uint32_t n_dec_blocks = 0;
@@ -145,6 +146,23 @@ struct sbc_ctx {
     bool ev_ok = false;
     double stage_ms[kNumStages] = {};
     int64_t stage_calls[kNumStages] = {};
+
+    // a client step that has been enqueued (sbc_compress_begin) and not yet completed
+    struct Pending {
+        bool active = false;
+        hipStream_t stream = nullptr;
+        int T = 0, b = 0, slot = 0, force_exact = 0;
+        double p = 0.0;
+        bool slot_is_new = false, use_history = false, sampled = false, any_bitmap = false;
+        bool timed[kNumStages] = {};
+        ResultBlock* res_now = nullptr;
+        ResultBlock* res_next = nullptr;
+        TensorDesc* d_desc = nullptr;
+        uint8_t* msg8 = nullptr;
+        size_t msg_capacity = 0, need = 0;
+        uint32_t n_chunks = 0;
+        unsigned gather_y = 1;
+    } pend;
 
     // last compress call, for the inspection entry points
     int last_T = 0;
@@ -213,6 +231,7 @@ void free_all(sbc_ctx* c) {
     if (c->h_chunk_tensor) (void)hipHostFree(c->h_chunk_tensor);
     if (c->h_order) (void)hipHostFree(c->h_order);
     if (c->h_result) (void)hipHostFree(c->h_result);
+    if (c->h_result_dec) (void)hipHostFree(c->h_result_dec);
     if (c->h_dec) (void)hipHostFree(c->h_dec);
     if (c->h_state) (void)hipHostFree(c->h_state);
     if (c->ev_ok) for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
@@ -223,6 +242,59 @@ int status_of_err(uint32_t err) {
     if (err & kErrInternal) return SBC_EINTERNAL;
     if (err & kErrNonFinite) return SBC_ENONFINITE;
     if (err & kErrCorrupt) return SBC_ECORRUPT;
+    return SBC_OK;
+}
+
+// Kernels are timed only when profiling was asked for: the launch then carries a start and a
+// stop event that take the dispatch's own begin and end time stamps (event 2s and 2s+1 for
+// stage s), so the figure is the kernel's duration without the gaps between dispatches.
+// Expects c (context), lvl (profile level), stream and timed[] in scope.
+#define SBC_LAUNCH(stage, on, kernel, grid, block, ...)                                                    \
+    do {                                                                                                   \
+        if ((on) && (lvl >= 2 || (lvl == 1 && (stage) == kStAccumulate))) {                                \
+            hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, c->ev[2 * (stage)], c->ev[2 * (stage) + 1], 0, \
+                                  __VA_ARGS__);                                                            \
+            timed[stage] = true;                                                                           \
+        } else {                                                                                           \
+            hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);                               \
+        }                                                                                                  \
+    } while (0)
+
+// Alg. 3 for the tensors whose positions are in the bitmap, then the message assembly, for the
+// pending client step.
+void launch_encode_and_gather(sbc_ctx* c, bool profile) {
+    sbc_ctx::Pending& P = c->pend;
+    const int lvl = c->profile_level;
+    hipStream_t stream = P.stream;
+    bool* timed = P.timed;
+    const int T = P.T, b = P.b;
+    if (P.any_bitmap) {
+        SBC_LAUNCH(kStChunkSummary, profile, k_chunk_summary, dim3(P.n_chunks), dim3(kChunkWords), P.d_desc,
+                   c->d_chunk_tensor, c->d_bitmap, c->d_sum, b);
+        SBC_LAUNCH(kStTensorScan, profile, k_tensor_scan, dim3(T), dim3(kScanThreads), P.d_desc, c->d_sum, c->d_prev_end,
+                   c->d_bitoff, c->d_state, b);
+        SBC_LAUNCH(kStPack, profile, k_pack, dim3(P.n_chunks), dim3(kChunkWords), P.d_desc, c->d_chunk_tensor,
+                   c->d_bitmap, c->d_sum, c->d_prev_end, c->d_bitoff, b, c->d_stage, P.res_now);
+    }
+    SBC_LAUNCH(kStGather, profile, k_gather, dim3(T, P.gather_y), dim3(256), P.d_desc, c->d_state, T, b,
+               c->d_stage, P.msg8, (uint64_t)P.msg_capacity, P.res_now, P.res_next);
+}
+
+// The pending step's result block on its way to the host / waited for.
+int enqueue_result_copy(sbc_ctx* c) {
+    if (hipGetLastError() != hipSuccess) return SBC_EHIP;
+    if (hipMemcpyAsync(c->h_result, c->pend.res_now, sizeof(ResultBlock), hipMemcpyDeviceToHost, c->pend.stream) != hipSuccess) {
+        (void)hipGetLastError();
+        return SBC_EHIP;
+    }
+    return SBC_OK;
+}
+
+int wait_result(sbc_ctx* c) {
+    if (hipStreamSynchronize(c->pend.stream) != hipSuccess) {
+        (void)hipGetLastError();
+        return SBC_EHIP;
+    }
     return SBC_OK;
 }
 
@@ -337,6 +409,7 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     ok = ok && host_alloc(&c->h_chunk_tensor, (size_t)c->max_chunks) == hipSuccess;
     ok = ok && host_alloc(&c->h_order, T) == hipSuccess;
     ok = ok && host_alloc(&c->h_result, 1) == hipSuccess;
+    ok = ok && host_alloc(&c->h_result_dec, 1) == hipSuccess;
     ok = ok && host_alloc(&c->h_dec, T) == hipSuccess;
     ok = ok && host_alloc(&c->h_state, T) == hipSuccess;
     if (ok) {
@@ -368,7 +441,7 @@ void sbc_destroy(sbc_ctx* c) {
 }
 
 int sbc_set_option(sbc_ctx* c, int option, int value) {
-    if (!c) return SBC_EINVAL;
+    if (!c || c->pend.active) return SBC_EINVAL;      // not between sbc_compress_begin and sbc_compress_end
     switch (option) {
         case SBC_OPT_FORCE_EXACT_PATH: c->force_exact = value ? 1 : 0; c->hist_valid = false; return SBC_OK;
         case SBC_OPT_CARRY_FILTER_KEYS: c->carry_keys = value ? 1 : 0; c->hist_valid = false; return SBC_OK;
@@ -391,11 +464,11 @@ int sbc_set_option(sbc_ctx* c, int option, int value) {
     }
 }
 
-int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* const* residual,
-                 const int64_t* numel, int n_tensors, double p, void* msg, size_t msg_capacity,
-                 size_t* msg_bytes) {
-    if (!c || !dW || !residual || !numel || !msg || !msg_bytes || n_tensors <= 0 || !valid_p(p))
+int sbc_compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, float* const* residual,
+                       const int64_t* numel, int n_tensors, double p, void* msg, size_t msg_capacity) {
+    if (!c || !dW || !residual || !numel || !msg || n_tensors <= 0 || !valid_p(p))
         return SBC_EINVAL;
+    if (c->pend.active) return SBC_EINVAL;            // one step at a time per context
     if (((uintptr_t)msg & 7u) != 0) return SBC_EINVAL;
     if (n_tensors > c->max_tensors) return SBC_ECAPACITY;
     const int T = n_tensors;
@@ -552,48 +625,15 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
     c->result_idx ^= 1;
     const unsigned gather_y = (unsigned)std::min<uint64_t>(64, std::max<uint64_t>(1, (max_bound + 1023) / 1024));
 
-    // Kernels are timed only when profiling was asked for: the launch then carries a start and a
-    // stop event that take the dispatch's own begin and end time stamps (event 2s and 2s+1 for
-    // stage s), so the figure is the kernel's duration without the gaps between dispatches.
+    // what sbc_compress_end and the launch helpers need
+    sbc_ctx::Pending& P = c->pend;
+    P.stream = stream; P.T = T; P.b = b; P.p = p; P.slot = slot; P.slot_is_new = slot_is_new;
+    P.force_exact = force_exact; P.use_history = use_history; P.sampled = sampled; P.any_bitmap = any_bitmap;
+    for (int st = 0; st < kNumStages; ++st) P.timed[st] = false;
+    P.res_now = res_now; P.res_next = res_next; P.d_desc = d_desc; P.msg8 = msg8;
+    P.msg_capacity = msg_capacity; P.need = need; P.n_chunks = n_chunks; P.gather_y = gather_y;
     const int lvl = c->profile_level;
-    bool timed[kNumStages] = {};
-#define SBC_LAUNCH(stage, on, kernel, grid, block, ...)                                                    \
-    do {                                                                                                   \
-        if ((on) && (lvl >= 2 || (lvl == 1 && (stage) == kStAccumulate))) {                                \
-            hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, c->ev[2 * (stage)], c->ev[2 * (stage) + 1], 0, \
-                                  __VA_ARGS__);                                                            \
-            timed[stage] = true;                                                                           \
-        } else {                                                                                           \
-            hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);                               \
-        }                                                                                                  \
-    } while (0)
-    auto encode_and_gather = [&](bool profile) {
-        if (any_bitmap) {
-            SBC_LAUNCH(kStChunkSummary, profile, k_chunk_summary, dim3(n_chunks), dim3(kChunkWords), d_desc,
-                       c->d_chunk_tensor, c->d_bitmap, c->d_sum, b);
-            SBC_LAUNCH(kStTensorScan, profile, k_tensor_scan, dim3(T), dim3(kScanThreads), d_desc, c->d_sum, c->d_prev_end,
-                       c->d_bitoff, c->d_state, b);
-            SBC_LAUNCH(kStPack, profile, k_pack, dim3(n_chunks), dim3(kChunkWords), d_desc, c->d_chunk_tensor,
-                       c->d_bitmap, c->d_sum, c->d_prev_end, c->d_bitoff, b, c->d_stage, res_now);
-        }
-        SBC_LAUNCH(kStGather, profile, k_gather, dim3(T, gather_y), dim3(256), d_desc, c->d_state, T, b,
-                   c->d_stage, msg8, (uint64_t)msg_capacity, res_now, res_next);
-    };
-    auto finish = [&]() -> int {                      // copy the result block back and wait
-        SBC_HOST_TS(2);
-        if (hipGetLastError() != hipSuccess) return SBC_EHIP;
-        if (hipMemcpyAsync(c->h_result, res_now, sizeof(ResultBlock), hipMemcpyDeviceToHost, stream) != hipSuccess) {
-            (void)hipGetLastError();
-            return SBC_EHIP;
-        }
-        SBC_HOST_TS(3);
-        if (hipStreamSynchronize(stream) != hipSuccess) {
-            (void)hipGetLastError();
-            return SBC_EHIP;
-        }
-        SBC_HOST_TS(4);
-        return SBC_OK;
-    };
+    bool* timed = P.timed;
 
     SBC_HOST_TS(1);
     // ---- fast path: [sample ->] accumulate + filter -> select (+ fused encode) -> gather ----
@@ -645,15 +685,32 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
     }
     SBC_LAUNCH(kStSelect, true, k_select, dim3(T), dim3(kSelThreads), d_desc, c->d_order,
                c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 0, res_now);
-    encode_and_gather(true);
-#undef SBC_LAUNCH
-    int rc = finish();
+    launch_encode_and_gather(c, true);
+    SBC_HOST_TS(2);
+    const int rc = enqueue_result_copy(c);
+    if (rc != SBC_OK) return rc;
+    SBC_HOST_TS(3);
+    P.active = true;
+    return SBC_OK;
+}
+
+int sbc_compress_end(sbc_ctx* c, size_t* msg_bytes) {
+    if (!c || !msg_bytes || !c->pend.active) return SBC_EINVAL;
+    sbc_ctx::Pending& P = c->pend;
+    P.active = false;
+    DeviceGuard guard(c->device);
+    hipStream_t stream = P.stream;
+    const int T = P.T, b = P.b;
+    TensorDesc* const d_desc = P.d_desc;
+    ResultBlock* const res_now = P.res_now;
+    int rc = wait_result(c);
+    SBC_HOST_TS(4);
     if (rc != SBC_OK) return rc;
     c->cache_valid = true;
-    if (slot_is_new) c->slot[slot].valid = true;
+    if (P.slot_is_new) c->slot[P.slot].valid = true;
     c->last_T = T;
     for (int st = 0; st < kNumStages; ++st) {
-        if (!timed[st]) continue;
+        if (!P.timed[st]) continue;
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, c->ev[2 * st], c->ev[2 * st + 1]) == hipSuccess) {
             c->stage_ms[st] += (double)ms;
@@ -674,34 +731,44 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
                            (uint64_t)hist_words);
         hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(res_now),
                            (uint64_t)(sizeof(ResultBlock) / 4));
-        hipLaunchKernelGGL(k_hist_flagged, dim3(n_chunks), dim3(kStreamThreads), 0, stream, d_desc,
+        hipLaunchKernelGGL(k_hist_flagged, dim3(P.n_chunks), dim3(kStreamThreads), 0, stream, d_desc,
                            c->d_chunk_tensor, c->d_state, c->d_hist);
         hipLaunchKernelGGL(k_pick_bins, dim3(T), dim3(256), 0, stream, d_desc, c->d_hist, c->d_state, res_now);
-        hipLaunchKernelGGL(k_extract, dim3(n_chunks), dim3(kStreamThreads), 0, stream, d_desc,
+        hipLaunchKernelGGL(k_extract, dim3(P.n_chunks), dim3(kStreamThreads), 0, stream, d_desc,
                            c->d_chunk_tensor, c->d_state, c->d_cand, res_now);
         hipLaunchKernelGGL(k_select, dim3(T), dim3(kSelThreads), 0, stream, d_desc, c->d_order,
                            c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 1, res_now);
-        encode_and_gather(false);
-        rc = finish();
+        launch_encode_and_gather(c, false);
+        rc = enqueue_result_copy(c);
+        if (rc == SBC_OK) rc = wait_result(c);
         if (rc != SBC_OK) return rc;
         err = c->h_result->err;
         if (err & kErrPrefilter) return SBC_EINTERNAL;
     }
     const int status = status_of_err(err);
     if (status != SBC_OK) return status;
-    if (c->h_result->msg_bytes > need) return SBC_EINTERNAL;
+    if (c->h_result->msg_bytes > P.need) return SBC_EINTERNAL;
     *msg_bytes = (size_t)c->h_result->msg_bytes;
     c->last_ok = true;
-    c->last_used_history = use_history;
+    c->last_used_history = P.use_history;
     c->result_dirty = false;
     // the next call may start from this call's thresholds unless they proved unhelpful
-    c->hist_valid = c->carry_keys && !sampled && !force_exact && !c->last_used_exact_path && !(err & kErrLoose);
+    c->hist_valid = c->carry_keys && !P.sampled && !P.force_exact && !c->last_used_exact_path && !(err & kErrLoose);
     if (c->hist_valid) {
-        c->hist_p = p;
+        c->hist_p = P.p;
         c->hist_n.resize(T);
         for (int t = 0; t < T; ++t) c->hist_n[t] = c->plan[t].n;
     }
     return SBC_OK;
+}
+
+int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* const* residual,
+                 const int64_t* numel, int n_tensors, double p, void* msg, size_t msg_capacity,
+                 size_t* msg_bytes) {
+    if (!msg_bytes) return SBC_EINVAL;
+    const int rc = sbc_compress_begin(c, hip_stream, dW, residual, numel, n_tensors, p, msg, msg_capacity);
+    if (rc != SBC_OK) return rc;
+    return sbc_compress_end(c, msg_bytes);
 }
 
 int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, size_t msg_bytes,
@@ -818,15 +885,15 @@ int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, siz
         c->dev_dec_valid = true;
         return SBC_OK;
     }
-    if (hipMemcpyAsync(c->h_result, res_dec, sizeof(ResultBlock), hipMemcpyDeviceToHost, stream) != hipSuccess ||
+    if (hipMemcpyAsync(c->h_result_dec, res_dec, sizeof(ResultBlock), hipMemcpyDeviceToHost, stream) != hipSuccess ||
         hipStreamSynchronize(stream) != hipSuccess) {
         (void)hipGetLastError();
         return SBC_EHIP;
     }
     SBC_HOST_TS(11);
     c->dev_dec_valid = true;
-    if (c->h_result->err == 0u) c->dec_result_dirty = false;
-    return status_of_err(c->h_result->err);
+    if (c->h_result_dec->err == 0u) c->dec_result_dirty = false;
+    return status_of_err(c->h_result_dec->err);
 }
 
 int sbc_decode_status(sbc_ctx* c, void* hip_stream) {
@@ -836,12 +903,12 @@ int sbc_decode_status(sbc_ctx* c, void* hip_stream) {
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     c->deferred_pending = false;
     c->deferred_dirty = true;
-    if (hipMemcpyAsync(c->h_result, c->d_result + 4, sizeof(ResultBlock), hipMemcpyDeviceToHost, stream) != hipSuccess ||
+    if (hipMemcpyAsync(c->h_result_dec, c->d_result + 4, sizeof(ResultBlock), hipMemcpyDeviceToHost, stream) != hipSuccess ||
         hipStreamSynchronize(stream) != hipSuccess) {
         (void)hipGetLastError();
         return SBC_EHIP;
     }
-    return status_of_err(c->h_result->err);
+    return status_of_err(c->h_result_dec->err);
 }
 
 int sbc_copy_baseline(void* hip_stream, void* dst, const void* src, size_t bytes) {

@@ -552,3 +552,44 @@ def test_deferred_decode_status():
         sbc.sbc_decompress_accumulate(run.ctx, msgs[3][0], msgs[3][1], p, 1.0, outs3)
         for a, b in zip(outs2, outs3):
             assert torch.equal(a, b)
+
+
+def test_compress_begin_end_interleaved_clients():
+    """sbc_compress_begin / sbc_compress_end: three independent clients in flight on their own
+    streams; every message and residual equals the oracle's, also on the histogram route."""
+    sizes = [70000, 64, 20000, 8193]
+    p = 0.01
+    clients = 3
+    runs = [DeviceRun(sizes) for _ in range(clients)]
+    streams = [torch.cuda.Stream() for _ in range(clients)]
+    try:
+        sbc.sbc_set_option(runs[2].ctx, sbc.SBC_OPT_FORCE_EXACT_PATH, 1)      # completes in sbc_compress_end
+        R = [[np.zeros(n, np.float32) for n in sizes] for _ in range(clients)]
+        bound = sbc.sbc_msg_bound(sizes, p)
+        with pytest.raises(sbc.SbcError):
+            sbc.sbc_compress_end(runs[0].ctx)                                 # nothing pending
+        for rnd in range(3):
+            dWs = [synth.small_model_update(sizes, client=c, round_=rnd) for c in range(clients)]
+            d_dW = [[torch.from_numpy(x).cuda() for x in dWs[c]] for c in range(clients)]
+            msgs = [torch.zeros(bound, dtype=torch.uint8, device="cuda:0") for _ in range(clients)]
+            torch.cuda.synchronize()
+            for c in range(clients):
+                sbc.sbc_compress_begin(runs[c].ctx, d_dW[c], runs[c].R, p, msgs[c], streams[c].cuda_stream)
+            with pytest.raises(sbc.SbcError):                                 # one step at a time per context
+                sbc.sbc_compress_begin(runs[0].ctx, d_dW[0], runs[0].R, p, msgs[0], streams[0].cuda_stream)
+            with pytest.raises(sbc.SbcError):
+                sbc.sbc_set_option(runs[0].ctx, sbc.SBC_OPT_CARRY_FILTER_KEYS, 1)
+            for c in (1, 0, 2):
+                nbytes = sbc.sbc_compress_end(runs[c].ctx)
+                res = o.compress_model(dWs[c], R[c], p)
+                assert msgs[c][:nbytes].cpu().numpy().tobytes() == o.build_message(res), (rnd, c)
+                for t, x in enumerate(res):
+                    got = runs[c].R[t].cpu().numpy()
+                    assert np.allclose(got, x.R_new, rtol=0, atol=1e-5 * max(abs(float(x.mu_signed)), 1e-30)), (rnd, c, t)
+                    mu_pos, mu_neg, side, nnz, bit_len = sbc.sbc_last_tensor_stats(runs[c].ctx, t)
+                    assert side == x.side and nnz == x.k
+                R[c] = [x.R_new for x in res]
+            assert sbc.sbc_last_route(runs[2].ctx) == sbc.SBC_ROUTE_HISTOGRAM
+    finally:
+        for r in runs:
+            r.close()
