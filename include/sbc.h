@@ -17,12 +17,15 @@
  *     pointers (dW[], residual[], out[]) and numel[] are HOST arrays whose
  *     ELEMENTS are device pointers / sizes.
  *   - The caller owns every buffer it passes.  The library reads or writes
- *     them only during the call and keeps no reference afterwards.  All
+ *     them only during the call (between sbc_compress_begin and
+ *     sbc_compress_end, and until the stream has passed a deferred decode
+ *     call, where those are used) and keeps no reference afterwards.  All
  *     scratch memory is owned by the sbc_ctx and allocated in sbc_create();
  *     sbc_compress() and sbc_decompress_accumulate() allocate nothing.
  *   - Work is enqueued on the caller's HIP stream (a hipStream_t passed as
- *     void*; NULL is the default stream).  Both entry points synchronise that
- *     stream once before returning, so results and the status are final.
+ *     void*; NULL is the default stream).  sbc_compress and (unless its status
+ *     is deferred) sbc_decompress_accumulate synchronise that stream once
+ *     before returning, so results and the status are final.
  *   - A context must not be used from two threads at once.
  *   - Tensor sizes: 1 <= numel < 2^32.  Sparsity: 0 < p < 1.
  *
