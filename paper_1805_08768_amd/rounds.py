@@ -37,13 +37,24 @@ class Client:
         self._dW_list = sbc.TensorList(self.dW)
         self.msg = torch.zeros(sbc.sbc_msg_bound(self.sizes, self.p), dtype=torch.uint8, device=device)
         self.nbytes = 0
+        self.stream = torch.cuda.Stream(device=device)    # clients work in parallel (Alg. 1)
+
+    def begin_upload(self, update: Sequence[np.ndarray]):
+        """dW_i <- R_i + update; dW*_i <- SBC(dW_i); R_i <- dW_i - dW*_i, enqueued on the client's
+        stream without waiting."""
+        with torch.cuda.stream(self.stream):
+            for dst, src in zip(self.dW, update):
+                dst.copy_(torch.from_numpy(np.ascontiguousarray(src, dtype=np.float32)))
+        sbc.sbc_compress_begin(self.ctx, self._dW_list, self._R_list, self.p, self.msg, self.stream)
+
+    def end_upload(self):
+        """Waits for begin_upload; returns (msg, nbytes)."""
+        self.nbytes = sbc.sbc_compress_end(self.ctx)
+        return self.msg, self.nbytes
 
     def upload(self, update: Sequence[np.ndarray]):
-        """dW_i <- R_i + update; dW*_i <- SBC(dW_i); R_i <- dW_i - dW*_i; returns (msg, nbytes)."""
-        for dst, src in zip(self.dW, update):
-            dst.copy_(torch.from_numpy(np.ascontiguousarray(src, dtype=np.float32)))
-        self.nbytes = sbc.sbc_compress(self.ctx, self._dW_list, self._R_list, self.p, self.msg)
-        return self.msg, self.nbytes
+        self.begin_upload(update)
+        return self.end_upload()
 
     def last_mask(self, tensor: int) -> torch.Tensor:
         """Bit mask (uint32 words, bit j of word j // 32) of the positions sent in the last upload."""
@@ -100,10 +111,9 @@ def run_rounds(sizes: Sequence[int], p: float, n_clients: int, n_rounds: int,
     try:
         for rnd in range(n_rounds):
             chosen = list(range(n_clients)) if participants is None else list(participants(rnd))
-            messages = []
-            for i in chosen:
-                msg, nbytes = clients[i].upload(local_update(i, rnd, W))
-                messages.append((msg, nbytes))
+            for i in chosen:                          # "for all clients in parallel"
+                clients[i].begin_upload(local_update(i, rnd, W))
+            messages = [clients[i].end_upload() for i in chosen]
             avg = server.average(messages)
             for w, a in zip(W, avg):
                 w += a.cpu().numpy()              # W <- W + dW, the broadcast every client downloads
