@@ -48,7 +48,7 @@ __device__ __forceinline__ uint32_t mix32(uint32_t x) {
 }
 
 // --------------------------------------------------------------------------
-// Prefilter thresholds from a sample.  One workgroup (1024 threads) per tensor.  Tensors of up to
+// Prefilter thresholds from a sample.  One workgroup (512 threads) per tensor.  Tensors of up to
 // kSampleMax entries are read completely (the threshold is then the exact k-th key to 16
 // bits); larger ones contribute 256 runs of 64 consecutive entries, one run at a pseudo-random
 // place in each of 256 equal strata.  With m sampled entries out of n, lambda = k*m/n of them
@@ -69,6 +69,8 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
     __shared__ uint32_t skey[kSampleMax];             // the sample, as keys (loops stay rolled: small code)
     __shared__ uint32_t hist0[2][256][COPIES];        // first byte: lane-private copies, one bank each
     __shared__ uint32_t hist[4][2][256];
+    __shared__ uint32_t whist[2][kSampleWindow];      // leading 16 key bits, counted down from the extreme
+    __shared__ uint32_t wave_ext[2][kSampleThreads / 64];
     __shared__ uint32_t res[4][8];
     __shared__ unsigned long long scratch[kSampleThreads / 64];
     SBC_TS(0, 0);
@@ -107,7 +109,12 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
 
     for (int i = tid; i < 3 * 2 * 256; i += kSampleThreads) (&hist[1][0][0])[i] = 0u;
     for (int i = tid; i < 2 * 256 * COPIES; i += kSampleThreads) (&hist0[0][0][0])[i] = 0u;
+    for (int i = tid; i < 2 * kSampleWindow; i += kSampleThreads) (&whist[0][0])[i] = 0u;
     __syncthreads();
+    uint32_t need[2] = {rs, rs};
+    const bool active[2] = {true, true};
+    uint32_t prefix[2] = {0u, 0u};
+    int first_pass = 0;
     // The sample: all of a thread's loads are issued before the first key is formed, so that the
     // kernel pays the memory latency once.
     const gcfloat_ptr R = as_global(d.R);
@@ -134,13 +141,63 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
                 a[s] = R[i]; w[s] = dW[i];
             }
         }
+        // Keys, and the most extreme key of each side (this thread's, then the workgroup's).
+        uint32_t key[PER], ext_p = 0u, ext_n = 0u;
 #pragma unroll
-        for (int s = 0; s < PER; ++s) skey[s * kSampleThreads + tid] = key_of_bits(__float_as_uint(a[s] + w[s]));
+        for (int s = 0; s < PER; ++s) {
+            key[s] = key_of_bits(__float_as_uint(a[s] + w[s]));
+            skey[s * kSampleThreads + tid] = key[s];
+            if ((uint32_t)(s * kSampleThreads + tid) < m) {
+                ext_p = key[s] > ext_p ? key[s] : ext_p;
+                ext_n = ~key[s] > ext_n ? ~key[s] : ext_n;
+            }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const uint32_t op = __shfl_xor(ext_p, off, 64), on = __shfl_xor(ext_n, off, 64);
+            ext_p = op > ext_p ? op : ext_p;
+            ext_n = on > ext_n ? on : ext_n;
+        }
+        if ((tid & 63) == 0) { wave_ext[0][tid >> 6] = ext_p; wave_ext[1][tid >> 6] = ext_n; }
+        __syncthreads();
+        SBC_TS(0, 1);                                 // sample loaded
+#pragma unroll
+        for (int wv = 0; wv < kSampleThreads / 64; ++wv) {
+            ext_p = wave_ext[0][wv] > ext_p ? wave_ext[0][wv] : ext_p;
+            ext_n = wave_ext[1][wv] > ext_n ? wave_ext[1][wv] : ext_n;
+        }
+        // The r-th most extreme key lies within a few octaves of the most extreme one: the leading
+        // 16 key bits are counted in a window of kSampleWindow values (16 octaves) below it, straight
+        // from the registers; the bulk of the sample spreads over hundreds of bins there, where the
+        // leading byte alone takes a handful of values.  Keys below the window are not counted.
+        const uint32_t top[2] = {ext_p >> 16, ext_n >> 16};
+#pragma unroll
+        for (int s = 0; s < PER; ++s) {
+            if ((uint32_t)(s * kSampleThreads + tid) < m) {
+                const uint32_t dp = top[0] - (key[s] >> 16), dn = top[1] - (~key[s] >> 16);
+                if (dp < (uint32_t)(kSampleWindow - 1)) atomicAdd(&whist[0][(uint32_t)(kSampleWindow - 1) - dp], 1u);
+                if (dn < (uint32_t)(kSampleWindow - 1)) atomicAdd(&whist[1][(uint32_t)(kSampleWindow - 1) - dn], 1u);
+            }
+        }
+        __syncthreads();
+        SBC_TS(0, 2);                                 // window histogram done
+        uint32_t digit[2];
+        bool found[2];
+        pick_wide_both<kSampleWindow, kSampleThreads>(whist, need, active, res[0], scratch, digit, found);
+        SBC_TS(0, 3);
+        if (found[0] && found[1]) {                   // uniform
+            prefix[0] = top[0] - ((uint32_t)(kSampleWindow - 1) - digit[0]);
+            prefix[1] = top[1] - ((uint32_t)(kSampleWindow - 1) - digit[1]);
+            first_pass = 2;
+        } else {
+            need[0] = need[1] = rs;                   // (a found side's need was lowered)
+        }
     }
     __syncthreads();
-    SBC_TS(0, 1);                                     // sample loaded
-    {   // first byte: floating-point keys take only a handful of values here, so every lane group
-        // counts into its own copy and the copies are added up afterwards
+    if (first_pass == 0) {
+        // The r-th entry lies below the window (mostly-zero tensors): byte by byte from the top.
+        // First byte: floating-point keys take only a handful of values here, so every lane group
+        // counts into its own copy and the copies are added up afterwards.
         const int copy = ((tid >> 6) & 1) * 8 + (tid & 7);
 #pragma unroll 8
         for (uint32_t i = tid; i < m; i += kSampleThreads) {
@@ -158,13 +215,10 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
         __syncthreads();
     }
     SBC_TS(0, 2);                                     // first-byte histogram done
-    // the leading bytes of the r-th largest key (positive side) and of the r-th largest
+    // the remaining bytes of the r-th largest key (positive side) and of the r-th largest
     // complemented key (negative side), one byte per pass
-    uint32_t need[2] = {rs, rs};
-    const bool active[2] = {true, true};
-    uint32_t prefix[2] = {0u, 0u};
 #pragma nounroll
-    for (int pass = 0; pass < passes; ++pass) {
+    for (int pass = first_pass; pass < passes; ++pass) {
         if (pass > 0) {
             const int shift = 24 - 8 * pass;
 #pragma unroll 8

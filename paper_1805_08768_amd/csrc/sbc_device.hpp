@@ -42,6 +42,7 @@ constexpr int kStreamThreads = 256;      // workgroup size of the streaming kern
 constexpr int kSampleThreads = 512;      // workgroup size of the sample kernel
 constexpr int kSelThreads = 1024;        // workgroup size of the select kernel
 constexpr int kSampleMax = 16384;        // entries sampled per tensor for the prefilter threshold
+constexpr int kSampleWindow = 2048;      // leading-16-bit key values counted below the sample's extreme
 
 // first digit of the histogram path: sign, exponent, top three mantissa bits
 constexpr int kL1Bits = 12;
