@@ -291,6 +291,29 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         for (int s = 0; s < 2; ++s) bsize[s] = found[s] ? sh.whist[s][digit[s]] : 0u;
     }
     __syncthreads();                                  // whist shares its space with what follows
+    if (pick && !list.staged && found[0] && found[1] && digit[0] != (uint32_t)(kWindow - 1) &&
+        digit[1] != (uint32_t)(kWindow - 1)) {
+        // Lists too long for LDS: nothing below the threshold's bucket matters any more, and what
+        // lies in or above it usually fits.  One more sweep over global memory copies that part,
+        // and every later sweep runs in LDS.
+        const uint32_t keep[2] = {kc[0] - need[0] + bsize[0], kc[1] - need[1] + bsize[1]};
+        if (keep[0] <= kSelLds && keep[1] <= kSelLds) {        // uniform
+            if (tid < 2) sh.res[3][tid] = 0u;
+            __syncthreads();
+            auto copy_in = [&](int sd, const uint2& e) {
+                if ((e.x >> kWinShift) >= wbase[sd] + digit[sd]) {
+                    const uint32_t q = atomicAdd(&sh.res[3][sd], 1u);
+                    if (q < kSelLds) sh.cand[sd][q] = e;
+                }
+            };
+            sweep<0>(sh, list, [&](const uint2& e) { copy_in(0, e); });
+            sweep<1>(sh, list, [&](const uint2& e) { copy_in(1, e); });
+            __syncthreads();
+            if (sh.res[3][0] != keep[0] || sh.res[3][1] != keep[1]) ok = false;   // cannot happen
+            list.cnt[0] = keep[0]; list.cnt[1] = keep[1];
+            list.staged = true;
+        }
+    }
     SBC_TS(1, 3);
     uint32_t itau[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};
     const bool rankable = found[0] && found[1] && digit[0] != (uint32_t)(kWindow - 1) &&
