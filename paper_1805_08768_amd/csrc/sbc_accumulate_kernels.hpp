@@ -374,10 +374,28 @@ __global__ __launch_bounds__(kStreamThreads) void k_accumulate_filter(
             filter_entry(a.w, idx + 3, lo_p, lo_n, sh, bad);
         }
     } else {
-        for (uint32_t i = tid; i < cnt; i += kStreamThreads) {
-            const float a = r[i] + dw[i];
-            r[i] = a;
-            filter_entry(a, e0 + i, lo_p, lo_n, sh, bad);
+        // a tensor's last, partial chunk, or operands that are only 4-byte aligned: eight entries per
+        // thread in flight at a time (later loads may not pass earlier stores to the same array,
+        // so a plain loop would pay the memory latency once per entry)
+        constexpr int IT = 8;
+        for (uint32_t base = 0; base < cnt; base += IT * kStreamThreads) {
+            float dv[IT], rv[IT];
+#pragma unroll
+            for (int j = 0; j < IT; ++j) {
+                const uint32_t i = base + j * kStreamThreads + tid;
+                const uint32_t ii = i < cnt ? i : 0u;
+                dv[j] = dw[ii];
+                rv[j] = r[ii];
+            }
+#pragma unroll
+            for (int j = 0; j < IT; ++j) {
+                const uint32_t i = base + j * kStreamThreads + tid;
+                if (i < cnt) {
+                    const float a = rv[j] + dv[j];
+                    r[i] = a;
+                    filter_entry(a, e0 + i, lo_p, lo_n, sh, bad);
+                }
+            }
         }
     }
     if (bad) atomicOr(&result->err, kErrNonFinite);
