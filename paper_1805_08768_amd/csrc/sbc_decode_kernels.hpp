@@ -336,13 +336,14 @@ __global__ __launch_bounds__(kDecThreads) void k_decode_accumulate(
 // what k_decode_accumulate carries from tile to tile in registers; here it goes through memory:
 //   k_dec_tile_fn      per tile: every segment's transition function composed with those before
 //                      it in the tile (seg_fn), and the tile's total (tile_fn)
-//   k_dec_tile_entry   per stream: the state in which each tile is entered (tile_entry)
-//   k_dec_tile_sums    per tile: with the entry states known, the unary ones, codes and
-//                      remainder sum before each segment within the tile (seg_pack) and the
-//                      tile's totals (tile_sum)
-//   k_dec_tile_offsets per stream: exclusive sums of the tile totals (tile_off); the code count
-//                      must equal nnz
-//   k_dec_tile_place   per tile: positions, checks, out[j] += fl32(scale * mu)
+//   k_dec_tile_sums    per tile: the state in which the tile is entered, from the totals of the
+//                      tiles before it (tile_entry); then the unary ones, codes and remainder
+//                      sum before each segment within the tile (seg_pack) and the tile's totals
+//                      (tile_sum)
+//   k_dec_tile_place   per tile: the sums of the tiles before it; positions, checks,
+//                      out[j] += fl32(scale * mu); the last tile checks the code count against nnz
+// Every tile folds what precedes it by itself (a few hundred small values), which costs less
+// than a launch per stream in between.
 // --------------------------------------------------------------------------
 struct DecWide {
     uint32_t t;           // tensor
@@ -453,42 +454,42 @@ __global__ __launch_bounds__(kDecThreads) void k_dec_tile_fn(
     if (tid == kDecThreads - 1) tile_fn[dw[which].tile0 + tile] = f;
 }
 
-__global__ __launch_bounds__(1024) void k_dec_tile_entry(
-        const uint8_t* __restrict__ msg, unsigned long long msg_bytes, const DecDesc* __restrict__ dd,
-        const DecWide* __restrict__ dw, int T, int b,
-        const unsigned long long* __restrict__ tile_fn, uint32_t* __restrict__ tile_entry) {
-    constexpr int kBatch = 4096;
-    __shared__ unsigned long long fns[kBatch];
-    __shared__ uint32_t states[kBatch];
-    __shared__ uint32_t s_carry;
-    const int which = blockIdx.x, tid = threadIdx.x;
-    const StreamInfo si = stream_info(msg, msg_bytes, dd, T, b, (int)dw[which].t);
-    const unsigned long long n_tiles = (si.n_seg + kDecThreads - 1) / kDecThreads;
-    if (!si.ok || n_tiles > dw[which].max_tiles) return;   // reported by k_dec_tile_fn
-    if (tid == 0) s_carry = 0u;
-    for (unsigned long long t0 = 0; t0 < n_tiles; t0 += kBatch) {
-        const uint32_t m = (uint32_t)((n_tiles - t0 < (unsigned long long)kBatch) ? n_tiles - t0 : kBatch);
-        __syncthreads();
-        for (uint32_t i = tid; i < m; i += 1024) fns[i] = tile_fn[dw[which].tile0 + t0 + i];
-        __syncthreads();
-        if (tid == 0) {
-            int st = (int)s_carry;
-            for (uint32_t i = 0; i < m; ++i) { states[i] = (uint32_t)st; st = apply_packed(fns[i], st); }
-            s_carry = (uint32_t)st;
-        }
-        __syncthreads();
-        for (uint32_t i = tid; i < m; i += 1024) tile_entry[dw[which].tile0 + t0 + i] = states[i];
+// State in which tile `tile` of a stream is entered: the total functions of tiles 0 .. tile-1
+// applied in order to state 0.  Thread i folds a run of consecutive tiles, the wavefronts scan
+// under composition, and the wavefront totals are walked.  wave_fn: kDecThreads / 64 words of
+// LDS.  Contains a barrier; every thread must call it.  The result is the same in every thread.
+__device__ __forceinline__ int tile_entry_state(const unsigned long long* __restrict__ fn_of_stream, uint32_t tile,
+                                                int S, unsigned long long* wave_fn) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    unsigned long long f = 0ull;
+    for (int s = 0; s < S; ++s) f |= (unsigned long long)s << (4 * s);           // identity
+    const uint32_t per = (tile + kDecThreads - 1) / kDecThreads;
+    for (uint32_t j = 0; j < per; ++j) {
+        const uint32_t i = (uint32_t)tid * per + j;
+        if (i < tile) f = compose_packed(fn_of_stream[i], f, S);
     }
+#pragma unroll
+    for (int dlt = 1; dlt < 64; dlt <<= 1) {
+        const unsigned long long o = __shfl_up(f, dlt, 64);
+        if (lane >= dlt) f = compose_packed(f, o, S);
+    }
+    if (lane == 63) wave_fn[wave] = f;
+    __syncthreads();
+    int st = 0;
+#pragma unroll
+    for (int w = 0; w < kDecThreads / 64; ++w) st = apply_packed(wave_fn[w], st);
+    return st;
 }
 
 __global__ __launch_bounds__(kDecThreads) void k_dec_tile_sums(
         const uint8_t* __restrict__ msg, unsigned long long msg_bytes, const DecDesc* __restrict__ dd,
         const DecWide* __restrict__ dw, int n_wide, int T, int b,
-        const unsigned long long* __restrict__ seg_fn, const uint32_t* __restrict__ tile_entry,
-        unsigned long long* __restrict__ seg_pack, unsigned long long* __restrict__ tile_sum,
-        ResultBlock* __restrict__ result) {
+        const unsigned long long* __restrict__ seg_fn, const unsigned long long* __restrict__ tile_fn,
+        uint32_t* __restrict__ tile_entry, unsigned long long* __restrict__ seg_pack,
+        unsigned long long* __restrict__ tile_sum, ResultBlock* __restrict__ result) {
     __shared__ uint32_t tile_words[kTileWords + kTileSlack];
     __shared__ unsigned long long scratch64[kDecThreads / 64];
+    __shared__ unsigned long long wave_fn[kDecThreads / 64];
     int which; uint32_t tile;
     if (!tile_of_block(dw, n_wide, blockIdx.x, &which, &tile)) return;
     const int tid = threadIdx.x;
@@ -497,7 +498,8 @@ __global__ __launch_bounds__(kDecThreads) void k_dec_tile_sums(
     if (!si.ok || n_tiles > dw[which].max_tiles || tile >= n_tiles) return;
     const unsigned long long w64 = stage_tile(si, tile, tile_words);
     const unsigned long long seg = (unsigned long long)tile * kDecThreads + tid;
-    const int tile_in = (int)tile_entry[dw[which].tile0 + tile];
+    const int tile_in = tile_entry_state(tile_fn + dw[which].tile0, tile, b + 1, wave_fn);
+    if (tid == 0) tile_entry[dw[which].tile0 + tile] = (uint32_t)tile_in;
     const int entry = tid == 0 ? tile_in : apply_packed(seg_fn[dw[which].seg0 + seg - 1], tile_in);
     uint32_t nU = 0u, nT = 0u;
     unsigned long long sR = 0ull;
@@ -523,40 +525,14 @@ __global__ __launch_bounds__(kDecThreads) void k_dec_tile_sums(
     if (tid == 0) tile_sum[dw[which].tile0 + tile] = tot;
 }
 
-__global__ __launch_bounds__(1024) void k_dec_tile_offsets(
-        const uint8_t* __restrict__ msg, unsigned long long msg_bytes, const DecDesc* __restrict__ dd,
-        const DecWide* __restrict__ dw, int T, int b,
-        const unsigned long long* __restrict__ tile_sum, unsigned long long* __restrict__ tile_off,
-        ResultBlock* __restrict__ result) {
-    __shared__ unsigned long long scratch64[1024 / 64];
-    const int which = blockIdx.x, tid = threadIdx.x;
-    const StreamInfo si = stream_info(msg, msg_bytes, dd, T, b, (int)dw[which].t);
-    const unsigned long long n_tiles = (si.n_seg + kDecThreads - 1) / kDecThreads;
-    if (!si.ok || n_tiles > dw[which].max_tiles) return;
-    unsigned long long cU = 0ull, cT = 0ull, cR = 0ull;
-    for (unsigned long long t0 = 0; t0 < n_tiles; t0 += 1024) {
-        const unsigned long long i = t0 + tid;
-        const unsigned long long v = i < n_tiles ? tile_sum[dw[which].tile0 + i] : 0ull;
-        unsigned long long tU, tT, tR;
-        const unsigned long long eU = block_excl_sum<unsigned long long, 1024>(v & 0xFFFFull, &tU, scratch64);
-        const unsigned long long eT = block_excl_sum<unsigned long long, 1024>((v >> 16) & 0xFFFFull, &tT, scratch64);
-        const unsigned long long eR = block_excl_sum<unsigned long long, 1024>(v >> 32, &tR, scratch64);
-        if (i < n_tiles) {
-            unsigned long long* o = tile_off + 3ull * (dw[which].tile0 + i);
-            o[0] = cU + eU; o[1] = cT + eT; o[2] = cR + eR;
-        }
-        cU += tU; cT += tT; cR += tR;
-    }
-    if (tid == 0 && cT != si.nnz) atomicOr(&result->err, kErrCorrupt);
-}
-
 __global__ __launch_bounds__(kDecThreads) void k_dec_tile_place(
         const uint8_t* __restrict__ msg, unsigned long long msg_bytes, const DecDesc* __restrict__ dd,
         const DecWide* __restrict__ dw, int n_wide, int T, int b, float scale,
         const unsigned long long* __restrict__ seg_fn, const uint32_t* __restrict__ tile_entry,
-        const unsigned long long* __restrict__ seg_pack, const unsigned long long* __restrict__ tile_off,
+        const unsigned long long* __restrict__ seg_pack, const unsigned long long* __restrict__ tile_sum,
         ResultBlock* __restrict__ result) {
     __shared__ uint32_t tile_words[kTileWords + kTileSlack];
+    __shared__ unsigned long long scratch64[kDecThreads / 64];
     int which; uint32_t tile;
     if (!tile_of_block(dw, n_wide, blockIdx.x, &which, &tile)) return;
     const int tid = threadIdx.x;
@@ -566,12 +542,26 @@ __global__ __launch_bounds__(kDecThreads) void k_dec_tile_place(
     if (!si.ok || n_tiles > dw[which].max_tiles || tile >= n_tiles) return;
     const unsigned long long w64 = stage_tile(si, tile, tile_words);
     const unsigned long long seg = (unsigned long long)tile * kDecThreads + tid;
+    // unary ones, codes and remainders of the tiles before this one
+    unsigned long long off[3];
+    {
+        unsigned long long part[3] = {0ull, 0ull, 0ull};
+        for (uint32_t i = (uint32_t)tid; i < tile; i += kDecThreads) {
+            const unsigned long long v = tile_sum[dw[which].tile0 + i];
+            part[0] += v & 0xFFFFull; part[1] += (v >> 16) & 0xFFFFull; part[2] += v >> 32;
+        }
+#pragma unroll
+        for (int j = 0; j < 3; ++j) (void)block_excl_sum<unsigned long long, kDecThreads>(part[j], &off[j], scratch64);
+    }
+    if (tile + 1 == n_tiles && tid == 0) {            // the stream's code count must equal nnz
+        const unsigned long long v = tile_sum[dw[which].tile0 + tile];
+        if (off[1] + ((v >> 16) & 0xFFFFull) != si.nnz) atomicOr(&result->err, kErrCorrupt);
+    }
     if (seg >= si.n_seg) return;
     const int tile_in = (int)tile_entry[dw[which].tile0 + tile];
     const int entry = tid == 0 ? tile_in : apply_packed(seg_fn[dw[which].seg0 + seg - 1], tile_in);
     const unsigned long long pk = seg_pack[dw[which].seg0 + seg];
-    const unsigned long long* o = tile_off + 3ull * (dw[which].tile0 + tile);
-    unsigned long long U = o[0] + (pk & 0xFFFFull), Tn = o[1] + ((pk >> 16) & 0xFFFFull), R = o[2] + (pk >> 32);
+    unsigned long long U = off[0] + (pk & 0xFFFFull), Tn = off[1] + ((pk >> 16) & 0xFFFFull), R = off[2] + (pk >> 32);
     const gfloat_ptr out = as_global(dd[t].out);
     const float addend = scale * si.mu;
     const uint32_t n = si.n, nnz = si.nnz;

@@ -84,7 +84,6 @@ struct sbc_ctx {
     unsigned long long* d_seg_pack = nullptr;
     unsigned long long* d_tile_fn = nullptr;
     unsigned long long* d_tile_sum = nullptr;
-    unsigned long long* d_tile_off = nullptr;
     uint32_t* d_tile_entry = nullptr;
     uint64_t dec_seg_cap = 0, dec_tile_cap = 0;
 
@@ -222,7 +221,7 @@ void free_all(sbc_ctx* c) {
     (void)hipFree(c->d_result); (void)hipFree(c->d_dec); (void)hipFree(c->d_dec_blocks);
     if (c->h_dec_blocks) (void)hipHostFree(c->h_dec_blocks);
     (void)hipFree(c->d_dec_wide); (void)hipFree(c->d_seg_fn); (void)hipFree(c->d_seg_pack); (void)hipFree(c->d_tile_fn);
-    (void)hipFree(c->d_tile_sum); (void)hipFree(c->d_tile_off); (void)hipFree(c->d_tile_entry);
+    (void)hipFree(c->d_tile_sum); (void)hipFree(c->d_tile_entry);
     if (c->h_dec_wide) (void)hipHostFree(c->h_dec_wide);
     (void)hipFree(c->d_wide_ids); (void)hipFree(c->d_wide_state); (void)hipFree(c->d_wide_hist);
     (void)hipFree(c->d_wide_acc); (void)hipFree(c->d_wide_tie);
@@ -394,7 +393,6 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     ok = ok && dev_alloc(&c->d_seg_pack, (size_t)c->dec_seg_cap) == hipSuccess;
     ok = ok && dev_alloc(&c->d_tile_fn, (size_t)c->dec_tile_cap) == hipSuccess;
     ok = ok && dev_alloc(&c->d_tile_sum, (size_t)c->dec_tile_cap) == hipSuccess;
-    ok = ok && dev_alloc(&c->d_tile_off, (size_t)c->dec_tile_cap * 3) == hipSuccess;
     ok = ok && dev_alloc(&c->d_tile_entry, (size_t)c->dec_tile_cap) == hipSuccess;
     ok = ok && dev_alloc(&c->d_wide_ids, (size_t)kMaxWide) == hipSuccess;
     ok = ok && dev_alloc(&c->d_wide_state, (size_t)kMaxWide) == hipSuccess;
@@ -864,17 +862,14 @@ int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, siz
     if (c->n_dec_wide > 0) {
         const uint8_t* m8 = static_cast<const uint8_t*>(msg);
         const unsigned long long mb = (unsigned long long)msg_bytes;
-        const dim3 tiles(c->dec_tiles), streams((unsigned)c->n_dec_wide);
+        const dim3 tiles(c->dec_tiles);
         hipLaunchKernelGGL(k_dec_tile_fn, tiles, dim3(kDecThreads), 0, stream, m8, mb, c->d_dec, c->d_dec_wide,
                            c->n_dec_wide, T, b, c->d_seg_fn, c->d_tile_fn, res_dec);
-        hipLaunchKernelGGL(k_dec_tile_entry, streams, dim3(1024), 0, stream, m8, mb, c->d_dec, c->d_dec_wide, T, b,
-                           c->d_tile_fn, c->d_tile_entry);
         hipLaunchKernelGGL(k_dec_tile_sums, tiles, dim3(kDecThreads), 0, stream, m8, mb, c->d_dec, c->d_dec_wide,
-                           c->n_dec_wide, T, b, c->d_seg_fn, c->d_tile_entry, c->d_seg_pack, c->d_tile_sum, res_dec);
-        hipLaunchKernelGGL(k_dec_tile_offsets, streams, dim3(1024), 0, stream, m8, mb, c->d_dec, c->d_dec_wide, T, b,
-                           c->d_tile_sum, c->d_tile_off, res_dec);
+                           c->n_dec_wide, T, b, c->d_seg_fn, c->d_tile_fn, c->d_tile_entry, c->d_seg_pack,
+                           c->d_tile_sum, res_dec);
         hipLaunchKernelGGL(k_dec_tile_place, tiles, dim3(kDecThreads), 0, stream, m8, mb, c->d_dec, c->d_dec_wide,
-                           c->n_dec_wide, T, b, scale, c->d_seg_fn, c->d_tile_entry, c->d_seg_pack, c->d_tile_off,
+                           c->n_dec_wide, T, b, scale, c->d_seg_fn, c->d_tile_entry, c->d_seg_pack, c->d_tile_sum,
                            res_dec);
     }
     SBC_HOST_TS(10);
