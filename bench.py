@@ -8,8 +8,9 @@ sbc_decompress_accumulate of the produced message into a dense accumulator (Golo
 and the server's scaled accumulation).  Inputs are resident in HBM before the timed region.
 
 Prints ONE JSON line.  `value` is entries per second over whole steps (wall clock between two
-device synchronisations; the client call waits for its result, the server calls are enqueued
-with their validation status collected once before the clock stops).  `compress_ms` and
+device synchronisations; the client call waits for its result, the client's next round is
+enqueued into a second message buffer, then the server call on the round's message, whose
+validation status is collected once for all steps before the clock stops).  `compress_ms` and
 `decode_ms` are the latencies of the two calls when each is waited for, from a second loop.  `roofline` is for the dominant kernel, the residual-accumulation pass:
 12 algorithmic bytes per entry (read dW, read R, write R') times the entries of the update,
 divided by that kernel's mean duration measured with HIP events on the launch stream during
@@ -122,7 +123,9 @@ def main() -> int:
         def __init__(self, index):
             self.R = sbc.TensorList(views(torch.zeros(N, dtype=torch.float32, device=dev)))
             self.out = sbc.TensorList(views(torch.zeros(N, dtype=torch.float32, device=dev)))
-            self.msg = sbc.MessageBuffer(torch.zeros(bound, dtype=torch.uint8, device=dev))
+            # two message buffers, used in turn: a round's message is decoded while the next is written
+            self.msgs = [sbc.MessageBuffer(torch.zeros(bound, dtype=torch.uint8, device=dev)) for _ in range(2)]
+            self.msg = self.msgs[0]
             self.stream_obj = torch.cuda.current_stream() if index == 0 else torch.cuda.Stream()
             self.stream = self.stream_obj.cuda_stream     # raw handle, looked up once
             self.ctx = sbc.sbc_create(0, N, T)
@@ -147,7 +150,7 @@ def main() -> int:
             c = clients[s % C]
             if profile_every:
                 sbc.sbc_profile_level(c.ctx, 1 if (s // C) % profile_every == 0 else 0)
-            sbc.sbc_compress_begin(c.ctx, dW_sets[s % n_sets], c.R, P, c.msg, c.stream)
+            sbc.sbc_compress_begin(c.ctx, dW_sets[s % n_sets], c.R, P, c.msgs[(s // C) % 2], c.stream)
 
         total_bytes = 0
         for s in range(first, min(first + C, first + count)):
@@ -155,13 +158,16 @@ def main() -> int:
         for s in range(first, first + count):
             c = clients[s % C]
             nbytes = sbc.sbc_compress_end(c.ctx)
-            sbc.sbc_decompress_accumulate(c.ctx, c.msg, nbytes, P, scale, c.out, c.stream)
             total_bytes += nbytes
             if routes is not None:
                 rt = sbc.sbc_last_route(c.ctx)
                 routes[rt] = routes.get(rt, 0) + 1
+            # the client's next round is enqueued first (it writes the other message buffer), then
+            # the server call on this round's message: the GPU has work while the host comes back
+            # from waiting for the next round's result
             if s + C < first + count:
                 begin(s + C)
+            sbc.sbc_decompress_accumulate(c.ctx, c.msgs[(s // C) % 2], nbytes, P, scale, c.out, c.stream)
         for c in clients:
             sbc.sbc_decode_status(c.ctx, c.stream)
         return total_bytes

@@ -126,8 +126,9 @@ int sbc_compress(sbc_ctx* ctx, void* hip_stream,
 /* The same step in two calls, for callers that keep several independent client steps in flight
  * (one context, one stream and one set of buffers per client): sbc_compress_begin checks its
  * arguments (same meaning and errors as above) and enqueues the step on hip_stream without
- * waiting; sbc_compress_end waits for it, completes the rare tensors that need a second pass,
- * and returns the status and the message size.  Between the two calls the context accepts
+ * waiting; sbc_compress_end waits for that step (not for work the caller has enqueued behind it
+ * on the stream), completes the rare tensors that need a second pass, and returns the status
+ * and the message size.  Between the two calls the context accepts
  * sbc_decompress_accumulate and nothing else (SBC_EINVAL), dW, residual and msg must not be
  * touched, and the host arrays passed to begin are no longer needed.  sbc_compress_end without
  * a pending step returns SBC_EINVAL.  sbc_compress is begin followed by end. */

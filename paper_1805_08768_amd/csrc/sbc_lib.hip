@@ -143,6 +143,7 @@ struct sbc_ctx {
     int profile_level = 0;
     hipEvent_t ev[2 * kNumStages] = {};
     bool ev_ok = false;
+    hipEvent_t ev_result = nullptr;       // recorded behind the copy of a client step's result block
     double stage_ms[kNumStages] = {};
     int64_t stage_calls[kNumStages] = {};
 
@@ -153,6 +154,7 @@ struct sbc_ctx {
         int T = 0, b = 0, slot = 0, force_exact = 0;
         double p = 0.0;
         bool slot_is_new = false, use_history = false, sampled = false, any_bitmap = false;
+        bool wait_on_event = false;   // begin/end form: the wait ends with this step, not with the stream
         bool timed[kNumStages] = {};
         ResultBlock* res_now = nullptr;
         ResultBlock* res_next = nullptr;
@@ -234,6 +236,8 @@ void free_all(sbc_ctx* c) {
     if (c->h_dec) (void)hipHostFree(c->h_dec);
     if (c->h_state) (void)hipHostFree(c->h_state);
     if (c->ev_ok) for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
+    if (c->ev_result) (void)hipEventDestroy(c->ev_result);
+    c->ev_result = nullptr;
     c->ev_ok = false;
 }
 
@@ -282,7 +286,10 @@ void launch_encode_and_gather(sbc_ctx* c, bool profile) {
 // The pending step's result block on its way to the host / waited for.
 int enqueue_result_copy(sbc_ctx* c) {
     if (hipGetLastError() != hipSuccess) return SBC_EHIP;
-    if (hipMemcpyAsync(c->h_result, c->pend.res_now, sizeof(ResultBlock), hipMemcpyDeviceToHost, c->pend.stream) != hipSuccess) {
+    // In the begin/end form an event lets the wait end when this step is done, whatever the caller
+    // has enqueued behind it; the one-call form waits for the stream, which is cheaper.
+    if (hipMemcpyAsync(c->h_result, c->pend.res_now, sizeof(ResultBlock), hipMemcpyDeviceToHost, c->pend.stream) != hipSuccess ||
+        (c->pend.wait_on_event && hipEventRecord(c->ev_result, c->pend.stream) != hipSuccess)) {
         (void)hipGetLastError();
         return SBC_EHIP;
     }
@@ -290,7 +297,7 @@ int enqueue_result_copy(sbc_ctx* c) {
 }
 
 int wait_result(sbc_ctx* c) {
-    if (hipStreamSynchronize(c->pend.stream) != hipSuccess) {
+    if ((c->pend.wait_on_event ? hipEventSynchronize(c->ev_result) : hipStreamSynchronize(c->pend.stream)) != hipSuccess) {
         (void)hipGetLastError();
         return SBC_EHIP;
     }
@@ -420,6 +427,10 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
         } else {
             c->ev_ok = true;
         }
+        if (ok && hipEventCreateWithFlags(&c->ev_result, hipEventDisableTiming) != hipSuccess) {
+            c->ev_result = nullptr;
+            ok = false;
+        }
     }
     if (!ok) {
         (void)hipGetLastError();
@@ -462,8 +473,9 @@ int sbc_set_option(sbc_ctx* c, int option, int value) {
     }
 }
 
-int sbc_compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, float* const* residual,
-                       const int64_t* numel, int n_tensors, double p, void* msg, size_t msg_capacity) {
+static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, float* const* residual,
+                          const int64_t* numel, int n_tensors, double p, void* msg, size_t msg_capacity,
+                          bool wait_on_event) {
     if (!c || !dW || !residual || !numel || !msg || n_tensors <= 0 || !valid_p(p))
         return SBC_EINVAL;
     if (c->pend.active) return SBC_EINVAL;            // one step at a time per context
@@ -630,6 +642,7 @@ int sbc_compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, flo
     for (int st = 0; st < kNumStages; ++st) P.timed[st] = false;
     P.res_now = res_now; P.res_next = res_next; P.d_desc = d_desc; P.msg8 = msg8;
     P.msg_capacity = msg_capacity; P.need = need; P.n_chunks = n_chunks; P.gather_y = gather_y;
+    P.wait_on_event = wait_on_event;
     const int lvl = c->profile_level;
     bool* timed = P.timed;
 
@@ -690,6 +703,11 @@ int sbc_compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, flo
     SBC_HOST_TS(3);
     P.active = true;
     return SBC_OK;
+}
+
+int sbc_compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, float* const* residual,
+                       const int64_t* numel, int n_tensors, double p, void* msg, size_t msg_capacity) {
+    return compress_begin(c, hip_stream, dW, residual, numel, n_tensors, p, msg, msg_capacity, true);
 }
 
 int sbc_compress_end(sbc_ctx* c, size_t* msg_bytes) {
@@ -764,7 +782,7 @@ int sbc_compress(sbc_ctx* c, void* hip_stream, const float* const* dW, float* co
                  const int64_t* numel, int n_tensors, double p, void* msg, size_t msg_capacity,
                  size_t* msg_bytes) {
     if (!msg_bytes) return SBC_EINVAL;
-    const int rc = sbc_compress_begin(c, hip_stream, dW, residual, numel, n_tensors, p, msg, msg_capacity);
+    const int rc = compress_begin(c, hip_stream, dW, residual, numel, n_tensors, p, msg, msg_capacity, false);
     if (rc != SBC_OK) return rc;
     return sbc_compress_end(c, msg_bytes);
 }
