@@ -63,7 +63,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported "
-              "(sharding is described in DESIGN.md only)" % args.gpus, file=sys.stderr)
+              "(nothing here shards over several GPUs)" % args.gpus, file=sys.stderr)
         return 2
 
     import torch
