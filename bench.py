@@ -37,7 +37,7 @@ PROFILE_EVERY = 4            # timed steps between two event-bracketed launches 
 # HBM bytes per launch of k_accumulate_filter on the default workload from two rocprofv3 --pmc
 # runs (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter shows for the plain
 # copy kernel of known size); the figures and commands are in profiles/.
-MEASURED_TRAFFIC_BYTES = 308364197
+MEASURED_TRAFFIC_BYTES = 308429553
 
 
 def main() -> int:
