@@ -71,6 +71,8 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
     __shared__ uint32_t hist[4][2][256];
     __shared__ uint32_t whist[2][kSampleWindow];      // leading 16 key bits, counted down from the extreme
     __shared__ uint32_t wave_ext[2][kSampleThreads / 64];
+    __shared__ uint32_t blist[2][kSampleThreads];     // subsampled variant: the sampled keys of the threshold's bucket
+    __shared__ uint32_t bcnt[2], btau[2];
     __shared__ uint32_t res[4][8];
     __shared__ unsigned long long scratch[kSampleThreads / 64];
     SBC_TS(0, 0);
@@ -191,6 +193,47 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
             first_pass = 2;
         } else {
             need[0] = need[1] = rs;                   // (a found side's need was lowered)
+        }
+        if (sampled && first_pass == 2) {
+            // All 32 bits of the r-th key are wanted: the sampled keys of its bucket (a handful) are
+            // collected and each is ranked against the others; the one that need[s] - 1 others
+            // exceed is the key.  A crowded bucket is left to the byte passes below.
+            if (tid < 2) bcnt[tid] = 0u;
+            __syncthreads();
+#pragma unroll
+            for (int s = 0; s < PER; ++s) {
+                if ((uint32_t)(s * kSampleThreads + tid) < m) {
+                    if ((key[s] >> 16) == prefix[0]) {
+                        const uint32_t q = atomicAdd(&bcnt[0], 1u);
+                        if (q < (uint32_t)kSampleThreads) blist[0][q] = key[s];
+                    }
+                    if ((~key[s] >> 16) == prefix[1]) {
+                        const uint32_t q = atomicAdd(&bcnt[1], 1u);
+                        if (q < (uint32_t)kSampleThreads) blist[1][q] = ~key[s];
+                    }
+                }
+            }
+            __syncthreads();
+            const uint32_t c0 = bcnt[0], c1 = bcnt[1];
+            if (c0 <= (uint32_t)kSampleThreads && c1 <= (uint32_t)kSampleThreads) {      // uniform
+#pragma unroll
+                for (int sd = 0; sd < 2; ++sd) {
+                    const uint32_t cn = sd ? c1 : c0;
+                    if ((uint32_t)tid < cn) {
+                        const uint32_t me = blist[sd][tid];
+                        uint32_t above = 0u, at_least = 0u;
+                        for (uint32_t j = 0; j < cn; ++j) {
+                            const uint32_t o = blist[sd][j];
+                            above += o > me ? 1u : 0u;
+                            at_least += o >= me ? 1u : 0u;
+                        }
+                        if (above < need[sd] && need[sd] <= at_least) btau[sd] = me;   // equal keys write the same value
+                    }
+                }
+                __syncthreads();
+                prefix[0] = btau[0]; prefix[1] = btau[1];
+                first_pass = 4;
+            }
         }
     }
     __syncthreads();
