@@ -173,9 +173,13 @@ __global__ __launch_bounds__(256) void k_gather(const TensorDesc* __restrict__ d
                                                 const uint32_t* __restrict__ stage, uint8_t* __restrict__ msg,
                                                 uint64_t msg_capacity, ResultBlock* __restrict__ result,
                                                 ResultBlock* __restrict__ next_result) {
-    __shared__ unsigned long long scratch64[4];
+    __shared__ unsigned long long part[2][4];
     const int t = blockIdx.x, tid = threadIdx.x;
     const bool lead = (blockIdx.y == 0);
+    // (loaded up front: nothing below depends on the sums until the offsets are needed)
+    const TensorDesc d = desc[t];
+    const uint32_t my_flags = st[t].flags;
+    const unsigned long long bit_len = st[t].bit_len;
     // word offset of this tensor's stream: streams are packed in tensor order
     unsigned long long mine = 0ull, all = 0ull;
     const int upto = (t == 0 && lead) ? T : t;          // workgroup (0, 0) also needs the grand total
@@ -184,12 +188,17 @@ __global__ __launch_bounds__(256) void k_gather(const TensorDesc* __restrict__ d
         all += words;
         if (i < t) mine += words;
     }
-    unsigned long long word_off, tot_all;
-    (void)block_excl_sum<unsigned long long, 256>(mine, &word_off, scratch64);
-    (void)block_excl_sum<unsigned long long, 256>(all, &tot_all, scratch64);
-    const TensorDesc d = desc[t];
-    if (st[t].flags & kStFailed) return;              // this tensor is redone by the histogram path
-    const unsigned long long bit_len = st[t].bit_len;
+    // both sums in one reduction
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        mine += __shfl_down(mine, off, 64);
+        all += __shfl_down(all, off, 64);
+    }
+    if ((tid & 63) == 0) { part[0][tid >> 6] = mine; part[1][tid >> 6] = all; }
+    __syncthreads();
+    const unsigned long long word_off = part[0][0] + part[0][1] + part[0][2] + part[0][3];
+    const unsigned long long tot_all = part[1][0] + part[1][1] + part[1][2] + part[1][3];
+    if (my_flags & kStFailed) return;                 // this tensor is redone by the histogram path
     const unsigned long long n_words = (bit_len + 31ull) >> 5;
     const unsigned long long table_end = 32ull + 24ull * (unsigned)T;
     if (n_words > d.bound_words || table_end + 4ull * (word_off + n_words) > msg_capacity) {
