@@ -234,6 +234,31 @@ def main() -> int:
     if args.breakdown:
         print("per-kernel us (event-bracketed):", breakdown, file=sys.stderr)
 
+    # untimed extra: the server side of one round with 32 participating clients (Alg. 1, server:
+    # decode every client's message and average): 32 decode calls back to back on messages of
+    # this workload (the three resident updates compressed from a zero residual, used in turn), one
+    # status check
+    server32 = None
+    if args.workload != "flat1p5e9":
+        sbc.sbc_set_option(ctx, sbc.SBC_OPT_DEFER_DECODE_STATUS, 1)
+        server_msgs = []
+        for i in range(n_sets):
+            buf = sbc.MessageBuffer(torch.zeros(bound, dtype=torch.uint8, device=dev))
+            for r_t in R.tensors:
+                r_t.zero_()
+            server_msgs.append((buf, sbc.sbc_compress(ctx, dW_sets[i], R, P, buf, stream)))
+        for rep_ in range(2):
+            torch.cuda.synchronize()
+            ts0 = time.perf_counter()
+            for i in range(32):
+                buf, nb = server_msgs[i % n_sets]
+                sbc.sbc_decompress_accumulate(ctx, buf, nb, P, scale, out, stream)
+            sbc.sbc_decode_status(ctx, stream)
+            torch.cuda.synchronize()
+            ts1 = time.perf_counter()
+        server32 = {"clients": 32, "ms_total": (ts1 - ts0) * 1e3, "ms_per_message": (ts1 - ts0) * 1e3 / 32}
+        sbc.sbc_set_option(ctx, sbc.SBC_OPT_DEFER_DECODE_STATUS, 0)
+
     # untimed extra: the same steps with three independent clients in flight, whose latency-bound
     # kernels and host round trips overlap one another's streaming pass
     pipelined = None
@@ -300,6 +325,7 @@ def main() -> int:
         "compress_frac_of_hbm_peak": BYTES_PER_ENTRY * N / (compress_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernel_us": breakdown,
         "pipelined": pipelined,
+        "server_average_32": server32,
         "copy_kernel_GBs": copy_gbs,
         "message_bytes": msg_bytes / args.steps,
         "routes": {"sampled": sum(v for k, v in routes.items() if not k & 1),
