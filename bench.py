@@ -32,7 +32,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 BYTES_PER_ENTRY = 12           # read dW, read R, write R'
 P = 0.001
-PROFILE_EVERY = 4            # timed steps between two event-bracketed launches of the streaming kernel
+PROFILE_EVERY = 8            # timed steps between two event-bracketed launches of the streaming kernel
 
 # HBM bytes per launch of k_accumulate_filter on the default workload from two rocprofv3 --pmc
 # runs (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter shows for the plain

@@ -226,7 +226,9 @@ int sbc_last_mask(sbc_ctx* ctx, int tensor, uint32_t* mask_words, size_t n_words
  * dispatch, so the figure is the kernel's own duration.
  *   level 0  off (default; no events are recorded)
  *   level 1  only the residual-accumulation kernel (the pass that carries the method's
- *            mandatory 12 bytes per entry) is timed
+ *            mandatory 12 bytes per entry) and the kernel launched before it are timed (with
+ *            events on its predecessor too, its own start stamp is not taken while that one
+ *            still drains)
  *   level 2  every kernel is timed
  * sbc_profile_enable sets the level and clears the accumulated totals; sbc_profile_level only
  * sets the level (a caller may time every n-th call and keep adding up). */

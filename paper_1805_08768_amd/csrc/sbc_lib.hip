@@ -254,7 +254,7 @@ int status_of_err(uint32_t err) {
 // Expects c (context), lvl (profile level), stream and timed[] in scope.
 #define SBC_LAUNCH(stage, on, kernel, grid, block, ...)                                                    \
     do {                                                                                                   \
-        if ((on) && (lvl >= 2 || (lvl == 1 && (stage) == kStAccumulate))) {                                \
+        if ((on) && (lvl >= 2 || (lvl == 1 && ((stage) == kStAccumulate || (stage) == kStSample)))) {      \
             hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, c->ev[2 * (stage)], c->ev[2 * (stage) + 1], 0, \
                                   __VA_ARGS__);                                                            \
             timed[stage] = true;                                                                           \
