@@ -207,13 +207,16 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     SBC_TS(1, 0);
     const int t = (int)order[blockIdx.x], tid = threadIdx.x;
     if (tid == 0) sh.any_slow = 0u;
-    if (pass == 1 && !(st[t].flags & kStExact)) return;
+    // (the descriptor and the state words go out together: one round trip instead of three)
     const TensorDesc d = desc[t];
-    if (pass == 0 && (d.flags & kDescWide) && (st[t].flags & kStWideDone)) return;   // done by the grid-wide kernels
-    const uint32_t k = d.k, n = d.n;
-    const bool sampled = (d.flags & kDescSampled) != 0u;
+    const uint32_t st_flags = st[t].flags;
     const uint32_t cnt_p = __builtin_amdgcn_readfirstlane(st[t].cand_cnt[0]);
     const uint32_t cnt_n = __builtin_amdgcn_readfirstlane(st[t].cand_cnt[1]);
+    const uint32_t lo_key_p = st[t].lo_key[0], lo_key_n = st[t].lo_key[1];
+    if (pass == 1 && !(st_flags & kStExact)) return;
+    if (pass == 0 && (d.flags & kDescWide) && (st_flags & kStWideDone)) return;   // done by the grid-wide kernels
+    const uint32_t k = d.k, n = d.n;
+    const bool sampled = (d.flags & kDescSampled) != 0u;
     if (cnt_p > n || cnt_n > n || (sampled && (cnt_p == 0u || cnt_n == 0u))) {
         // (a sampled threshold is the key of an entry of the tensor, so that entry is a candidate)
         if (tid == 0) atomicOr(&result->err, kErrInternal);
@@ -244,7 +247,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     const bool pick = !sampled || cnt_p > d.kcap || cnt_n > d.kcap;
     uint32_t need[2] = {kc[0], kc[1]}, tau[2] = {0u, 0u};
     const bool both[2] = {true, true};
-    const uint32_t wbase[2] = {st[t].lo_key[0] >> kWinShift, st[t].lo_key[1] >> kWinShift};
+    const uint32_t wbase[2] = {lo_key_p >> kWinShift, lo_key_n >> kWinShift};
     bool ok = true;
     for (int i = tid; i < 2 * kWindow; i += kSelThreads) (&sh.whist[0][0])[i] = 0u;
     __syncthreads();
@@ -320,7 +323,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
                           digit[1] != (uint32_t)(kWindow - 1) && bsize[0] <= kRankMax && bsize[1] <= kRankMax;
     if (!pick) {
         // every candidate is kept: the filter key serves as the threshold (no candidate lies below it)
-        tau[0] = st[t].lo_key[0]; tau[1] = st[t].lo_key[1];
+        tau[0] = lo_key_p; tau[1] = lo_key_n;
     } else if (rankable) {
         // The usual case: few entries share the threshold's leading bits.  They are copied out,
         // and every thread ranks one of them against the others by (key descending, index
