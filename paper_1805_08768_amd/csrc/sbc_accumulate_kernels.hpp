@@ -42,6 +42,16 @@ __global__ __launch_bounds__(256) void k_zero_words(uint32_t* __restrict__ p, ui
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0u;
 }
 
+// The result block of a call, copied to pinned host memory (one small dispatch; the runtime's own
+// device-to-host copy of 16 bytes takes longer).
+__global__ void k_publish(ResultBlock* __restrict__ host_dst, const ResultBlock* __restrict__ src) {
+    if (threadIdx.x == 0) {
+        host_dst->msg_bytes = src->msg_bytes;
+        host_dst->pad = src->pad;
+        host_dst->err = src->err;
+    }
+}
+
 __device__ __forceinline__ uint32_t mix32(uint32_t x) {
     x ^= x >> 16; x *= 0x7FEB352Du; x ^= x >> 15; x *= 0x846CA68Bu; x ^= x >> 16;
     return x;

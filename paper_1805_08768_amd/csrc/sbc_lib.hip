@@ -92,6 +92,7 @@ struct sbc_ctx {
     uint32_t* h_chunk_tensor = nullptr;
     uint32_t* h_order = nullptr;
     uint32_t* h_wide_ids = nullptr;
+    ResultBlock* h_result_dev = nullptr;  // h_result as the device addresses it
     ResultBlock* h_result = nullptr;      // compress
     ResultBlock* h_result_dec = nullptr;  // decode (its own block: a decode call may come between begin and end)
     DecDesc* h_dec = nullptr;
@@ -288,7 +289,8 @@ int enqueue_result_copy(sbc_ctx* c) {
     if (hipGetLastError() != hipSuccess) return SBC_EHIP;
     // In the begin/end form an event lets the wait end when this step is done, whatever the caller
     // has enqueued behind it; the one-call form waits for the stream, which is cheaper.
-    if (hipMemcpyAsync(c->h_result, c->pend.res_now, sizeof(ResultBlock), hipMemcpyDeviceToHost, c->pend.stream) != hipSuccess ||
+    hipLaunchKernelGGL(k_publish, dim3(1), dim3(64), 0, c->pend.stream, c->h_result_dev, c->pend.res_now);
+    if (hipGetLastError() != hipSuccess ||
         (c->pend.wait_on_event && hipEventRecord(c->ev_result, c->pend.stream) != hipSuccess)) {
         (void)hipGetLastError();
         return SBC_EHIP;
@@ -414,6 +416,7 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     ok = ok && host_alloc(&c->h_chunk_tensor, (size_t)c->max_chunks) == hipSuccess;
     ok = ok && host_alloc(&c->h_order, T) == hipSuccess;
     ok = ok && host_alloc(&c->h_result, 1) == hipSuccess;
+    ok = ok && hipHostGetDevicePointer(reinterpret_cast<void**>(&c->h_result_dev), c->h_result, 0) == hipSuccess;
     ok = ok && host_alloc(&c->h_result_dec, 1) == hipSuccess;
     ok = ok && host_alloc(&c->h_dec, T) == hipSuccess;
     ok = ok && host_alloc(&c->h_state, T) == hipSuccess;
