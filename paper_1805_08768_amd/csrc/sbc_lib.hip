@@ -470,7 +470,8 @@ int sbc_set_option(sbc_ctx* c, int option, int value) {
         case SBC_OPT_WIDE_MIN_KEPT:
             if (value < 0) return SBC_EINVAL;
             c->wide_min_kept = value ? (uint32_t)value : kWideMinKept;
-            c->cache_valid = false;                    // which tensors are wide is part of the plan
+            c->cache_valid = false;                    // which tensors are wide is part of both plans
+            c->dev_dec_valid = false;
             return SBC_OK;
         default: return SBC_EINVAL;
     }
