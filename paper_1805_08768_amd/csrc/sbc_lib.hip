@@ -284,6 +284,45 @@ void launch_encode_and_gather(sbc_ctx* c, bool profile) {
                c->d_stage, P.msg8, (uint64_t)P.msg_capacity, P.res_now, P.res_next);
 }
 
+// Alg. 2 for the pending step's tensors that keep very many entries, as grid-wide sweeps over
+// their candidate lists with one-workgroup steps in between (the tensors k_select then skips).
+void launch_wide_selection(sbc_ctx* c) {
+    sbc_ctx::Pending& P = c->pend;
+    const int lvl = c->profile_level;
+    hipStream_t stream = P.stream;
+    bool* timed = P.timed;
+    TensorDesc* const d_desc = P.d_desc;
+    ResultBlock* const res_now = P.res_now;
+    const dim3 sweep(c->wide_blocks, (unsigned)c->n_wide), one((unsigned)c->n_wide);
+    const bool time_wide = lvl >= 2;
+    for (int pass = 0; pass < 3; ++pass) {
+        if (pass == 0 && time_wide) {
+            hipExtLaunchKernelGGL(k_wide_count, sweep, dim3(kWideThreads), 0, stream, c->ev[2 * kStWide], nullptr, 0,
+                                  d_desc, c->d_wide_ids, c->d_state, c->d_cand, c->d_wide_state, c->d_wide_hist, pass);
+        } else {
+            hipLaunchKernelGGL(k_wide_count, sweep, dim3(kWideThreads), 0, stream, d_desc, c->d_wide_ids, c->d_state,
+                               c->d_cand, c->d_wide_state, c->d_wide_hist, pass);
+        }
+        hipLaunchKernelGGL(k_wide_pick, one, dim3(kSelThreads), 0, stream, d_desc, c->d_wide_ids, c->d_state,
+                           c->d_wide_state, c->d_wide_hist, pass);
+    }
+    hipLaunchKernelGGL(k_wide_ties, sweep, dim3(kWideThreads), 0, stream, d_desc, c->d_wide_ids, c->d_state,
+                       c->d_cand, c->d_wide_state, c->d_wide_tie);
+    hipLaunchKernelGGL(k_wide_rank, one, dim3(kSelThreads), 0, stream, c->d_wide_ids, c->d_wide_state, c->d_wide_tie);
+    hipLaunchKernelGGL(k_wide_sums, sweep, dim3(kWideThreads), 0, stream, d_desc, c->d_wide_ids, c->d_state,
+                       c->d_cand, c->d_wide_state, c->d_wide_acc);
+    hipLaunchKernelGGL(k_wide_decide, one, dim3(128), 0, stream, d_desc, c->d_wide_ids, c->d_state,
+                       c->d_wide_state, c->d_wide_acc, res_now);
+    if (time_wide) {
+        hipExtLaunchKernelGGL(k_wide_apply, sweep, dim3(kWideThreads), 0, stream, nullptr, c->ev[2 * kStWide + 1], 0,
+                              d_desc, c->d_wide_ids, c->d_state, c->d_cand, c->d_wide_state, c->d_bitmap, res_now);
+        timed[kStWide] = true;
+    } else {
+        hipLaunchKernelGGL(k_wide_apply, sweep, dim3(kWideThreads), 0, stream, d_desc, c->d_wide_ids, c->d_state,
+                           c->d_cand, c->d_wide_state, c->d_bitmap, res_now);
+    }
+}
+
 // The pending step's result block on its way to the host / waited for.
 int enqueue_result_copy(sbc_ctx* c) {
     if (hipGetLastError() != hipSuccess) return SBC_EHIP;
@@ -667,37 +706,7 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
         SBC_LAUNCH(kStAccumulate, true, k_accumulate_filter<false>, dim3(n_chunks), dim3(kStreamThreads), d_desc,
                    c->d_chunk_tensor, c->d_state, c->d_cand, c->d_bitmap, c->d_stage, res_now);
     }
-    if (c->n_wide > 0) {
-        // tensors that keep very many entries: Alg. 2 as grid-wide sweeps over their candidate lists
-        const dim3 sweep(c->wide_blocks, (unsigned)c->n_wide), one((unsigned)c->n_wide);
-        const bool time_wide = lvl >= 2;
-        for (int pass = 0; pass < 3; ++pass) {
-            if (pass == 0 && time_wide) {
-                hipExtLaunchKernelGGL(k_wide_count, sweep, dim3(kWideThreads), 0, stream, c->ev[2 * kStWide], nullptr, 0,
-                                      d_desc, c->d_wide_ids, c->d_state, c->d_cand, c->d_wide_state, c->d_wide_hist, pass);
-            } else {
-                hipLaunchKernelGGL(k_wide_count, sweep, dim3(kWideThreads), 0, stream, d_desc, c->d_wide_ids, c->d_state,
-                                   c->d_cand, c->d_wide_state, c->d_wide_hist, pass);
-            }
-            hipLaunchKernelGGL(k_wide_pick, one, dim3(kSelThreads), 0, stream, d_desc, c->d_wide_ids, c->d_state,
-                               c->d_wide_state, c->d_wide_hist, pass);
-        }
-        hipLaunchKernelGGL(k_wide_ties, sweep, dim3(kWideThreads), 0, stream, d_desc, c->d_wide_ids, c->d_state,
-                           c->d_cand, c->d_wide_state, c->d_wide_tie);
-        hipLaunchKernelGGL(k_wide_rank, one, dim3(kSelThreads), 0, stream, c->d_wide_ids, c->d_wide_state, c->d_wide_tie);
-        hipLaunchKernelGGL(k_wide_sums, sweep, dim3(kWideThreads), 0, stream, d_desc, c->d_wide_ids, c->d_state,
-                           c->d_cand, c->d_wide_state, c->d_wide_acc);
-        hipLaunchKernelGGL(k_wide_decide, one, dim3(128), 0, stream, d_desc, c->d_wide_ids, c->d_state,
-                           c->d_wide_state, c->d_wide_acc, res_now);
-        if (time_wide) {
-            hipExtLaunchKernelGGL(k_wide_apply, sweep, dim3(kWideThreads), 0, stream, nullptr, c->ev[2 * kStWide + 1], 0,
-                                  d_desc, c->d_wide_ids, c->d_state, c->d_cand, c->d_wide_state, c->d_bitmap, res_now);
-            timed[kStWide] = true;
-        } else {
-            hipLaunchKernelGGL(k_wide_apply, sweep, dim3(kWideThreads), 0, stream, d_desc, c->d_wide_ids, c->d_state,
-                               c->d_cand, c->d_wide_state, c->d_bitmap, res_now);
-        }
-    }
+    if (c->n_wide > 0) launch_wide_selection(c);
     SBC_LAUNCH(kStSelect, true, k_select, dim3(T), dim3(kSelThreads), d_desc, c->d_order,
                c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 0, res_now);
     launch_encode_and_gather(c, true);
