@@ -216,6 +216,24 @@ def main() -> int:
         sbc.sbc_compress(ctx, dW_sets[i % n_sets], R, P, msg, stream)
     breakdown = {name: round(ms / max(1, calls) * 1e3, 2) for name, ms, calls in sbc.sbc_profile_read(ctx)}
     sbc.sbc_profile_enable(ctx, 0)
+    # untimed extra: the kernels' durations with the caches flushed before every call (512 MiB,
+    # twice the last-level cache, read in between; a write would leave the cache full of dirty
+    # lines whose write-back the next kernel pays for), against the back-to-back figures above
+    # where part of the residual may still be cached from the previous round
+    cold = None
+    if args.workload != "flat1p5e9":
+        flush = torch.zeros(128 << 20, dtype=torch.int32, device=dev)
+        sbc.sbc_profile_enable(ctx, 2)
+        for i in range(10):
+            flush.sum()
+            torch.cuda.synchronize()
+            sbc.sbc_compress(ctx, dW_sets[i % n_sets], R, P, msg, stream)
+        cold_us = {kernel: round(ms / max(1, calls) * 1e3, 2) for kernel, ms, calls in sbc.sbc_profile_read(ctx)}
+        cold = {"kernel_us": cold_us,
+                "k_accumulate_filter_frac_of_hbm_peak":
+                    BYTES_PER_ENTRY * N / (cold_us["k_accumulate_filter"] * 1e-6) / 1e9 / HBM_PEAK_GBS}
+        sbc.sbc_profile_enable(ctx, 0)
+        del flush
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     src, dst = flat_sets[0], (flat_sets[1] if n_sets > 1 else out.tensors[0])
     for _ in range(3):
@@ -324,6 +342,7 @@ def main() -> int:
         "compress_algorithmic_GBs": BYTES_PER_ENTRY * N / (compress_ms * 1e-3) / 1e9,
         "compress_frac_of_hbm_peak": BYTES_PER_ENTRY * N / (compress_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernel_us": breakdown,
+        "cold_cache": cold,
         "pipelined": pipelined,
         "server_average_32": server32,
         "copy_kernel_GBs": copy_gbs,
