@@ -37,7 +37,7 @@ PROFILE_EVERY = 8            # timed steps between two event-bracketed launches 
 # HBM bytes per launch of k_accumulate_filter on the default workload from two rocprofv3 --pmc
 # runs (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter shows for the plain
 # copy kernel of known size); the figures and commands are in profiles/.
-MEASURED_TRAFFIC_BYTES = 308429553
+MEASURED_TRAFFIC_BYTES = 308450968
 
 
 def main() -> int:
@@ -149,7 +149,7 @@ def main() -> int:
         def begin(s):
             c = clients[s % C]
             if profile_every:
-                sbc.sbc_profile_level(c.ctx, 1 if (s // C) % profile_every == 0 else 0)
+                sbc.sbc_profile_level(c.ctx, 1 if ((s - first) // C) % profile_every == 0 else 0)
             sbc.sbc_compress_begin(c.ctx, dW_sets[s % n_sets], c.R, P, c.msgs[(s // C) % 2], c.stream)
 
         total_bytes = 0
@@ -207,7 +207,10 @@ def main() -> int:
     compress_ms = t_compress * 1e3 / args.steps
     decode_ms = t_decode * 1e3 / args.steps
     k1_ms, k1_calls = prof["k_accumulate_filter"]
-    k1_avg_ms = k1_ms / max(1, k1_calls)
+    if k1_calls == 0:
+        print("bench.py: no timed launch of the streaming kernel", file=sys.stderr)
+        return 1
+    k1_avg_ms = k1_ms / k1_calls
     achieved = BYTES_PER_ENTRY * N / (k1_avg_ms * 1e-3) / 1e9
 
     # untimed extras: per-kernel breakdown, copy yardstick, paper-accounted compression ratio
