@@ -593,3 +593,36 @@ def test_compress_begin_end_interleaved_clients():
     finally:
         for r in runs:
             r.close()
+
+
+def test_config3_in_the_benchmark_call_sequence():
+    """The ResNet-50-shaped workload through the exact call sequence bench.py times: the client's
+    next round is enqueued (begin) into the other message buffer before the server call on the
+    current message, whose status is deferred; messages and the averaged update against the oracle."""
+    sizes = synth.numels(synth.resnet50_shapes())
+    p, scale, rounds = 1e-3, 1.0 / 32.0, 3
+    bound = sbc.sbc_msg_bound(sizes, p)
+    with DeviceRun(sizes) as run:
+        sbc.sbc_set_option(run.ctx, sbc.SBC_OPT_DEFER_DECODE_STATUS, 1)
+        msgs = [torch.zeros(bound, dtype=torch.uint8, device="cuda:0") for _ in range(2)]
+        outs = [torch.zeros(n, dtype=torch.float32, device="cuda:0") for n in sizes]
+        host_dW = [synth.resnet50_update(round_=r) for r in range(rounds)]
+        d_dW = [[torch.from_numpy(x).cuda() for x in upd] for upd in host_dW]
+        R_host = [np.zeros(n, np.float32) for n in sizes]
+        want_out = [np.zeros(n, np.float32) for n in sizes]
+        sbc.sbc_compress_begin(run.ctx, d_dW[0], run.R, p, msgs[0])
+        for s in range(rounds):
+            print("step", s, flush=True)
+            nbytes = sbc.sbc_compress_end(run.ctx)
+            got = msgs[s % 2][:nbytes].cpu().numpy().tobytes()
+            if s + 1 < rounds:
+                sbc.sbc_compress_begin(run.ctx, d_dW[s + 1], run.R, p, msgs[(s + 1) % 2])
+            sbc.sbc_decompress_accumulate(run.ctx, msgs[s % 2], nbytes, p, scale, outs)
+            res = o.compress_model(host_dW[s], R_host, p)
+            want = o.build_message(res)
+            assert got == want, "step %d: message differs" % s
+            o.decode_accumulate(want, sizes, scale, want_out)
+            R_host = [x.R_new for x in res]
+        sbc.sbc_decode_status(run.ctx)
+        for t in range(len(sizes)):
+            assert np.array_equal(outs[t].cpu().numpy(), want_out[t]), "tensor %d: averaged update" % t
