@@ -154,6 +154,26 @@ int sbc_decompress_accumulate(sbc_ctx* ctx, void* hip_stream,
                               const int64_t* numel, int n_tensors, double p,
                               float scale, float* const* out);
 
+/* The server step for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same operation as sbc_decompress_accumulate on the
+ * kernel that decodes one stream per workgroup, without a context: the tables that kernel reads
+ * live in a device array that is part of the loaded library (about 9 KiB on every GPU the library
+ * runs on, held until the process ends), and the call neither allocates, frees, copies to or from
+ * the host nor waits: it enqueues three kernels on hip_stream and returns.
+ *   device       HIP device the stream and all buffers belong to
+ *   msg, out, numel, n_tensors, p, scale   as for sbc_decompress_accumulate
+ *   status       device, 4-byte aligned: receives SBC_OK, SBC_ECORRUPT or SBC_EINTERNAL once the
+ *                stream has passed the call (validation is done on the device)
+ * At most SBC_NOALLOC_MAX_TENSORS tensors per call (SBC_ECAPACITY beyond, nothing enqueued); other
+ * argument errors as for sbc_decompress_accumulate.  All calls on one GPU share the one array,
+ * which keeps the previous call's contents (every call rewrites what it reads): calls on one GPU
+ * must not overlap, i.e. use one stream, or order the streams. */
+#define SBC_NOALLOC_MAX_TENSORS 192
+int sbc_decompress_accumulate_noalloc(int device, void* hip_stream,
+                                      const void* msg, size_t msg_bytes,
+                                      const int64_t* numel, int n_tensors, double p,
+                                      float scale, float* const* out, int32_t* status);
+
 /* Options of a context.  Except for SBC_OPT_SAMPLED_THRESHOLD none of them changes a result:
  * sbc_compress is exact on every route.  It finds each tensor's top-k candidates with a filter key per sign side and, for a tensor
  * whose filter turns out to have kept fewer than k entries, falls back to an exact histogram

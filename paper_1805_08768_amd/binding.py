@@ -36,7 +36,7 @@ EXPORTS = (
     "sbc_create", "sbc_destroy", "sbc_golomb_bstar", "sbc_num_kept", "sbc_msg_bound", "sbc_msg_bound_sampled",
     "sbc_compress", "sbc_compress_begin", "sbc_compress_end", "sbc_decompress_accumulate", "sbc_last_tensor_stats", "sbc_last_mask",
     "sbc_profile_enable", "sbc_profile_level", "sbc_profile_read", "sbc_copy_baseline", "sbc_set_option",
-    "sbc_last_route", "sbc_strerror", "sbc_decode_status",
+    "sbc_last_route", "sbc_strerror", "sbc_decode_status", "sbc_decompress_accumulate_noalloc",
 )
 
 
@@ -100,6 +100,9 @@ def load() -> ctypes.CDLL:
     lib.sbc_last_route.restype = ctypes.c_int
     lib.sbc_decode_status.argtypes = [vp, vp]
     lib.sbc_decode_status.restype = ctypes.c_int
+    lib.sbc_decompress_accumulate_noalloc.argtypes = [ctypes.c_int, vp, vp, sz, ctypes.POINTER(i64), ctypes.c_int,
+                                                      ctypes.c_double, ctypes.c_float, ctypes.POINTER(vp), vp]
+    lib.sbc_decompress_accumulate_noalloc.restype = ctypes.c_int
     lib.sbc_strerror.argtypes = [ctypes.c_int]
     lib.sbc_strerror.restype = ctypes.c_char_p
     _lib = lib
@@ -254,6 +257,24 @@ def sbc_decompress_accumulate(ctx, msg: torch.Tensor, msg_bytes: int, p: float, 
                                           len(out.tensors), p, scale, out.ptrs)
     if rc != SBC_OK:
         raise SbcError(rc, "sbc_decompress_accumulate")
+
+
+def sbc_decompress_accumulate_noalloc(msg: torch.Tensor, msg_bytes: int, p: float, scale: float, out,
+                                      status: torch.Tensor, stream=None, device: int = 0) -> None:
+    """The server step without a context and without any allocation; only enqueues.  `status`
+    (one int32 on the device) receives the validation result once the stream has passed the call."""
+    msg = _as_msg(msg)
+    if msg_bytes > msg.capacity:
+        raise ValueError("msg must be a contiguous uint8 tensor holding msg_bytes bytes")
+    _check_device(status)
+    if status.dtype != torch.int32 or status.numel() < 1:
+        raise ValueError("status must be an int32 device tensor")
+    out = _as_list(out)
+    rc = load().sbc_decompress_accumulate_noalloc(int(device), _stream_handle(stream), msg.ptr, msg_bytes,
+                                                  out.numel_arr, len(out.tensors), p, scale, out.ptrs,
+                                                  ctypes.c_void_p(status.data_ptr()))
+    if rc != SBC_OK:
+        raise SbcError(rc, "sbc_decompress_accumulate_noalloc")
 
 
 def sbc_decode_status(ctx, stream=None) -> None:

@@ -10,6 +10,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <numeric>
 #include <vector>
@@ -343,6 +344,81 @@ int wait_result(sbc_ctx* c) {
         return SBC_EHIP;
     }
     return SBC_OK;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// Server step without any allocation, for callers that cannot call hipMalloc (code under HIP graph
+// capture, tight serving loops, harnesses that forbid allocation).  The tables the decode kernel
+// reads (tensor descriptors, workgroup -> stream table, result block) live in a file-scope device
+// array instead of a context; one small kernel fills them from the launch arguments, the decode
+// kernel of sbc_decompress_accumulate runs on them, and a last kernel stores the status where the
+// caller asked for it.  Nothing is copied to or from the host and nothing waits.
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+struct NoAllocScratch {
+    ResultBlock result[2];
+    DecDesc dec[SBC_NOALLOC_MAX_TENSORS];
+    uint2 blocks[SBC_NOALLOC_MAX_TENSORS + kMaxDecExtra];
+};
+
+// launch arguments of the set-up kernel (kernel arguments may take 4 KiB)
+struct NoAllocArgs {
+    float* out[SBC_NOALLOC_MAX_TENSORS];
+    uint32_t n[SBC_NOALLOC_MAX_TENSORS];
+    uint16_t first_block[SBC_NOALLOC_MAX_TENSORS];
+    uint8_t shares[SBC_NOALLOC_MAX_TENSORS];
+};
+static_assert(sizeof(NoAllocArgs) <= 3584, "must fit the kernel argument segment");
+
+constexpr int kNoAllocMaxDevices = 64;
+
+}  // namespace
+
+// Every GPU the library runs on holds its own copy of this array until the process ends.  In
+// host code the name is only a handle for hipGetSymbolAddress: the address the kernels receive
+// is looked up once per device (noalloc_scratch_of) and kept.
+static __device__ __align__(256) unsigned char scratch[(sizeof(NoAllocScratch) + 255) / 256 * 256];
+
+__global__ __launch_bounds__(256) void k_noalloc_setup(NoAllocScratch* __restrict__ s, NoAllocArgs a, int T) {
+    const int tid = threadIdx.x;
+    // the array keeps the previous call's contents: everything the decode kernel reads is rewritten
+    if (tid < 2) { s->result[tid].err = 0u; s->result[tid].pad = 0u; s->result[tid].msg_bytes = 0ull; }
+    for (int t = tid; t < T; t += 256) {
+        DecDesc d;
+        d.out = a.out[t]; d.n = a.n[t]; d.wide = 0u;
+        s->dec[t] = d;
+        const uint32_t shares = a.shares[t];
+        for (uint32_t sh = 0; sh < shares; ++sh) s->blocks[a.first_block[t] + sh] = make_uint2((uint32_t)t, sh | (shares << 16));
+    }
+}
+
+__global__ void k_noalloc_finish(const NoAllocScratch* __restrict__ s, int32_t* __restrict__ status) {
+    if (threadIdx.x == 0) {
+        const uint32_t err = s->result[0].err;
+        *status = (err & kErrInternal) ? SBC_EINTERNAL : (err & kErrCorrupt) ? SBC_ECORRUPT : SBC_OK;
+    }
+}
+
+namespace {
+
+// Device address of `scratch` on `device` (which must be current), looked up on first use.
+NoAllocScratch* noalloc_scratch_of(int device) {
+    static NoAllocScratch* ptr[kNoAllocMaxDevices] = {};
+    static std::mutex lock;
+    if (device < 0 || device >= kNoAllocMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> g(lock);
+    if (!ptr[device]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        ptr[device] = static_cast<NoAllocScratch*>(p);
+    }
+    return ptr[device];
 }
 
 }  // namespace
@@ -1016,6 +1092,42 @@ int sbc_last_mask(sbc_ctx* c, int tensor, uint32_t* mask_words, size_t n_words) 
         (void)hipGetLastError();
         return SBC_EHIP;
     }
+    return SBC_OK;
+}
+
+int sbc_decompress_accumulate_noalloc(int device, void* hip_stream, const void* msg, size_t msg_bytes,
+                                      const int64_t* numel, int n_tensors, double p, float scale,
+                                      float* const* out, int32_t* status) {
+    if (!msg || !numel || !out || !status || n_tensors <= 0 || !valid_p(p) || device < 0) return SBC_EINVAL;
+    if ((((uintptr_t)msg) & 7u) != 0 || (((uintptr_t)status) & 3u) != 0) return SBC_EINVAL;
+    if (n_tensors > SBC_NOALLOC_MAX_TENSORS || device >= kNoAllocMaxDevices) return SBC_ECAPACITY;
+    const int T = n_tensors;
+    const int b = bstar_of(p);
+    if (b > kMaxB) return SBC_EINVAL;
+    if (msg_bytes < 32 + 24ull * (unsigned)T) return SBC_ECORRUPT;
+    NoAllocArgs a;
+    std::memset(&a, 0, sizeof(a));
+    uint32_t n_blocks = 0, extra = 0;
+    for (int t = 0; t < T; ++t) {
+        if (numel[t] < 1 || numel[t] >= (int64_t)1 << 32 || !out[t] || ((uintptr_t)out[t] & 3u)) return SBC_EINVAL;
+        const int64_t k = kept_of(numel[t], p);
+        uint32_t shares = (uint32_t)std::min<int64_t>(kDecShareMax, std::max<int64_t>(1, k / kDecSharePer));
+        if (extra + shares - 1u > kMaxDecExtra) shares = 1u;
+        extra += shares - 1u;
+        a.out[t] = out[t]; a.n[t] = (uint32_t)numel[t];
+        a.first_block[t] = (uint16_t)n_blocks; a.shares[t] = (uint8_t)shares;
+        n_blocks += shares;
+    }
+    DeviceGuard guard(device);
+    NoAllocScratch* const s = noalloc_scratch_of(device);
+    if (!s) return SBC_EHIP;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    hipLaunchKernelGGL(k_noalloc_setup, dim3(1), dim3(256), 0, stream, s, a, T);
+    hipLaunchKernelGGL(k_decode_accumulate, dim3(n_blocks), dim3(kDecThreads), 0, stream,
+                       static_cast<const uint8_t*>(msg), (unsigned long long)msg_bytes, s->dec, s->blocks, T, b, scale,
+                       &s->result[0], &s->result[1]);
+    hipLaunchKernelGGL(k_noalloc_finish, dim3(1), dim3(64), 0, stream, s, status);
+    if (hipGetLastError() != hipSuccess) return SBC_EHIP;
     return SBC_OK;
 }
 

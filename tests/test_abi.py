@@ -83,6 +83,7 @@ def test_strerror_and_null_arguments():
     assert lib.sbc_compress(None, None, None, None, None, 0, 0.01, None, 0, None) == sbc.SBC_EINVAL
     assert lib.sbc_decompress_accumulate(None, None, None, 0, None, 0, 0.01, 1.0, None) == sbc.SBC_EINVAL
     assert lib.sbc_last_tensor_stats(None, 0, None, None, None, None, None) == sbc.SBC_EINVAL
+    assert lib.sbc_decompress_accumulate_noalloc(0, None, None, 0, None, 0, 0.01, 1.0, None, None) == sbc.SBC_EINVAL
     assert lib.sbc_create(None, 0, 10, 1) == sbc.SBC_EINVAL
     ctx = ctypes.c_void_p()
     assert lib.sbc_create(ctypes.byref(ctx), 0, 0, 1) == sbc.SBC_EINVAL
