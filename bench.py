@@ -34,7 +34,7 @@ BYTES_PER_ENTRY = 12           # read dW, read R, write R'
 P = 0.001
 PROFILE_EVERY = 8            # timed steps between two event-bracketed launches of the streaming kernel
 
-# HBM bytes per launch of k_accumulate_filter on the default workload from two rocprofv3 --pmc
+# HBM bytes per launch of k_client_step on the default workload from two rocprofv3 --pmc
 # runs (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter shows for the plain
 # copy kernel of known size); the figures and commands are in profiles/.
 MEASURED_TRAFFIC_BYTES = 308450968
@@ -49,6 +49,7 @@ def main() -> int:
     ap.add_argument("--breakdown", action="store_true", help="also print per-kernel times to stderr")
     ap.add_argument("--carry-keys", action="store_true",
                     help="set SBC_OPT_CARRY_FILTER_KEYS (filter keys from the previous round instead of sampling)")
+    ap.add_argument("--fused-step", action="store_true", help="set SBC_OPT_FUSED_STEP")
     ap.add_argument("--sampled-threshold", action="store_true",
                     help="set SBC_OPT_SAMPLED_THRESHOLD (the subsampled variant with a noisy amount of sparsity; "
                          "reported for reference, not the benchmark's mode)")
@@ -131,6 +132,8 @@ def main() -> int:
             self.ctx = sbc.sbc_create(0, N, T)
             if args.carry_keys:
                 sbc.sbc_set_option(self.ctx, sbc.SBC_OPT_CARRY_FILTER_KEYS, 1)
+            if args.fused_step:
+                sbc.sbc_set_option(self.ctx, sbc.SBC_OPT_FUSED_STEP, 1)
             if args.sampled_threshold:
                 sbc.sbc_set_option(self.ctx, sbc.SBC_OPT_SAMPLED_THRESHOLD, 1)
             # the server calls only enqueue; their status is collected once, inside the timed region
@@ -206,7 +209,7 @@ def main() -> int:
         t_compress += tb - ta
     compress_ms = t_compress * 1e3 / args.steps
     decode_ms = t_decode * 1e3 / args.steps
-    k1_ms, k1_calls = prof["k_accumulate_filter"]
+    k1_ms, k1_calls = prof["k_client_step"]
     if k1_calls == 0:
         print("bench.py: no timed launch of the streaming kernel", file=sys.stderr)
         return 1
@@ -233,8 +236,8 @@ def main() -> int:
             sbc.sbc_compress(ctx, dW_sets[i % n_sets], R, P, msg, stream)
         cold_us = {kernel: round(ms / max(1, calls) * 1e3, 2) for kernel, ms, calls in sbc.sbc_profile_read(ctx)}
         cold = {"kernel_us": cold_us,
-                "k_accumulate_filter_frac_of_hbm_peak":
-                    BYTES_PER_ENTRY * N / (cold_us["k_accumulate_filter"] * 1e-6) / 1e9 / HBM_PEAK_GBS}
+                "k_client_step_frac_of_hbm_peak":
+                    BYTES_PER_ENTRY * N / (cold_us["k_client_step"] * 1e-6) / 1e9 / HBM_PEAK_GBS}
         sbc.sbc_profile_enable(ctx, 0)
         del flush
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -335,7 +338,7 @@ def main() -> int:
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES if args.workload == "resnet50" else None,
-                     "kernel": "k_accumulate_filter", "kernel_avg_us": k1_avg_ms * 1e3,
+                     "kernel": "k_client_step", "kernel_avg_us": k1_avg_ms * 1e3,
                      "kernel_launches_timed": k1_calls,
                      "algorithmic_bytes_per_launch": BYTES_PER_ENTRY * N},
         "cpu_baseline": cpu,

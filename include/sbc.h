@@ -203,6 +203,10 @@ int sbc_decompress_accumulate_noalloc(int device, void* hip_stream,
  *       must hold sbc_msg_bound_sampled() bytes; set the option on a decoding context as well,
  *       so that it reserves for the longer streams.  The options FORCE_EXACT_PATH and
  *       CARRY_FILTER_KEYS are ignored while it is set.
+ *   SBC_OPT_FUSED_STEP         (0/1, default 0)  1 lets the streaming kernel finish, by itself, every
+ *       tensor that keeps few enough entries for one workgroup (Alg. 2 and Alg. 3 run in the last
+ *       workgroup of the tensor to finish streaming, beside the streaming of the other tensors)
+ *       instead of leaving all of them to the selection kernel that follows.  Same results.
  *   SBC_OPT_DEFER_DECODE_STATUS (0/1, default 0)  1 makes sbc_decompress_accumulate return as
  *       soon as its kernels are enqueued (SBC_OK unless an argument is bad), so that a server can
  *       decode the messages of all clients back to back without waiting for each; validation
@@ -210,7 +214,7 @@ int sbc_decompress_accumulate_noalloc(int device, void* hip_stream,
  *       Every message buffer must stay unchanged until the stream has passed its call.  The
  *       option cannot be changed while a status is outstanding (SBC_EINVAL). */
 enum { SBC_OPT_FORCE_EXACT_PATH = 1, SBC_OPT_CARRY_FILTER_KEYS = 2, SBC_OPT_WIDE_MIN_KEPT = 3,
-       SBC_OPT_SAMPLED_THRESHOLD = 4, SBC_OPT_DEFER_DECODE_STATUS = 5 };
+       SBC_OPT_SAMPLED_THRESHOLD = 4, SBC_OPT_DEFER_DECODE_STATUS = 5, SBC_OPT_FUSED_STEP = 6 };
 int sbc_set_option(sbc_ctx* ctx, int option, int value);
 
 /* With SBC_OPT_DEFER_DECODE_STATUS: waits for hip_stream (the stream the deferred
@@ -224,7 +228,10 @@ int sbc_decode_status(sbc_ctx* ctx, void* hip_stream);
  * SBC_ROUTE_HISTOGRAM (the histogram route ran for at least one tensor), SBC_ROUTE_WIDE (the
  * grid-wide selection kernels completed at least one tensor); SBC_EINVAL (negative) without a
  * successful call. */
-enum { SBC_ROUTE_CARRIED_KEYS = 1, SBC_ROUTE_HISTOGRAM = 2, SBC_ROUTE_WIDE = 4 };
+enum { SBC_ROUTE_CARRIED_KEYS = 1, SBC_ROUTE_HISTOGRAM = 2, SBC_ROUTE_WIDE = 4,
+       SBC_ROUTE_LOOSE_KEYS = 8,    /* some filter key let so many entries pass that the next call samples afresh */
+       SBC_ROUTE_TAKEN_OVER = 16 }; /* a tensor the streaming kernel could not finish was completed by the
+                                       one-workgroup selection kernel in a second pass */
 int sbc_last_route(sbc_ctx* ctx);
 
 /* Inspection of the most recent sbc_compress() on this context, for tests and reports
@@ -235,6 +242,13 @@ int sbc_last_route(sbc_ctx* ctx);
  *   bit_len        : length of the tensor's Golomb stream in bits */
 int sbc_last_tensor_stats(sbc_ctx* ctx, int tensor, double* mu_pos, double* mu_neg,
                           int* side, int64_t* nnz, int64_t* bit_len);
+
+/* Candidates per sign side that the filter of the most recent sbc_compress() let pass for a
+ * tensor that the streaming kernel finished itself (0 for the others: one-chunk tensors, which
+ * need no filter, and tensors selected by the other kernels).  Out pointers are host memory and
+ * may be NULL.  The ratio to the kept count is what a filter key costs ("Sparse Binarization":
+ * the selection works on these instead of the whole tensor). */
+int sbc_last_candidates(sbc_ctx* ctx, int tensor, int64_t* positive, int64_t* negative);
 
 /* Copies the kept-position bitmap of tensor `tensor` from the most recent sbc_compress()
  * into host memory: entry j is bit (j%32) of mask_words[j/32]; n_words must be

@@ -28,15 +28,18 @@ SBC_OPT_CARRY_FILTER_KEYS = 2
 SBC_OPT_WIDE_MIN_KEPT = 3
 SBC_OPT_SAMPLED_THRESHOLD = 4
 SBC_OPT_DEFER_DECODE_STATUS = 5
+SBC_OPT_FUSED_STEP = 6
 SBC_ROUTE_CARRIED_KEYS = 1
 SBC_ROUTE_HISTOGRAM = 2
 SBC_ROUTE_WIDE = 4
+SBC_ROUTE_LOOSE_KEYS = 8
+SBC_ROUTE_TAKEN_OVER = 16
 
 EXPORTS = (
     "sbc_create", "sbc_destroy", "sbc_golomb_bstar", "sbc_num_kept", "sbc_msg_bound", "sbc_msg_bound_sampled",
     "sbc_compress", "sbc_compress_begin", "sbc_compress_end", "sbc_decompress_accumulate", "sbc_last_tensor_stats", "sbc_last_mask",
     "sbc_profile_enable", "sbc_profile_level", "sbc_profile_read", "sbc_copy_baseline", "sbc_set_option",
-    "sbc_last_route", "sbc_strerror", "sbc_decode_status", "sbc_decompress_accumulate_noalloc",
+    "sbc_last_route", "sbc_strerror", "sbc_decode_status", "sbc_decompress_accumulate_noalloc", "sbc_last_candidates",
 )
 
 
@@ -83,6 +86,8 @@ def load() -> ctypes.CDLL:
                                           ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int),
                                           ctypes.POINTER(i64), ctypes.POINTER(i64)]
     lib.sbc_last_tensor_stats.restype = ctypes.c_int
+    lib.sbc_last_candidates.argtypes = [vp, ctypes.c_int, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    lib.sbc_last_candidates.restype = ctypes.c_int
     lib.sbc_last_mask.argtypes = [vp, ctypes.c_int, vp, sz]
     lib.sbc_last_mask.restype = ctypes.c_int
     lib.sbc_profile_enable.argtypes = [vp, ctypes.c_int]
@@ -295,6 +300,15 @@ def sbc_last_tensor_stats(ctx, tensor: int) -> Tuple[float, float, int, int, int
     if rc != SBC_OK:
         raise SbcError(rc, "sbc_last_tensor_stats")
     return mp.value, mn.value, side.value, nnz.value, bl.value
+
+
+def sbc_last_candidates(ctx, tensor: int) -> Tuple[int, int]:
+    """(positive, negative) candidate counts of one tensor of the latest sbc_compress call."""
+    cp, cn = ctypes.c_int64(), ctypes.c_int64()
+    rc = load().sbc_last_candidates(ctx, int(tensor), ctypes.byref(cp), ctypes.byref(cn))
+    if rc != SBC_OK:
+        raise SbcError(rc, "sbc_last_candidates")
+    return cp.value, cn.value
 
 
 def sbc_last_mask(ctx, tensor: int, numel: int) -> torch.Tensor:

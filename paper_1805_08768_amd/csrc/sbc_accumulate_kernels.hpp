@@ -99,9 +99,12 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
         z.kc[0] = z.kc[1] = 0u;
         z.S[0] = z.S[1] = 0.0;
         z.side = 0; z.mu_signed = 0.f; z.nnz = 0u; z.flags = 0u; z.bit_len = 0ull;
+        z.done = 0u; z.pad = 0u; z.cand_seen[0] = z.cand_seen[1] = 0u;
         st[t] = z;
     }
     if (force_exact) return;
+    // a one-chunk tensor that the streaming kernel finishes by itself needs no filter key
+    if ((d.flags & kDescInline) && d.nchunks == 1u && d.n <= 6144u) return;       // (kSmallMaxN of the streaming kernel)
 
     const uint32_t n = d.n;
     const uint32_t m = n < (uint32_t)kSampleMax ? n : (uint32_t)kSampleMax;

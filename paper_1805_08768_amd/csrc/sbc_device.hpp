@@ -14,7 +14,13 @@ namespace sbc {
 __device__ unsigned long long g_phase_clock[3][1024][16];
 #define SBC_TS(k, i) do { if (threadIdx.x == 0 && blockIdx.x < 1024) g_phase_clock[k][blockIdx.x][i] = wall_clock64(); } while (0)
 #define SBC_TS_VAL(k, i, v) do { if (threadIdx.x == 0 && blockIdx.x < 1024) g_phase_clock[k][blockIdx.x][i] = (v); } while (0)
+// the streaming kernel: every workgroup (up to 16384), eight stamps each
+__device__ unsigned long long g_step_clock[16384][8];
+#define SBC_STEP_TS(i) do { if (threadIdx.x == 0 && blockIdx.x < 16384) g_step_clock[blockIdx.x][i] = wall_clock64(); } while (0)
+#define SBC_STEP_VAL(i, v) do { if (threadIdx.x == 0 && blockIdx.x < 16384) g_step_clock[blockIdx.x][i] = (v); } while (0)
 #else
+#define SBC_STEP_TS(i) do {} while (0)
+#define SBC_STEP_VAL(i, v) do {} while (0)
 #define SBC_TS(k, i) do {} while (0)
 #define SBC_TS_VAL(k, i, v) do {} while (0)
 #endif
@@ -62,15 +68,20 @@ constexpr uint32_t kErrCorrupt = 4u;
 constexpr uint32_t kErrPrefilter = 8u;   // not an error: some tensor needs the histogram path
 constexpr uint32_t kErrWide = 32u;       // not an error: the grid-wide selection kernels completed some tensor
 constexpr uint32_t kErrLoose = 16u;      // not an error: a carried-over filter key let far too many entries pass
+constexpr uint32_t kErrDeferred = 64u;   // not an error: a tensor the streaming kernel could not finish itself is left to k_select
 
 // TensorDesc::flags
 constexpr uint32_t kDescFused = 1u;      // sorted and encoded inside the select kernel
 constexpr uint32_t kDescWide = 2u;       // keeps so many entries that the grid-wide selection kernels take it
 constexpr uint32_t kDescSampled = 4u;    // subsampled variant: the sampled threshold decides what is kept
+constexpr uint32_t kDescInline = 8u;     // finished inside the streaming kernel by the last of its workgroups
 // TensorState::flags
 constexpr uint32_t kStFailed = 1u;       // prefilter kept fewer than k candidates on a side
 constexpr uint32_t kStExact = 2u;        // taken over by the histogram path
 constexpr uint32_t kStWideDone = 4u;     // selected and applied by the grid-wide kernels
+constexpr uint32_t kStInlineDone = 8u;   // selected and encoded inside the streaming kernel
+constexpr uint32_t kStResidualDone = 16u; // ... which also applied the residual update (one-chunk tensors)
+constexpr uint32_t kStDeferred = 32u;    // the streaming kernel left this tensor to k_select
 
 // One tensor of the call, built on the host.
 struct TensorDesc {
@@ -86,6 +97,8 @@ struct TensorDesc {
     uint32_t kept_off;    // first entry of this tensor in the kept-index scratch
     uint32_t flags;
     uint32_t kcap;        // most entries a side may keep: k, or min(n, 2k + 64) in the subsampled variant
+    uint32_t grp0;        // first of this tensor's chunk groups
+    uint32_t pad;
 };
 
 // Per-tensor results, written on the device.
@@ -102,6 +115,19 @@ struct alignas(8) TensorState {
     uint32_t nnz;
     uint32_t flags;
     uint64_t bit_len;
+    uint32_t done;         // chunks (or groups of chunks) of this tensor that the streaming kernel has completed
+    uint32_t pad;
+    uint32_t cand_seen[2]; // candidates per side the finishing workgroup found (inspection)
+};
+
+// Per group of kGroupChunks consecutive chunks of a tensor that the streaming kernel finishes
+// itself: how many of the group's chunks have been counted in (a first level, so that the
+// workgroups of a large tensor do not all queue on one counter).
+constexpr int kGroupChunks = 32;
+constexpr int kMaxGroups = 64;           // groups of a tensor the streaming kernel finishes itself
+struct alignas(16) GroupState {
+    uint32_t done;
+    uint32_t pad[3];
 };
 
 // Per-chunk summary of the kept-position bitmap.
@@ -128,6 +154,26 @@ __device__ __forceinline__ uint32_t key_of_bits(uint32_t u) {
 }
 __device__ __forceinline__ uint32_t bits_of_key(uint32_t key) {
     return (key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key;
+}
+
+// Filter keys a following call may start from instead of sampling: this call's exact threshold,
+// lowered by a margin that shrinks with k (the k-th order statistic of similar data moves by
+// about 1/sqrt(k) of the tail's scale from round to round).  Only a filter: a tensor it
+// misleads is noticed and redone through the histogram route.
+__device__ __forceinline__ uint32_t carried_key(uint32_t tau_side_key, uint32_t k) {
+    const float margin = fminf(0.25f, fmaxf(0.04f, 3.0f * rsqrtf((float)k)));
+    const float x = __uint_as_float(bits_of_key(tau_side_key));       // how extreme the k-th entry is
+    const float lo_x = x - margin * fabsf(x) - 1.17549435e-38f;
+    const uint32_t lo = key_of_bits(__float_as_uint(lo_x));
+    return lo > tau_side_key ? tau_side_key : lo;
+}
+
+// A side key moved towards less extreme values by the fraction `margin` of its value.
+__device__ __forceinline__ uint32_t lowered_key(uint32_t side_key, float margin) {
+    const float x = __uint_as_float(bits_of_key(side_key));
+    const float lo_x = x - margin * fabsf(x) - 1.17549435e-38f;
+    const uint32_t lo = key_of_bits(__float_as_uint(lo_x));
+    return lo > side_key ? side_key : lo;
 }
 
 // ----------------------------------------------------------------- scans ----

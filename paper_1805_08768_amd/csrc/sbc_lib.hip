@@ -20,6 +20,7 @@
 #include "sbc_encode_kernels.hpp"
 #include "sbc_decode_kernels.hpp"
 #include "sbc_wide_kernels.hpp"
+#include "sbc_step_kernels.hpp"
 
 using namespace sbc;
 
@@ -28,8 +29,8 @@ namespace {
 enum Stage { kStSample = 0, kStAccumulate, kStWide, kStSelect, kStChunkSummary, kStTensorScan, kStPack,
              kStGather, kNumStages };
 const char* const kStageNames[kNumStages] = {
-    "k_sample_thresholds", "k_accumulate_filter", "k_wide_* (grid-wide selection, all launches)", "k_select",
-    "k_chunk_summary", "k_tensor_scan", "k_pack", "k_gather"};
+    "k_sample_thresholds", "k_client_step", "k_wide_* (grid-wide selection, all launches)", "k_select",
+    "k_chunk_summary", "k_tensor_scan", "k_pack", "k_finish_message"};
 }  // namespace
 
 constexpr int kDescSlots = 4;             // device copies of the tensor table, keyed by the pointer lists
@@ -58,6 +59,9 @@ struct sbc_ctx {
     // ---- device scratch of sbc_compress ----
     TensorDesc* d_desc = nullptr;         // kDescSlots tables of max_tensors entries
     uint32_t* d_chunk_tensor = nullptr;
+    uint2* d_sched = nullptr;             // workgroup of the streaming kernel -> (chunk, tensor)
+    GroupState* d_group = nullptr;        // per group of chunks: candidate and completion counters
+    uint64_t max_groups = 0;
     uint32_t* d_order = nullptr;
     uint32_t* d_hist = nullptr;
     TensorState* d_state = nullptr;
@@ -91,6 +95,7 @@ struct sbc_ctx {
     // ---- pinned host staging ----
     TensorDesc* h_desc = nullptr;
     uint32_t* h_chunk_tensor = nullptr;
+    uint2* h_sched = nullptr;
     uint32_t* h_order = nullptr;
     uint32_t* h_wide_ids = nullptr;
     ResultBlock* h_result_dev = nullptr;  // h_result as the device addresses it
@@ -107,6 +112,8 @@ struct sbc_ctx {
     std::vector<int64_t> cache_numel;
     uint64_t cache_total = 0, cache_chunks = 0, cache_stage_words = 0, cache_kept_total = 0, cache_max_bound = 0;
     bool cache_any_bitmap = false;
+    bool cache_all_inline = false;        // every tensor is finished inside the streaming kernel
+    int cache_force_exact = 0;
     std::vector<TensorDesc> plan;         // without the pointers
     std::vector<uint32_t> plan_order;
     int n_wide = 0;                       // tensors given to the grid-wide selection
@@ -124,6 +131,7 @@ struct sbc_ctx {
     // ---- options ----
     int force_exact = 0;
     int carry_keys = 0;
+    int fused_step = 0;                   // the streaming kernel finishes the tensors it can by itself
     int sampled = 0;                      // subsampled variant: the sampled threshold decides what is kept
     int defer_decode = 0;                 // decode calls return once enqueued; sbc_decode_status reports
     bool deferred_pending = false;        // some deferred decode has not been waited for yet
@@ -155,7 +163,7 @@ struct sbc_ctx {
         hipStream_t stream = nullptr;
         int T = 0, b = 0, slot = 0, force_exact = 0;
         double p = 0.0;
-        bool slot_is_new = false, use_history = false, sampled = false, any_bitmap = false;
+        bool slot_is_new = false, use_history = false, sampled = false, any_bitmap = false, all_inline = false;
         bool wait_on_event = false;   // begin/end form: the wait ends with this step, not with the stream
         bool timed[kNumStages] = {};
         ResultBlock* res_now = nullptr;
@@ -173,6 +181,8 @@ struct sbc_ctx {
     bool last_used_exact_path = false;
     bool last_used_history = false;
     bool last_used_wide = false;
+    bool last_loose = false;
+    bool last_deferred = false;
 };
 
 namespace {
@@ -219,7 +229,7 @@ template <typename T>
 hipError_t host_alloc(T** p, size_t count) { return hipHostMalloc(reinterpret_cast<void**>(p), count * sizeof(T), hipHostMallocDefault); }
 
 void free_all(sbc_ctx* c) {
-    (void)hipFree(c->d_desc); (void)hipFree(c->d_chunk_tensor); (void)hipFree(c->d_order); (void)hipFree(c->d_hist);
+    (void)hipFree(c->d_desc); (void)hipFree(c->d_chunk_tensor); (void)hipFree(c->d_sched); (void)hipFree(c->d_group); (void)hipFree(c->d_order); (void)hipFree(c->d_hist);
     (void)hipFree(c->d_state); (void)hipFree(c->d_cand); (void)hipFree(c->d_bitmap); (void)hipFree(c->d_stage);
     (void)hipFree(c->d_kept); (void)hipFree(c->d_sum); (void)hipFree(c->d_prev_end); (void)hipFree(c->d_bitoff);
     (void)hipFree(c->d_result); (void)hipFree(c->d_dec); (void)hipFree(c->d_dec_blocks);
@@ -232,6 +242,7 @@ void free_all(sbc_ctx* c) {
     if (c->h_wide_ids) (void)hipHostFree(c->h_wide_ids);
     if (c->h_desc) (void)hipHostFree(c->h_desc);
     if (c->h_chunk_tensor) (void)hipHostFree(c->h_chunk_tensor);
+    if (c->h_sched) (void)hipHostFree(c->h_sched);
     if (c->h_order) (void)hipHostFree(c->h_order);
     if (c->h_result) (void)hipHostFree(c->h_result);
     if (c->h_result_dec) (void)hipHostFree(c->h_result_dec);
@@ -281,8 +292,9 @@ void launch_encode_and_gather(sbc_ctx* c, bool profile) {
         SBC_LAUNCH(kStPack, profile, k_pack, dim3(P.n_chunks), dim3(kChunkWords), P.d_desc, c->d_chunk_tensor,
                    c->d_bitmap, c->d_sum, c->d_prev_end, c->d_bitoff, b, c->d_stage, P.res_now);
     }
-    SBC_LAUNCH(kStGather, profile, k_gather, dim3(T, P.gather_y), dim3(256), P.d_desc, c->d_state, T, b,
-               c->d_stage, P.msg8, (uint64_t)P.msg_capacity, P.res_now, P.res_next);
+    SBC_LAUNCH(kStGather, profile, k_finish_message, dim3(T, P.gather_y), dim3(256), P.d_desc, c->d_state, T, b,
+               c->d_stage, c->d_kept, c->d_group, P.msg8, (uint64_t)P.msg_capacity, P.res_now, P.res_next,
+               c->h_result_dev);
 }
 
 // Alg. 2 for the pending step's tensors that keep very many entries, as grid-wide sweeps over
@@ -329,7 +341,7 @@ int enqueue_result_copy(sbc_ctx* c) {
     if (hipGetLastError() != hipSuccess) return SBC_EHIP;
     // In the begin/end form an event lets the wait end when this step is done, whatever the caller
     // has enqueued behind it; the one-call form waits for the stream, which is cheaper.
-    hipLaunchKernelGGL(k_publish, dim3(1), dim3(64), 0, c->pend.stream, c->h_result_dev, c->pend.res_now);
+    // (k_finish_message has written the result block to pinned host memory)
     if (hipGetLastError() != hipSuccess ||
         (c->pend.wait_on_event && hipEventRecord(c->ev_result, c->pend.stream) != hipSuccess)) {
         (void)hipGetLastError();
@@ -494,6 +506,11 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     bool ok = true;
     ok = ok && dev_alloc(&c->d_desc, (size_t)kDescSlots * T) == hipSuccess;
     ok = ok && dev_alloc(&c->d_chunk_tensor, (size_t)c->max_chunks) == hipSuccess;
+    c->max_groups = c->max_chunks / kGroupChunks + (uint64_t)max_tensors;
+    ok = ok && dev_alloc(&c->d_sched, (size_t)c->max_chunks) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_group, (size_t)c->max_groups) == hipSuccess;
+    ok = ok && hipMemset(c->d_group, 0, sizeof(GroupState) * c->max_groups) == hipSuccess;
+    ok = ok && host_alloc(&c->h_sched, (size_t)c->max_chunks) == hipSuccess;
     ok = ok && dev_alloc(&c->d_order, T) == hipSuccess;
     ok = ok && dev_alloc(&c->d_hist, T * kL1Bins) == hipSuccess;
     ok = ok && dev_alloc(&c->d_state, T) == hipSuccess;
@@ -570,8 +587,17 @@ void sbc_destroy(sbc_ctx* c) {
 int sbc_set_option(sbc_ctx* c, int option, int value) {
     if (!c || c->pend.active) return SBC_EINVAL;      // not between sbc_compress_begin and sbc_compress_end
     switch (option) {
-        case SBC_OPT_FORCE_EXACT_PATH: c->force_exact = value ? 1 : 0; c->hist_valid = false; return SBC_OK;
+        case SBC_OPT_FORCE_EXACT_PATH:
+            c->force_exact = value ? 1 : 0;
+            c->hist_valid = false;
+            c->cache_valid = false;                    // which tensors the streaming kernel finishes is part of the plan
+            return SBC_OK;
         case SBC_OPT_CARRY_FILTER_KEYS: c->carry_keys = value ? 1 : 0; c->hist_valid = false; return SBC_OK;
+        case SBC_OPT_FUSED_STEP:
+            c->fused_step = value ? 1 : 0;
+            c->hist_valid = false;
+            c->cache_valid = false;                    // which tensors the streaming kernel finishes is part of the plan
+            return SBC_OK;
         case SBC_OPT_SAMPLED_THRESHOLD:
             c->sampled = value ? 1 : 0;
             c->cache_valid = false;                    // the capacities of the plan depend on it
@@ -611,13 +637,13 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
     // to call while those stay the same.  The tensor table itself (sizes, offsets and the
     // pointers) lives in one of kDescSlots device copies keyed by the pointer lists, so a caller
     // that alternates between a few sets of buffers uploads nothing in the steady state.
-    uint64_t total = 0, chunks = 0, stage_words = 0, kept_total = 0, max_bound = 0;
-    bool any_bitmap = false;
+    uint64_t total = 0, chunks = 0, stage_words = 0, kept_total = 0, max_bound = 0, groups = 0;
+    bool any_bitmap = false, all_inline = true;
     // in the subsampled variant the keys must come from this call's sample
     const bool sampled = c->sampled != 0;
     const int force_exact = sampled ? 0 : c->force_exact;
     bool use_history = !sampled && c->hist_valid && !force_exact && c->hist_p == p && c->hist_n.size() == (size_t)T;
-    const bool sizes_same = c->cache_valid && c->cache_T == T && c->cache_p == p &&
+    const bool sizes_same = c->cache_valid && c->cache_T == T && c->cache_p == p && c->cache_force_exact == force_exact &&
                             std::memcmp(c->cache_numel.data(), numel, sizeof(int64_t) * T) == 0;
     auto pointers_ok = [&](int t) -> bool {
         if (!dW[t] || !residual[t]) return false;
@@ -630,6 +656,7 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
     if (sizes_same) {
         total = c->cache_total; chunks = c->cache_chunks; stage_words = c->cache_stage_words;
         kept_total = c->cache_kept_total; max_bound = c->cache_max_bound; any_bitmap = c->cache_any_bitmap;
+        all_inline = c->cache_all_inline;
         if (use_history)
             for (int t = 0; t < T; ++t) if (c->hist_n[t] != c->plan[t].n) { use_history = false; break; }
         for (int i = 0; i < kDescSlots; ++i) {
@@ -662,7 +689,16 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
             if (bw >= (1ull << 32)) return SBC_ECAPACITY;
             d.bound_words = (uint32_t)bw;
             const bool fused = d.kcap <= kFusedMaxK && bw <= kFusedMaxWords;
-            d.flags = (fused ? kDescFused : 0u) | (sampled ? kDescSampled : 0u);
+            // finished inside the streaming kernel: exact mode, and few enough kept entries and stream
+            // words for one workgroup's LDS (a one-chunk tensor: any k, encoded from a bitmap)
+            const uint32_t n_groups = (d.nchunks + kGroupChunks - 1u) / kGroupChunks;
+            const bool inl = c->fused_step && !sampled && !force_exact && fused && n_groups <= (uint32_t)kMaxGroups &&
+                             (d.nchunks == 1u && d.n <= kSmallMaxN ? bw <= kSmallMaxWords
+                                                                   : (d.kcap <= kInlineMaxK && bw <= kInlineMaxWords));
+            d.flags = (fused ? kDescFused : 0u) | (sampled ? kDescSampled : 0u) | (inl ? kDescInline : 0u);
+            all_inline = all_inline && inl;
+            d.grp0 = (uint32_t)groups;
+            if (inl) groups += n_groups;
             if (!fused && d.kcap >= c->wide_min_kept && n_wide < kMaxWide) {
                 d.flags |= kDescWide;
                 c->h_wide_ids[n_wide++] = (uint32_t)t;
@@ -676,7 +712,7 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
             stage_words += bw;
             max_bound = std::max<uint64_t>(max_bound, bw);
             if (total > (uint64_t)c->max_elems || chunks > c->max_chunks || kept_total > c->kept_cap ||
-                stage_words > c->stage_cap)
+                stage_words > c->stage_cap || groups > c->max_groups)
                 return SBC_ECAPACITY;
             c->plan[t] = d;
         }
@@ -701,8 +737,23 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
             uint32_t* ct = c->h_chunk_tensor + c->plan[t].chunk0;
             for (uint32_t j = 0; j < c->plan[t].nchunks; ++j) ct[j] = (uint32_t)t;
         }
+        // Order of the streaming kernel's workgroups: the one-chunk tensors it finishes on the spot
+        // go first (their selection then runs beside the streaming of everything else), the others
+        // follow by decreasing size, so that the tensors whose completion costs most complete early
+        // and the last workgroups to finish belong to tensors with little left to do.
+        {
+            uint64_t w = 0;
+            for (int pass = 0; pass < 2; ++pass)
+                for (int i = 0; i < T; ++i) {
+                    const TensorDesc& d = c->plan[c->plan_order[i]];
+                    const bool first = (d.flags & kDescInline) && d.nchunks == 1u && d.n <= kSmallMaxN;
+                    if (first != (pass == 0)) continue;
+                    for (uint32_t j = 0; j < d.nchunks; ++j) c->h_sched[w++] = make_uint2(d.chunk0 + j, c->plan_order[i]);
+                }
+        }
         if ((c->n_wide > 0 && hipMemcpyAsync(c->d_wide_ids, c->h_wide_ids, sizeof(uint32_t) * c->n_wide, hipMemcpyHostToDevice, stream) != hipSuccess) ||
             hipMemcpyAsync(c->d_order, c->h_order, sizeof(uint32_t) * T, hipMemcpyHostToDevice, stream) != hipSuccess ||
+            hipMemcpyAsync(c->d_sched, c->h_sched, sizeof(uint2) * chunks, hipMemcpyHostToDevice, stream) != hipSuccess ||
             hipMemcpyAsync(c->d_chunk_tensor, c->h_chunk_tensor, sizeof(uint32_t) * chunks, hipMemcpyHostToDevice, stream) != hipSuccess) {
             (void)hipGetLastError();
             return SBC_EHIP;
@@ -711,6 +762,7 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
         c->cache_T = T; c->cache_p = p;
         c->cache_total = total; c->cache_chunks = chunks; c->cache_stage_words = stage_words;
         c->cache_kept_total = kept_total; c->cache_max_bound = max_bound; c->cache_any_bitmap = any_bitmap;
+        c->cache_all_inline = all_inline; c->cache_force_exact = force_exact;
         // (cache_valid is set once this call has completed: the uploads above must have happened)
     }
     bool slot_is_new = false;
@@ -745,6 +797,8 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
     if (c->result_dirty) {                            // after an error, or on the first call
         hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(c->d_result),
                            (uint64_t)(2 * sizeof(ResultBlock) / 4));
+        hipLaunchKernelGGL(k_zero_words, dim3(64), dim3(256), 0, stream, reinterpret_cast<uint32_t*>(c->d_group),
+                           (uint64_t)c->max_groups * (sizeof(GroupState) / 4));
         use_history = false;
     }
     c->result_dirty = true;                           // until this call has completed normally
@@ -758,6 +812,7 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
     sbc_ctx::Pending& P = c->pend;
     P.stream = stream; P.T = T; P.b = b; P.p = p; P.slot = slot; P.slot_is_new = slot_is_new;
     P.force_exact = force_exact; P.use_history = use_history; P.sampled = sampled; P.any_bitmap = any_bitmap;
+    P.all_inline = all_inline;
     for (int st = 0; st < kNumStages; ++st) P.timed[st] = false;
     P.res_now = res_now; P.res_next = res_next; P.d_desc = d_desc; P.msg8 = msg8;
     P.msg_capacity = msg_capacity; P.need = need; P.n_chunks = n_chunks; P.gather_y = gather_y;
@@ -775,16 +830,28 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
     }
     // 12 bytes per entry pass through; beyond about twice the 256 MiB last-level cache the update
     // is loaded with the nontemporal hint
-    if (total * 12ull > (512ull << 20)) {
-        SBC_LAUNCH(kStAccumulate, true, k_accumulate_filter<true>, dim3(n_chunks), dim3(kStreamThreads), d_desc,
-                   c->d_chunk_tensor, c->d_state, c->d_cand, c->d_bitmap, c->d_stage, res_now);
+    const int carry = c->carry_keys && !sampled && !force_exact ? 1 : 0;
+    if (!c->fused_step) {
+        if (total * 12ull > (512ull << 20)) {
+            SBC_LAUNCH(kStAccumulate, true, k_accumulate_filter<true>, dim3(n_chunks), dim3(kStreamThreads), d_desc,
+                       c->d_chunk_tensor, c->d_state, c->d_cand, c->d_bitmap, c->d_stage, res_now);
+        } else {
+            SBC_LAUNCH(kStAccumulate, true, k_accumulate_filter<false>, dim3(n_chunks), dim3(kStreamThreads), d_desc,
+                       c->d_chunk_tensor, c->d_state, c->d_cand, c->d_bitmap, c->d_stage, res_now);
+        }
+    } else if (total * 12ull > (512ull << 20)) {
+        SBC_LAUNCH(kStAccumulate, true, k_client_step<true>, dim3(n_chunks), dim3(kStepThreads), d_desc, c->d_sched,
+                   c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, c->d_group, b, carry, res_now);
     } else {
-        SBC_LAUNCH(kStAccumulate, true, k_accumulate_filter<false>, dim3(n_chunks), dim3(kStreamThreads), d_desc,
-                   c->d_chunk_tensor, c->d_state, c->d_cand, c->d_bitmap, c->d_stage, res_now);
+        SBC_LAUNCH(kStAccumulate, true, k_client_step<false>, dim3(n_chunks), dim3(kStepThreads), d_desc, c->d_sched,
+                   c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, c->d_group, b, carry, res_now);
     }
-    if (c->n_wide > 0) launch_wide_selection(c);
-    SBC_LAUNCH(kStSelect, true, k_select, dim3(T), dim3(kSelThreads), d_desc, c->d_order,
-               c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 0, res_now);
+    if (!all_inline) {
+        // the tensors the streaming kernel does not finish itself
+        if (c->n_wide > 0) launch_wide_selection(c);
+        SBC_LAUNCH(kStSelect, true, k_select, dim3(T), dim3(kSelThreads), d_desc, c->d_order,
+                   c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 0, res_now);
+    }
     launch_encode_and_gather(c, true);
     SBC_HOST_TS(2);
     const int rc = enqueue_result_copy(c);
@@ -829,26 +896,32 @@ int sbc_compress_end(sbc_ctx* c, size_t* msg_bytes) {
     c->last_used_wide = (err & kErrWide) != 0u;
 
     // ---- histogram path for the tensors whose filter kept fewer than k candidates ----
-    if ((err & kErrPrefilter) && !(err & (kErrInternal | kErrNonFinite))) {
-        c->last_used_exact_path = true;
-        const uint32_t hist_words = (uint32_t)T * kL1Bins;
-        hipLaunchKernelGGL(k_zero_words, dim3((hist_words + 2047) / 2048), dim3(256), 0, stream, c->d_hist,
-                           (uint64_t)hist_words);
+    // ---- second pass: the histogram route for the tensors whose filter kept fewer than k candidates,
+    // and k_select for the tensors the streaming kernel left to it ----
+    const uint32_t loose = err & kErrLoose;
+    c->last_deferred = (err & kErrDeferred) != 0u;
+    if ((err & (kErrPrefilter | kErrDeferred)) && !(err & (kErrInternal | kErrNonFinite))) {
+        c->last_used_exact_path = (err & kErrPrefilter) != 0u;
         hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(res_now),
                            (uint64_t)(sizeof(ResultBlock) / 4));
-        hipLaunchKernelGGL(k_hist_flagged, dim3(P.n_chunks), dim3(kStreamThreads), 0, stream, d_desc,
-                           c->d_chunk_tensor, c->d_state, c->d_hist);
-        hipLaunchKernelGGL(k_pick_bins, dim3(T), dim3(256), 0, stream, d_desc, c->d_hist, c->d_state, res_now);
-        hipLaunchKernelGGL(k_extract, dim3(P.n_chunks), dim3(kStreamThreads), 0, stream, d_desc,
-                           c->d_chunk_tensor, c->d_state, c->d_cand, res_now);
+        if (err & kErrPrefilter) {
+            const uint32_t hist_words = (uint32_t)T * kL1Bins;
+            hipLaunchKernelGGL(k_zero_words, dim3((hist_words + 2047) / 2048), dim3(256), 0, stream, c->d_hist,
+                               (uint64_t)hist_words);
+            hipLaunchKernelGGL(k_hist_flagged, dim3(P.n_chunks), dim3(kStreamThreads), 0, stream, d_desc,
+                               c->d_chunk_tensor, c->d_state, c->d_hist);
+            hipLaunchKernelGGL(k_pick_bins, dim3(T), dim3(256), 0, stream, d_desc, c->d_hist, c->d_state, res_now);
+            hipLaunchKernelGGL(k_extract, dim3(P.n_chunks), dim3(kStreamThreads), 0, stream, d_desc,
+                               c->d_chunk_tensor, c->d_state, c->d_cand, res_now);
+        }
         hipLaunchKernelGGL(k_select, dim3(T), dim3(kSelThreads), 0, stream, d_desc, c->d_order,
                            c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 1, res_now);
         launch_encode_and_gather(c, false);
         rc = enqueue_result_copy(c);
         if (rc == SBC_OK) rc = wait_result(c);
         if (rc != SBC_OK) return rc;
-        err = c->h_result->err;
-        if (err & kErrPrefilter) return SBC_EINTERNAL;
+        err = c->h_result->err | loose;
+        if (err & (kErrPrefilter | kErrDeferred)) return SBC_EINTERNAL;
     }
     const int status = status_of_err(err);
     if (status != SBC_OK) return status;
@@ -856,6 +929,7 @@ int sbc_compress_end(sbc_ctx* c, size_t* msg_bytes) {
     *msg_bytes = (size_t)c->h_result->msg_bytes;
     c->last_ok = true;
     c->last_used_history = P.use_history;
+    c->last_loose = (err & kErrLoose) != 0u;
     c->result_dirty = false;
     // the next call may start from this call's thresholds unless they proved unhelpful
     c->hist_valid = c->carry_keys && !P.sampled && !P.force_exact && !c->last_used_exact_path && !(err & kErrLoose);
@@ -1063,6 +1137,18 @@ int sbc_last_tensor_stats(sbc_ctx* c, int tensor, double* mu_pos, double* mu_neg
     return SBC_OK;
 }
 
+int sbc_last_candidates(sbc_ctx* c, int tensor, int64_t* positive, int64_t* negative) {
+    if (!c || !c->last_ok || tensor < 0 || tensor >= c->last_T) return SBC_EINVAL;
+    DeviceGuard guard(c->device);
+    if (hipMemcpy(c->h_state, c->d_state + tensor, sizeof(TensorState), hipMemcpyDeviceToHost) != hipSuccess) {
+        (void)hipGetLastError();
+        return SBC_EHIP;
+    }
+    if (positive) *positive = (int64_t)c->h_state[0].cand_seen[0];
+    if (negative) *negative = (int64_t)c->h_state[0].cand_seen[1];
+    return SBC_OK;
+}
+
 int sbc_last_mask(sbc_ctx* c, int tensor, uint32_t* mask_words, size_t n_words) {
     if (!c || !c->last_ok || !mask_words || tensor < 0 || tensor >= c->last_T) return SBC_EINVAL;
     const TensorDesc& d = c->plan[tensor];
@@ -1137,12 +1223,16 @@ int sbc_debug_host_times(double* out) { for (int i = 0; i < 16; ++i) out[i] = g_
 int sbc_debug_phase_clocks(unsigned long long* out) {
     return hipMemcpyFromSymbol(out, HIP_SYMBOL(sbc::g_phase_clock), sizeof(unsigned long long) * 3 * 1024 * 16) == hipSuccess ? 0 : -3;
 }
+int sbc_debug_step_clocks(unsigned long long* out) {
+    return hipMemcpyFromSymbol(out, HIP_SYMBOL(sbc::g_step_clock), sizeof(unsigned long long) * 16384 * 8) == hipSuccess ? 0 : -3;
+}
 #endif
 
 int sbc_last_route(sbc_ctx* c) {
     if (!c || !c->last_ok) return SBC_EINVAL;
     return (c->last_used_history ? SBC_ROUTE_CARRIED_KEYS : 0) | (c->last_used_exact_path ? SBC_ROUTE_HISTOGRAM : 0) |
-           (c->last_used_wide ? SBC_ROUTE_WIDE : 0);
+           (c->last_used_wide ? SBC_ROUTE_WIDE : 0) | (c->last_loose ? SBC_ROUTE_LOOSE_KEYS : 0) |
+           (c->last_deferred ? SBC_ROUTE_TAKEN_OVER : 0);
 }
 
 }  // extern "C"

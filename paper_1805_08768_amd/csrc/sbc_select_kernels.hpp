@@ -11,8 +11,7 @@
 //     shifted to the threshold's scale in one 64-bit integer, or one integer per fp32 exponent
 //     where that does not apply), so it does not depend on the order of the list, and is
 //     rounded to fp64 in a fixed order.
-// It then decides the side (positive iff mu+ >= mu-, which for equal counts is S+ >= S-)
-// and applies it:
+// It then decides the side (positive iff mu+ >= mu-) and applies it:
 //   * residual update R[j] = A[j] - mu_signed at the k kept entries;
 //   * tensors flagged kDescFused: the kept indices are sorted in LDS (bucket by leading
 //     index bits, rank inside the bucket), their gaps Golomb-coded into LDS words and the
@@ -213,8 +212,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     const uint32_t cnt_p = __builtin_amdgcn_readfirstlane(st[t].cand_cnt[0]);
     const uint32_t cnt_n = __builtin_amdgcn_readfirstlane(st[t].cand_cnt[1]);
     const uint32_t lo_key_p = st[t].lo_key[0], lo_key_n = st[t].lo_key[1];
-    if (pass == 1 && !(st_flags & kStExact)) return;
+    if (pass == 1 && !(st_flags & (kStExact | kStDeferred))) return;
     if (pass == 0 && (d.flags & kDescWide) && (st_flags & kStWideDone)) return;   // done by the grid-wide kernels
+    if (pass == 0 && (st_flags & kStInlineDone)) return;                          // done by the streaming kernel
     const uint32_t k = d.k, n = d.n;
     const bool sampled = (d.flags & kDescSampled) != 0u;
     if (cnt_p > n || cnt_n > n || (sampled && (cnt_p == 0u || cnt_n == 0u))) {
@@ -226,6 +226,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         // the filter kept too few entries on a side: the histogram path redoes this tensor
         if (tid == 0) {
             st[t].flags = kStFailed;
+            st[t].bit_len = 0ull; st[t].nnz = 0u;
             atomicOr(&result->err, pass == 0 ? kErrPrefilter : kErrInternal);
         }
         return;
@@ -473,8 +474,8 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     }
     SBC_TS(1, 5);                                     // sums done
     const double Sp = Ssum[0], Sn = Ssum[1];
-    // mu+ >= mu-; with equal counts that is S+ >= S-
-    const int chosen = sampled ? ((Sp / (double)kc[0] >= Sn / (double)kc[1]) ? 0 : 1) : ((Sp >= Sn) ? 0 : 1);
+    // Alg. 2 compares the means (sums that differ may still give equal means: the positive side then)
+    const int chosen = (Sp / (double)kc[0] >= Sn / (double)kc[1]) ? 0 : 1;
     const uint32_t kk = kc[chosen];                   // entries this tensor sends
     const float mu32 = (float)((chosen ? Sn : Sp) / (double)kk);
     const float mu_signed = chosen ? -mu32 : mu32;
@@ -486,19 +487,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         st[t].side = chosen ? -1 : 1;
         st[t].mu_signed = mu_signed;
         if (!ok) atomicOr(&result->err, kErrInternal);
-        // Filter keys a following round may start from instead of sampling: this round's exact
-        // threshold, lowered by a margin that shrinks with k (the k-th order statistic of similar
-        // data moves by about 1/sqrt(k) of the tail's scale from round to round).  Only a filter:
-        // if it misleads, the select kernel notices and the histogram path takes over.
-        const float margin = fminf(0.75f, fmaxf(0.04f, 3.0f * rsqrtf((float)k)));
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            const float x = __uint_as_float(bits_of_key(tau[s]));      // how extreme the k-th entry is
-            const float lo_x = x - margin * fabsf(x) - 1.17549435e-38f;
-            uint32_t lo = key_of_bits(__float_as_uint(lo_x));
-            if (lo > tau[s]) lo = tau[s];
-            st[t].lo_key[s] = lo;
-        }
+        // filter keys a following round may start from instead of sampling
+        st[t].lo_key[0] = carried_key(tau[0], k);
+        st[t].lo_key[1] = carried_key(tau[1], k);
         // far more candidates than needed (the lists no longer fit in LDS, or many times k):
         // the next call should estimate its keys afresh
         const uint32_t many = min(kSelLds, 8u * k + 4096u);

@@ -299,9 +299,8 @@ __global__ __launch_bounds__(128) void k_wide_decide(
     const uint32_t k = desc[t].k;
     const double Sp = S[0], Sn = S[1];
     const uint32_t kc[2] = {ws[w].kc[0], ws[w].kc[1]};
-    // mu+ >= mu-; with equal counts that is S+ >= S-
-    const int chosen = (desc[t].flags & kDescSampled) ? ((Sp / (double)kc[0] >= Sn / (double)kc[1]) ? 0 : 1)
-                                                      : ((Sp >= Sn) ? 0 : 1);
+    // Alg. 2 compares the means
+    const int chosen = (Sp / (double)kc[0] >= Sn / (double)kc[1]) ? 0 : 1;
     const float mu32 = (float)((chosen ? Sn : Sp) / (double)kc[chosen]);
     st[t].kc[0] = kc[0]; st[t].kc[1] = kc[1];
     st[t].tau[0] = ws[w].tau[0]; st[t].tau[1] = ws[w].tau[1];

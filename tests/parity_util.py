@@ -12,6 +12,7 @@ from oracle import sbc_oracle as o
 from paper_1805_08768_amd import binding as sbc
 
 REL_TOL = 1e-5  # mu+, mu- and the residual at kept positions, against the fp64 oracle
+FUSED_STEP = 0  # set by the test modules' fixtures: every DeviceRun then sets SBC_OPT_FUSED_STEP
 
 
 def mask_to_positions(words: torch.Tensor, n: int) -> np.ndarray:
@@ -31,6 +32,8 @@ class DeviceRun:
         self.ctx = sbc.sbc_create(dev_index, sum(self.sizes) + slack, len(self.sizes))
         if sampled:
             sbc.sbc_set_option(self.ctx, sbc.SBC_OPT_SAMPLED_THRESHOLD, 1)
+        if FUSED_STEP:
+            sbc.sbc_set_option(self.ctx, sbc.SBC_OPT_FUSED_STEP, 1)
         self.R = [torch.zeros(n, dtype=torch.float32, device=device) for n in self.sizes]
 
     def close(self):

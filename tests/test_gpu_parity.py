@@ -8,9 +8,31 @@ import torch
 
 from oracle import sbc_oracle as o
 from paper_1805_08768_amd import binding as sbc, synth
+import parity_util
 from parity_util import DeviceRun, check_round, mask_to_positions
 
 pytestmark = pytest.mark.gpu
+
+# tests that only run with the default setting of SBC_OPT_FUSED_STEP (the largest inputs, and calls
+# that create their contexts themselves)
+DEFAULT_ONLY = ("test_config5b", "test_config2_companion", "test_tensor_of_many_chunks", "test_unaligned_views",
+                "test_inspection_requires", "test_same_input_twice")
+
+
+@pytest.fixture(autouse=True, params=[0, 1], ids=["plain", "fused"])
+def fused_step(request):
+    """Every test runs with the streaming kernel leaving all tensors to the selection kernel, and
+    with the streaming kernel finishing the tensors it can by itself."""
+    if request.param and request.node.name.startswith(DEFAULT_ONLY):
+        pytest.skip("runs with the default setting only")
+    parity_util.FUSED_STEP = request.param
+    yield request.param
+    parity_util.FUSED_STEP = 0
+
+
+def main_route(ctx):
+    """Which of the three candidate routes the latest call took (without the advisory bits)."""
+    return sbc.sbc_last_route(ctx) & (sbc.SBC_ROUTE_CARRIED_KEYS | sbc.SBC_ROUTE_HISTOGRAM | sbc.SBC_ROUTE_WIDE)
 
 
 def run_rounds(sizes, gen, p, rounds=1, check_decode=True):
@@ -106,7 +128,7 @@ def test_histogram_path_forced():
             R = [np.zeros(n, np.float32) for n in sizes]
             for r in range(2):
                 res = check_round(run, synth.small_model_update(sizes, round_=r), R, p)
-                assert sbc.sbc_last_route(run.ctx) == sbc.SBC_ROUTE_HISTOGRAM
+                assert main_route(run.ctx) == sbc.SBC_ROUTE_HISTOGRAM
                 R = [x.R_new for x in res]
     dWs = [synth.palette_update(200000), np.zeros(70000, np.float32)]
     with DeviceRun([200000, 70000]) as run:
@@ -150,14 +172,14 @@ def test_misleading_sample_falls_back_per_tensor():
     with DeviceRun(sizes) as run:
         R = [np.zeros(n, np.float32) for n in sizes]
         res = check_round(run, dWs, R, 0.001)                # k = 400 for tensor 1
-        assert sbc.sbc_last_route(run.ctx) == sbc.SBC_ROUTE_HISTOGRAM, "the sample was meant to mislead the filter"
+        assert main_route(run.ctx) == sbc.SBC_ROUTE_HISTOGRAM, "the sample was meant to mislead the filter"
         # after a fallback the next round samples again; the residual still holds the planted
         # entries, so it falls back again
         check_round(run, synth.small_model_update(sizes, round_=5), [r.R_new for r in res], 0.001)
-        assert sbc.sbc_last_route(run.ctx) == sbc.SBC_ROUTE_HISTOGRAM
+        assert main_route(run.ctx) == sbc.SBC_ROUTE_HISTOGRAM
     with DeviceRun(sizes) as run:                            # ordinary data: the fast route alone
         check_round(run, synth.small_model_update(sizes, round_=5), [np.zeros(n, np.float32) for n in sizes], 0.001)
-        assert sbc.sbc_last_route(run.ctx) == 0
+        assert main_route(run.ctx) == 0
 
 
 def test_carried_filter_keys():
@@ -177,7 +199,7 @@ def test_carried_filter_keys():
                     x.zero_()
             dWs = [(d * np.float32(sc)).astype(np.float32) for d in synth.small_model_update(sizes, round_=r)]
             res = check_round(run, dWs, R, 0.001, check_decode=(r % 4 == 0))
-            routes.append(sbc.sbc_last_route(run.ctx))
+            routes.append(main_route(run.ctx))
             R = [x.R_new for x in res]
     print("routes", routes)
     assert routes[0] == 0                                    # first round samples
@@ -188,7 +210,7 @@ def test_carried_filter_keys():
         R = [np.zeros(n, np.float32) for n in sizes]
         for r in range(3):
             res = check_round(run, synth.small_model_update(sizes, round_=r), R, 0.001, check_decode=False)
-            assert sbc.sbc_last_route(run.ctx) == 0
+            assert main_route(run.ctx) == 0
             R = [x.R_new for x in res]
 
 
@@ -589,7 +611,7 @@ def test_compress_begin_end_interleaved_clients():
                     mu_pos, mu_neg, side, nnz, bit_len = sbc.sbc_last_tensor_stats(runs[c].ctx, t)
                     assert side == x.side and nnz == x.k
                 R[c] = [x.R_new for x in res]
-            assert sbc.sbc_last_route(runs[2].ctx) == sbc.SBC_ROUTE_HISTOGRAM
+            assert main_route(runs[2].ctx) == sbc.SBC_ROUTE_HISTOGRAM
     finally:
         for r in runs:
             r.close()
