@@ -176,6 +176,30 @@ __device__ __forceinline__ uint32_t lowered_key(uint32_t side_key, float margin)
     return lo > side_key ? side_key : lo;
 }
 
+// Filter key for a following call when this call's candidate list (cnt entries at or beyond
+// cur_side_key, the k-th of them at tau_side_key) is too short to hold the entry of rank r > k
+// that the key should sit at.  The list says nothing about what lies below its own key, so the
+// count above a value x is extrapolated as exp(-x / s).  If the list is clearly longer than k,
+// s comes from the list itself (k entries above tau, cnt above the current key): the slope just
+// below the k-th entry, where entries that were never sent pile up from round to round.
+// Otherwise the whole side is taken as exponential (n / 2 entries in all), which gives
+// s = tau / ln(n / 2k).  Only a filter: if the guess is too tight the histogram route redoes the
+// tensor, if it is too loose the list is longer than it had to be.
+__device__ __forceinline__ uint32_t extrapolated_key(uint32_t tau_side_key, uint32_t cur_side_key, uint32_t k,
+                                                     uint32_t r, uint32_t n, uint32_t cnt) {
+    const uint32_t zero_key = key_of_bits(0u);                          // every entry of the side's sign
+    const float xt = __uint_as_float(bits_of_key(tau_side_key));        // how extreme the k-th entry is
+    const float xc = __uint_as_float(bits_of_key(cur_side_key));        // and the current key
+    if (!(xt > 0.f) || n <= 2u * r) return cur_side_key < zero_key ? cur_side_key : zero_key;
+    float x;
+    if (cnt >= k + k / 8u + 2u && cnt < r && xc > 0.f && xt > xc)
+        x = xc - (xt - xc) * logf((float)r / (float)cnt) / logf((float)cnt / (float)k);
+    else
+        x = xt * (1.f - logf((float)r / (float)k) / logf((float)n / (float)(2u * k)));
+    const uint32_t guess = x > 0.f ? key_of_bits(__float_as_uint(x)) : zero_key;
+    return guess < cur_side_key ? guess : cur_side_key;
+}
+
 // ----------------------------------------------------------------- scans ----
 
 template <typename T>
@@ -306,15 +330,20 @@ struct RunCounter {
 // need exceeds the total, found[s] stays false.  res: 8 words of LDS that nothing else touches
 // until the caller's next barrier, scratch: NT/64 u64 (LDS).  Contains barriers; every thread
 // must call it.
-// Same for a wide digit: hist[s][0..NB-1], PER = NB/NT consecutive bins per thread.
+// Same for a wide digit: hist[s][0..NB-1], PER = NB/NT consecutive bins per thread.  If rank2
+// is given, the same scan also finds the digit at which the count from the top reaches
+// rank2[s] (digit2[s]; 0xFFFFFFFF if the total is smaller); res2: two more words of LDS.
 template <int NB, int NT>
 __device__ __forceinline__ void pick_wide_both(const uint32_t (*hist)[NB], uint32_t (&need)[2],
                                                const bool (&active)[2], uint32_t* res,
-                                               unsigned long long* scratch, uint32_t (&digit)[2], bool (&found)[2]) {
+                                               unsigned long long* scratch, uint32_t (&digit)[2], bool (&found)[2],
+                                               const uint32_t* rank2 = nullptr, uint32_t* res2 = nullptr,
+                                               uint32_t* digit2 = nullptr) {
     constexpr int PER = NB / NT;
     static_assert(PER >= 1 && PER * NT == NB, "bins divide evenly over the threads");
     const int t = threadIdx.x;
     if (t < 8) res[t] = (t & 3) == 0 ? 0xFFFFFFFFu : 0u;       // res[4*s + {0: digit, 1: above}]
+    if (rank2 && t < 2) res2[t] = 0xFFFFFFFFu;
     uint32_t h[2][PER], loc0 = 0u, loc1 = 0u;
 #pragma unroll
     for (int j = 0; j < PER; ++j) {                            // walking from the top digit down
@@ -333,6 +362,8 @@ __device__ __forceinline__ void pick_wide_both(const uint32_t (*hist)[NB], uint3
             if (active[s] && cum[s] < need[s] && need[s] <= cum[s] + h[s][j]) {
                 res[4 * s] = (uint32_t)(NB - 1 - (t * PER + j)); res[4 * s + 1] = cum[s];
             }
+            if (rank2 && active[s] && cum[s] < rank2[s] && rank2[s] <= cum[s] + h[s][j])
+                res2[s] = (uint32_t)(NB - 1 - (t * PER + j));
             cum[s] += h[s][j];
         }
     }
@@ -342,6 +373,7 @@ __device__ __forceinline__ void pick_wide_both(const uint32_t (*hist)[NB], uint3
         digit[s] = res[4 * s];
         found[s] = active[s] && digit[s] != 0xFFFFFFFFu;
         if (found[s]) need[s] -= res[4 * s + 1];
+        if (rank2) digit2[s] = res2[s];
     }
 }
 

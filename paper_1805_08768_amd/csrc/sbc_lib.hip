@@ -161,7 +161,7 @@ struct sbc_ctx {
     struct Pending {
         bool active = false;
         hipStream_t stream = nullptr;
-        int T = 0, b = 0, slot = 0, force_exact = 0;
+        int T = 0, b = 0, slot = 0, force_exact = 0, carry = 0;
         double p = 0.0;
         bool slot_is_new = false, use_history = false, sampled = false, any_bitmap = false, all_inline = false;
         bool wait_on_event = false;   // begin/end form: the wait ends with this step, not with the stream
@@ -831,6 +831,7 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
     // 12 bytes per entry pass through; beyond about twice the 256 MiB last-level cache the update
     // is loaded with the nontemporal hint
     const int carry = c->carry_keys && !sampled && !force_exact ? 1 : 0;
+    P.carry = carry;
     if (!c->fused_step) {
         if (total * 12ull > (512ull << 20)) {
             SBC_LAUNCH(kStAccumulate, true, k_accumulate_filter<true>, dim3(n_chunks), dim3(kStreamThreads), d_desc,
@@ -850,7 +851,7 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
         // the tensors the streaming kernel does not finish itself
         if (c->n_wide > 0) launch_wide_selection(c);
         SBC_LAUNCH(kStSelect, true, k_select, dim3(T), dim3(kSelThreads), d_desc, c->d_order,
-                   c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 0, res_now);
+                   c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 0, carry, res_now);
     }
     launch_encode_and_gather(c, true);
     SBC_HOST_TS(2);
@@ -915,7 +916,7 @@ int sbc_compress_end(sbc_ctx* c, size_t* msg_bytes) {
                                c->d_chunk_tensor, c->d_state, c->d_cand, res_now);
         }
         hipLaunchKernelGGL(k_select, dim3(T), dim3(kSelThreads), 0, stream, d_desc, c->d_order,
-                           c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 1, res_now);
+                           c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 1, P.carry, res_now);
         launch_encode_and_gather(c, false);
         rc = enqueue_result_copy(c);
         if (rc == SBC_OK) rc = wait_result(c);

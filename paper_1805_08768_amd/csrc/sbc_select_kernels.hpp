@@ -200,7 +200,7 @@ __device__ __forceinline__ long long exponent_sums(SelectShared& sh, const CandL
 __global__ __launch_bounds__(kSelThreads) void k_select(
         const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ order,
         TensorState* __restrict__ st, const uint2* __restrict__ cand, uint32_t* __restrict__ bitmap,
-        uint32_t* __restrict__ stage, uint32_t* __restrict__ kept_idx, int b, int pass,
+        uint32_t* __restrict__ stage, uint32_t* __restrict__ kept_idx, int b, int pass, int carry,
         ResultBlock* __restrict__ result) {
     __shared__ SelectShared sh;
     SBC_TS(1, 0);
@@ -231,6 +231,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         }
         return;
     }
+    if (tid == 0) { st[t].cand_seen[0] = cnt_p; st[t].cand_seen[1] = cnt_n; }    // (inspection only)
     SBC_TS(1, 1);                                     // descriptor and counts read
     SBC_TS_VAL(1, 13, cnt_p); SBC_TS_VAL(1, 14, cnt_n); SBC_TS_VAL(1, 15, (unsigned)t);
     CandLists list;
@@ -288,8 +289,19 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     uint32_t digit[2] = {0u, 0u};
     bool found[2] = {false, false};
     uint32_t bsize[2] = {0u, 0u};
+    // Filter keys a following call may start from instead of sampling.  With the residual carried
+    // over, the k-th entry sits at the edge of a cliff (everything above it has just been cut down
+    // to about mu), so a margin in value below it lets a flood of entries pass, while a margin in
+    // rank does not: the key is the lower edge of the window bin of this call's r-th most extreme
+    // entry, r = 2 k + 4 sqrt(k) + 16 (if the next update is small beside the residual, the k
+    // entries kept now are gone from above that key, and k more must remain).  A list shorter
+    // than r says nothing about that entry: its place is extrapolated from the k-th.
+    const uint32_t r_next = 2u * k + 4u * (uint32_t)sqrtf((float)k) + 16u;
+    uint32_t digit2[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};
     if (pick) {
-        pick_wide_both<kWindow, kSelThreads>(sh.whist, need, both, sh.res[0], sh.scratch64, digit, found);
+        const uint32_t rank2[2] = {r_next, r_next};
+        pick_wide_both<kWindow, kSelThreads>(sh.whist, need, both, sh.res[0], sh.scratch64, digit, found,
+                                             carry ? rank2 : nullptr, sh.res[1], digit2);
         // entries in each side's threshold bucket (same leading key bits as the k-th entry)
 #pragma unroll
         for (int s = 0; s < 2; ++s) bsize[s] = found[s] ? sh.whist[s][digit[s]] : 0u;
@@ -488,8 +500,12 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         st[t].mu_signed = mu_signed;
         if (!ok) atomicOr(&result->err, kErrInternal);
         // filter keys a following round may start from instead of sampling
-        st[t].lo_key[0] = carried_key(tau[0], k);
-        st[t].lo_key[1] = carried_key(tau[1], k);
+        if (carry) {
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+                st[t].lo_key[s] = digit2[s] != 0xFFFFFFFFu ? (wbase[s] + digit2[s]) << kWinShift
+                                                           : extrapolated_key(tau[s], s ? lo_key_n : lo_key_p, k, r_next, n, s ? cnt_n : cnt_p);
+        }
         // far more candidates than needed (the lists no longer fit in LDS, or many times k):
         // the next call should estimate its keys afresh
         const uint32_t many = min(kSelLds, 8u * k + 4096u);

@@ -279,21 +279,23 @@ __device__ __forceinline__ Decision select_tensor(StepShared& sh, int& parity, c
     bool found[2];
     pick_wide_both<kStepWindow, kStepThreads>(sh.whist(), need, both, sh.res[0], sh.scratch64, digit, found);
     uint32_t next_key[2] = {lo_cur[0], lo_cur[1]};
+    bool short_list[2] = {false, false};
+    const uint32_t r_next = 2u * k + 4u * (uint32_t)sqrtf((float)k) + 16u;
     if (carry) {                                          // uniform
         // With the residual carried over, the k-th entry sits at the edge of a cliff (everything above
         // it has just been cut down to about mu), so a margin in value below it lets a flood of
         // entries pass, while a margin in rank does not: the key is the lower edge of the bin of this
         // call's r-th most extreme entry, r = 2 k + 4 sqrt(k) + 16 (if the next update is small beside
         // the residual, the k entries kept now are gone from above that key, and k more must
-        // remain).  A list shorter than r keeps its current key, lowered by a tenth.
-        const uint32_t r_next = 2u * k + 4u * (uint32_t)sqrtf((float)k) + 16u;
+        // remain).  A list shorter than r says nothing about that entry: its place is extrapolated
+        // from the k-th, once that is known.
         uint32_t need2[2] = {min(r_next, cnt[0]), min(r_next, cnt[1])}, digit2[2];
         bool found2[2];
         pick_wide_both<kStepWindow, kStepThreads>(sh.whist(), need2, both, sh.res[1], sh.scratch64, digit2, found2);
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             if (cnt[s] >= r_next && found2[s]) next_key[s] = mn[s] + (digit2[s] << shift[s]);
-            else next_key[s] = lowered_key(lo_cur[s], 0.1f);
+            else short_list[s] = true;
         }
     }
     if (!found[0] || !found[1]) {                         // uniform; cannot happen: each side holds at least k entries
@@ -429,7 +431,11 @@ __device__ __forceinline__ Decision select_tensor(StepShared& sh, int& parity, c
         st_t->S[0] = S[0]; st_t->S[1] = S[1];
         st_t->side = dec.chosen ? -1 : 1;
         st_t->mu_signed = dec.mu_signed;
-        if (carry) { st_t->lo_key[0] = next_key[0]; st_t->lo_key[1] = next_key[1]; }
+        if (carry) {
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+                st_t->lo_key[s] = short_list[s] ? extrapolated_key(tau[s], lo_cur[s], k, r_next, d.n, cnt[s]) : next_key[s];
+        }
     }
     return dec;
 }
