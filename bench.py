@@ -10,17 +10,29 @@ and the server's scaled accumulation).  Inputs are resident in HBM before the ti
 Prints ONE JSON line.  `value` is entries per second over whole steps (wall clock between two
 device synchronisations; the client call waits for its result, the client's next round is
 enqueued into a second message buffer, then the server call on the round's message, whose
-validation status is collected once for all steps before the clock stops).  `compress_ms` and
-`decode_ms` are the latencies of the two calls when each is waited for, from a second loop.  `roofline` is for the dominant kernel, the residual-accumulation pass:
-12 algorithmic bytes per entry (read dW, read R, write R') times the entries of the update,
-divided by that kernel's mean duration measured with HIP events on the launch stream during
-the timed steps.  `cpu_baseline` is the CPU oracle timed on this machine's host cores.
+validation status is collected once for all steps before the clock stops); the median and the
+minimum of the single steps' periods stand beside the mean.  `compress_ms` and `decode_ms` are
+the latencies of the two calls when each is waited for, from a second loop.
+
+`roofline` is for the dominant kernel, the residual-accumulation pass: 12 algorithmic bytes per
+entry (read dW, read R, write R') times the entries of the update, divided by that kernel's
+duration measured with HIP events on the launch stream.  Its headline figures (`frac`,
+`achieved`, `kernel_avg_us`) are taken with the caches flushed before every call, so that no
+part of the residual is still in the last-level cache from the round before; `timed_region`
+holds the same kernel's duration on the launches inside the timed steps (back to back, partly
+cache-warm).  `step_frac` is the same byte count over the whole compress call.  `traffic` is
+read from the committed counter summary under profiles/, with its source beside it.
+`cpu_baseline` is the CPU oracle timed on this machine's host cores: on one core, and with
+the tensors dealt out over all cores the process may use.
 """
 from __future__ import annotations
 
 import argparse
 import json
+import multiprocessing
 import os
+import re
+import statistics
 import sys
 import time
 
@@ -32,12 +44,116 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 BYTES_PER_ENTRY = 12           # read dW, read R, write R'
 P = 0.001
-PROFILE_EVERY = 8            # timed steps between two event-bracketed launches of the streaming kernel
+PROFILE_EVERY = 4            # timed steps between two event-bracketed launches of the streaming kernel
+COLD_LAUNCHES = 12           # calls with the caches flushed before each
+CPU_ROUNDS = 3               # rounds of the whole update the CPU oracle is timed on, per leg
 
-# HBM bytes per launch of k_client_step on the default workload from two rocprofv3 --pmc
-# runs (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter shows for the plain
-# copy kernel of known size); the figures and commands are in profiles/.
-MEASURED_TRAFFIC_BYTES = 308450968
+# HBM bytes per launch of the streaming kernel on the default workload come from two rocprofv3
+# --pmc runs (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter shows for the
+# plain copy kernel of known size); the summary of those runs is read at run time.
+TRAFFIC_SUMMARY = os.path.join("profiles", "bench_resnet50_hbm_counters.md")
+
+
+def traffic_from_profile():
+    """(bytes per launch, kernel name, source) from the committed counter summary, or (None, None, None)."""
+    try:
+        text = open(os.path.join(ROOT, TRAFFIC_SUMMARY)).read()
+    except OSError:
+        return None, None, None
+    m = re.search(r"^HBM traffic per launch of (\S+) = (\d+) bytes", text, flags=re.M)
+    if not m:
+        return None, None, None
+    return int(m.group(2)), m.group(1), TRAFFIC_SUMMARY
+
+
+# ---------------------------------------------------------------------------------------------
+# CPU baseline: the oracle as it stands, in child processes that never touch the GPU.  They are
+# started before the parent's first GPU call and wait for their work until the GPU part is over.
+# ---------------------------------------------------------------------------------------------
+def _cpu_worker(conn):
+    import numpy as np
+    from oracle import sbc_oracle as oracle
+    updates, sizes, p, scale = None, None, None, None
+    while True:
+        msg = conn.recv()
+        if msg[0] == "data":                       # the worker's tensors of every round (untimed)
+            _, updates, p, scale = msg
+            sizes = [len(d) for d in updates[0]]
+            conn.send(("ready", os.getpid()))
+        elif msg[0] == "go":                       # Alg. 1 on those tensors: client rounds + server accumulation
+            t0 = time.perf_counter()
+            R = [np.zeros(n, np.float32) for n in sizes]
+            accs = [np.zeros(n, np.float32) for n in sizes]
+            nbytes = 0
+            for dWs in updates:
+                res = oracle.compress_model(dWs, R, p)
+                R = [x.R_new for x in res]
+                m = oracle.build_message(res)
+                nbytes += len(m)
+                oracle.decode_accumulate(m, sizes, scale, accs)
+            conn.send(("done", time.perf_counter() - t0, nbytes))
+        else:
+            return
+
+
+class CpuBaseline:
+    """One child process per usable core, each with a share of the tensors (largest first, always
+    to the least loaded: the tensors of a model are compressed independently, Alg. 2)."""
+
+    def __init__(self):
+        self.cores = sorted(os.sched_getaffinity(0))
+        ctx = multiprocessing.get_context("spawn")
+        self.workers = []
+        for _ in self.cores:
+            parent, child = ctx.Pipe()
+            pr = ctx.Process(target=_cpu_worker, args=(child,), daemon=True)
+            pr.start()
+            child.close()
+            self.workers.append((pr, parent))
+
+    def _leg(self, n_workers, host_sets, sizes, p, scale):
+        order = sorted(range(len(sizes)), key=lambda t: -sizes[t])
+        load, share = [0] * n_workers, [[] for _ in range(n_workers)]
+        for t in order:
+            w = min(range(n_workers), key=lambda i: load[i])
+            share[w].append(t)
+            load[w] += sizes[t]
+        used = [w for w in range(n_workers) if share[w]]
+        for w in used:
+            self.workers[w][1].send(("data", [[h[t] for t in share[w]] for h in host_sets], p, scale))
+        for w in used:
+            assert self.workers[w][1].recv()[0] == "ready"
+        t0 = time.perf_counter()
+        for w in used:
+            self.workers[w][1].send(("go",))
+        results = [self.workers[w][1].recv() for w in used]
+        wall = time.perf_counter() - t0
+        n_total = sum(sizes) * len(host_sets)
+        return {"value": n_total / wall, "unit": "elements/s", "cores": len(used), "kind": "oracle",
+                "seconds": round(wall, 2), "slowest_worker_seconds": round(max(r[1] for r in results), 2),
+                "message_bytes_per_round": sum(r[2] for r in results) / len(host_sets)}
+
+    def run(self, host_sets, sizes, p, scale):
+        one = self._leg(1, host_sets, sizes, p, scale)
+        every = self._leg(len(self.workers), host_sets, sizes, p, scale)
+        sample = ("%d rounds (compress + build message + decode-accumulate, residual carried) of the same "
+                  "%d-tensor update, %d entries per round; one core: %.1f s; %d processes, tensors dealt out "
+                  "by size: %.1f s" % (len(host_sets), len(sizes), sum(sizes), one["seconds"], every["cores"],
+                                       every["seconds"]))
+        out = dict(every)
+        out["sample"] = sample
+        out["usable_cores"] = len(self.cores)
+        out["legs"] = [one, every]
+        return out
+
+    def close(self):
+        for pr, conn in self.workers:
+            try:
+                conn.send(("stop",))
+            except OSError:
+                pass
+        for pr, conn in self.workers:
+            pr.join(timeout=10)
 
 
 def main() -> int:
@@ -66,6 +182,11 @@ def main() -> int:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported "
               "(nothing here shards over several GPUs)" % args.gpus, file=sys.stderr)
         return 2
+
+    # the CPU baseline's processes start before this process touches the GPU
+    cpu_pool = None
+    if not args.no_cpu_baseline and args.workload == "resnet50":
+        cpu_pool = CpuBaseline()
 
     import torch
     from paper_1805_08768_amd import accounting, binding as sbc, synth
@@ -142,7 +263,7 @@ def main() -> int:
     clients = [Client(i) for i in range(C)]
     ctx, R, out, msg, stream = clients[0].ctx, clients[0].R, clients[0].out, clients[0].msg, clients[0].stream
 
-    def run_steps(clients, first, count, profile_every=0, routes=None):
+    def run_steps(clients, first, count, profile_every=0, routes=None, stamps=None):
         """Steps first .. first+count-1; step s is client s mod C's next round: the client call
         (begin ... end: the message size is needed on the host), then the server call on the
         produced message.  Every client has at most one step in flight.  With profile_every, every
@@ -161,6 +282,8 @@ def main() -> int:
         for s in range(first, first + count):
             c = clients[s % C]
             nbytes = sbc.sbc_compress_end(c.ctx)
+            if stamps is not None:
+                stamps.append(time.perf_counter())          # this step's message is complete
             total_bytes += nbytes
             if routes is not None:
                 rt = sbc.sbc_last_route(c.ctx)
@@ -186,9 +309,12 @@ def main() -> int:
         sbc.sbc_profile_enable(c.ctx, 0)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    msg_bytes = run_steps(clients, args.warmup, args.steps, PROFILE_EVERY, routes)
+    stamps = []
+    msg_bytes = run_steps(clients, args.warmup, args.steps, PROFILE_EVERY, routes, stamps)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    # single steps: the time from one step's finished message to the next one's
+    periods_ms = [(b - a) * 1e3 for a, b in zip(stamps, stamps[1:])]
     prof = {}
     for c in clients:
         for kernel, ms, calls in sbc.sbc_profile_read(c.ctx):
@@ -199,22 +325,22 @@ def main() -> int:
     # untimed extra: latency of each call on its own (one client, every call waited for)
     sbc.sbc_set_option(ctx, sbc.SBC_OPT_DEFER_DECODE_STATUS, 0)
     sbc.sbc_profile_level(ctx, 0)
-    t_compress = t_decode = 0.0
+    compress_all, decode_all = [], []
     for i in range(args.steps):
         ta = time.perf_counter()
         nbytes = sbc.sbc_compress(ctx, dW_sets[i % n_sets], R, P, msg, stream)
         tb = time.perf_counter()
         sbc.sbc_decompress_accumulate(ctx, msg, nbytes, P, scale, out, stream)
-        t_decode += time.perf_counter() - tb
-        t_compress += tb - ta
-    compress_ms = t_compress * 1e3 / args.steps
-    decode_ms = t_decode * 1e3 / args.steps
-    k1_ms, k1_calls = prof["k_client_step"]
+        decode_all.append((time.perf_counter() - tb) * 1e3)
+        compress_all.append((tb - ta) * 1e3)
+    compress_ms = sum(compress_all) / args.steps
+    decode_ms = sum(decode_all) / args.steps
+    stream_kernel = sbc.sbc_profile_read(ctx)[1][0]       # the residual-accumulation kernel of this configuration
+    k1_ms, k1_calls = prof[stream_kernel]
     if k1_calls == 0:
         print("bench.py: no timed launch of the streaming kernel", file=sys.stderr)
         return 1
-    k1_avg_ms = k1_ms / k1_calls
-    achieved = BYTES_PER_ENTRY * N / (k1_avg_ms * 1e-3) / 1e9
+    warm_us = k1_ms / k1_calls * 1e3
 
     # untimed extras: per-kernel breakdown, copy yardstick, paper-accounted compression ratio
     sbc.sbc_profile_enable(ctx, 2)
@@ -230,16 +356,33 @@ def main() -> int:
     if args.workload != "flat1p5e9":
         flush = torch.zeros(128 << 20, dtype=torch.int32, device=dev)
         sbc.sbc_profile_enable(ctx, 2)
-        for i in range(10):
+        for i in range(COLD_LAUNCHES):
             flush.sum()
             torch.cuda.synchronize()
             sbc.sbc_compress(ctx, dW_sets[i % n_sets], R, P, msg, stream)
-        cold_us = {kernel: round(ms / max(1, calls) * 1e3, 2) for kernel, ms, calls in sbc.sbc_profile_read(ctx)}
-        cold = {"kernel_us": cold_us,
-                "k_client_step_frac_of_hbm_peak":
-                    BYTES_PER_ENTRY * N / (cold_us["k_client_step"] * 1e-6) / 1e9 / HBM_PEAK_GBS}
+        cold_read = sbc.sbc_profile_read(ctx)
+        cold_us = {kernel: round(ms / max(1, calls) * 1e3, 2) for kernel, ms, calls in cold_read}
         sbc.sbc_profile_enable(ctx, 0)
+        cold_compress = []                                  # the call's latency, no events on its dispatches
+        for i in range(COLD_LAUNCHES):
+            flush.sum()
+            torch.cuda.synchronize()
+            ta = time.perf_counter()
+            sbc.sbc_compress(ctx, dW_sets[i % n_sets], R, P, msg, stream)
+            cold_compress.append((time.perf_counter() - ta) * 1e3)
+        cold = {"kernel_us": cold_us, "launches": cold_read[1][2],
+                "compress_ms_median": statistics.median(cold_compress), "compress_ms_min": min(cold_compress)}
         del flush
+    # the headline kernel figure: caches flushed before the call where the call's footprint could
+    # otherwise partly stay in the last-level cache; beyond it there is nothing to flush
+    if cold is not None:
+        k1_us, k1_launches, k1_how = cold["kernel_us"][stream_kernel], cold["launches"], "caches flushed before every call"
+    else:
+        k1_us, k1_launches, k1_how = warm_us, k1_calls, "launches of the timed steps (footprint far beyond the last-level cache)"
+    achieved = BYTES_PER_ENTRY * N / (k1_us * 1e-6) / 1e9
+    traffic, traffic_kernel, traffic_source = traffic_from_profile()
+    if args.workload != "resnet50" or traffic_kernel is None or not stream_kernel.startswith(traffic_kernel):
+        traffic, traffic_source = None, None
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     src, dst = flat_sets[0], (flat_sets[1] if n_sets > 1 else out.tensors[0])
     for _ in range(3):
@@ -300,22 +443,18 @@ def main() -> int:
         for c in three[1:]:
             sbc.sbc_destroy(c.ctx)
 
-    cpu = None
-    if not args.no_cpu_baseline and args.workload == "resnet50":
-        from oracle import sbc_oracle as oracle
-        dWs = host_sets[0]
-        zeros = [np.zeros_like(d) for d in dWs]
-        tc = time.perf_counter()
-        res = oracle.compress_model(dWs, zeros, P)
-        m = oracle.build_message(res)
-        accs = [np.zeros(n, np.float32) for n in sizes]
-        oracle.decode_accumulate(m, sizes, scale, accs)
-        dt = time.perf_counter() - tc
-        cpu = {"value": N / dt, "unit": "elements/s", "cores": 1, "kind": "oracle",
-               "sample": "one full step (compress + decode-accumulate) of the same 161-tensor update, "
-                         "%d entries, %.1f s" % (N, dt)}
     for c in clients:
         sbc.sbc_destroy(c.ctx)
+    torch.cuda.synchronize()
+
+    # the GPU part is over: the waiting CPU processes get their work
+    cpu = None
+    if cpu_pool is not None:
+        cpu = cpu_pool.run([gen(r) for r in range(CPU_ROUNDS)], sizes, P, scale)
+        cpu_pool.close()
+
+    def frac_of_peak(ms):
+        return BYTES_PER_ENTRY * N / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
 
     line = {
         "metric": "SBC compress+encode throughput (elements/s, HBM GB/s, % of peak) per round",
@@ -325,6 +464,8 @@ def main() -> int:
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": ms_per_step,
+        "ms_per_step_median": statistics.median(periods_ms) if periods_ms else ms_per_step,
+        "ms_per_step_min": min(periods_ms) if periods_ms else ms_per_step,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -337,16 +478,27 @@ def main() -> int:
                    "selection": "subsampled threshold (noisy count)" if args.sampled_threshold else "exact top-k"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES if args.workload == "resnet50" else None,
-                     "kernel": "k_client_step", "kernel_avg_us": k1_avg_ms * 1e3,
-                     "kernel_launches_timed": k1_calls,
-                     "algorithmic_bytes_per_launch": BYTES_PER_ENTRY * N},
+                     "traffic": traffic, "traffic_source": traffic_source,
+                     "kernel": stream_kernel, "kernel_avg_us": k1_us,
+                     "kernel_launches_timed": k1_launches, "kernel_timed": k1_how,
+                     "algorithmic_bytes_per_launch": BYTES_PER_ENTRY * N,
+                     "timed_region": {"kernel_avg_us": warm_us, "kernel_launches_timed": k1_calls,
+                                      "frac": BYTES_PER_ENTRY * N / (warm_us * 1e-6) / 1e9 / HBM_PEAK_GBS},
+                     # the same bytes over the whole compress call (every kernel of it and the wait for its result)
+                     "step_frac": frac_of_peak(compress_ms),
+                     "step_frac_median": frac_of_peak(statistics.median(compress_all)),
+                     "step_frac_best": frac_of_peak(min(compress_all)),
+                     "step_frac_caches_flushed": frac_of_peak(cold["compress_ms_median"]) if cold else None},
         "cpu_baseline": cpu,
         "compress_ms": compress_ms,
+        "compress_ms_median": statistics.median(compress_all),
+        "compress_ms_min": min(compress_all),
         "decode_ms": decode_ms,
+        "decode_ms_median": statistics.median(decode_all),
+        "decode_ms_min": min(decode_all),
         "compress_elements_per_s": N / (compress_ms * 1e-3),
         "compress_algorithmic_GBs": BYTES_PER_ENTRY * N / (compress_ms * 1e-3) / 1e9,
-        "compress_frac_of_hbm_peak": BYTES_PER_ENTRY * N / (compress_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "compress_frac_of_hbm_peak": frac_of_peak(compress_ms),
         "kernel_us": breakdown,
         "cold_cache": cold,
         "pipelined": pipelined,

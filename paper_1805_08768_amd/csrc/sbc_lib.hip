@@ -1114,7 +1114,8 @@ int sbc_profile_level(sbc_ctx* c, int level) {
 
 int sbc_profile_read(sbc_ctx* c, int stage, const char** name, double* total_ms, int64_t* calls) {
     if (!c || stage < 0 || stage >= kNumStages) return SBC_EINVAL;
-    if (name) *name = kStageNames[stage];
+    // (the streaming pass is one of two kernels, by SBC_OPT_FUSED_STEP)
+    if (name) *name = (stage == kStAccumulate && !c->fused_step) ? "k_accumulate_filter" : kStageNames[stage];
     if (total_ms) *total_ms = c->stage_ms[stage];
     if (calls) *calls = c->stage_calls[stage];
     return SBC_OK;
