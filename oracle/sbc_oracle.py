@@ -6,11 +6,11 @@ tests, the smoke check and the benchmark's CPU-baseline leg may import it; the
 product path (the HIP library and its Python binding) never does, and this
 module imports nothing from the product path.
 
-Every function follows one passage of the paper, in the paper's order and
-notation, with NumPy fp32/fp64 element-wise operations, one library sort, and
-plain Python loops for everything that is sequential in the paper (the Golomb
-coder and decoder work one bit at a time).  Nothing here is blocked, fused or
-reordered.
+Every function follows one passage of the paper, with NumPy fp32/fp64
+element-wise operations, one library sort, and plain Python loops for
+everything that is sequential in the paper (the Golomb coder and decoder work
+on a list of single bits through a small bit writer and reader).  Nothing here
+is blocked, fused or reordered.
 
 Readings taken where the paper leaves a choice (each is repeated at the place
 it is used):
@@ -271,44 +271,77 @@ def golomb_gaps(kept: Sequence[int]) -> np.ndarray:
     return np.asarray(gaps, dtype=np.int64)
 
 
+class BitWriter:
+    """A growing list of bits with the two shapes a Golomb code word is made of."""
+
+    def __init__(self) -> None:
+        self.bits: List[int] = []
+
+    def unary(self, count: int) -> None:
+        """`count` ones closed by a zero."""
+        self.bits += [1] * count + [0]
+
+    def field(self, value: int, width: int) -> None:
+        """`value` as a `width`-bit number, most significant bit first."""
+        self.bits += [(value >> (width - 1 - t)) & 1 for t in range(width)]
+
+
+class BitReader:
+    """Reads the same two shapes back from a list of bits whose length is the exact stream length."""
+
+    def __init__(self, bits: Sequence[int]) -> None:
+        self.bits = bits
+        self.at = 0
+
+    def exhausted(self) -> bool:
+        return self.at >= len(self.bits)
+
+    def unary(self) -> int:
+        """Number of ones before the next zero; the zero is consumed.  None if the stream ends
+        before a zero turns up (only ones were left: no further code word)."""
+        run = 0
+        while self.at + run < len(self.bits) and self.bits[self.at + run]:
+            run += 1
+        if self.at + run >= len(self.bits):
+            self.at = len(self.bits)
+            return None
+        self.at += run + 1
+        return run
+
+    def field(self, width: int) -> int:
+        if self.at + width > len(self.bits):
+            raise IndexError("bit stream ends inside a %d-bit field" % width)
+        value = 0
+        for bit in self.bits[self.at:self.at + width]:
+            value = 2 * value + int(bit)
+        self.at += width
+        return value
+
+
 def golomb_encode(kept: Sequence[int], b: int) -> List[int]:
-    """Alg. 3: for each kept position emit q ones, a zero, then r in b bits
-    (most significant first), where q, r = divmod(d - 1, 2^b)."""
-    msg: List[int] = []
-    prev = -1
-    for pos in kept:
-        pos = int(pos)
-        d_minus_1 = pos - prev - 1
-        q = d_minus_1 // (1 << b)
-        r = d_minus_1 % (1 << b)
-        msg.extend([1] * q)
-        msg.append(0)
-        for t in range(b - 1, -1, -1):
-            msg.append((r >> t) & 1)
-        prev = pos
-    return msg
+    """Alg. 3: every kept position is sent as the number of skipped entries since the previous
+    kept one (d - 1), split by 2^b into a quotient in unary and a remainder in b bits."""
+    out = BitWriter()
+    for skipped in golomb_gaps(kept):
+        quotient, remainder = divmod(int(skipped), 1 << b)
+        out.unary(quotient)
+        out.field(remainder, b)
+    return out.bits
 
 
 def golomb_decode(msg: Sequence[int], b: int) -> List[int]:
-    """Alg. 4 with its state (i, q, j); size(msg) is the exact bit length.
-    Returns the 0-based positions (the algorithm's j is 1-based)."""
+    """Alg. 4: code words are read until the stream (whose exact bit length is len(msg)) is used
+    up; each gives the distance to the next kept position.  Returns 0-based positions."""
+    src = BitReader(msg)
     positions: List[int] = []
-    i = 0
-    q = 0
-    j = 0
-    size = len(msg)
-    while i < size:
-        if msg[i] == 0:
-            r = 0
-            for t in range(1, b + 1):
-                r = (r << 1) | msg[i + t]
-            j = j + q * (1 << b) + r + 1
-            positions.append(j - 1)
-            q = 0
-            i = i + b + 1
-        else:
-            q = q + 1
-            i = i + 1
+    nxt = 0                                   # first position a code word with no skipped entries would name
+    while not src.exhausted():
+        quotient = src.unary()
+        if quotient is None:
+            break
+        nxt += (quotient << b) + src.field(b)
+        positions.append(nxt)
+        nxt += 1
     return positions
 
 
