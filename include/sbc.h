@@ -160,7 +160,7 @@ int sbc_decompress_accumulate(sbc_ctx* ctx, void* hip_stream,
  * live in a device array that is part of the loaded library (about 9 KiB on every GPU the library
  * runs on, held until the process ends), and the call neither allocates, frees, copies to or from
  * the host nor waits: it enqueues three kernels on hip_stream and returns.
- *   device       HIP device the stream and all buffers belong to
+ *   device       HIP device the stream and all buffers belong to (SBC_EINVAL if there is no such device)
  *   msg, out, numel, n_tensors, p, scale   as for sbc_decompress_accumulate
  *   status       device, 4-byte aligned: receives SBC_OK, SBC_ECORRUPT or SBC_EINTERNAL once the
  *                stream has passed the call (validation is done on the device)

@@ -1189,6 +1189,9 @@ int sbc_decompress_accumulate_noalloc(int device, void* hip_stream, const void* 
     if (!msg || !numel || !out || !status || n_tensors <= 0 || !valid_p(p) || device < 0) return SBC_EINVAL;
     if ((((uintptr_t)msg) & 7u) != 0 || (((uintptr_t)status) & 3u) != 0) return SBC_EINVAL;
     if (n_tensors > SBC_NOALLOC_MAX_TENSORS || device >= kNoAllocMaxDevices) return SBC_ECAPACITY;
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) != hipSuccess) { (void)hipGetLastError(); return SBC_EHIP; }
+    if (device >= n_dev) return SBC_EINVAL;
     const int T = n_tensors;
     const int b = bstar_of(p);
     if (b > kMaxB) return SBC_EINVAL;
