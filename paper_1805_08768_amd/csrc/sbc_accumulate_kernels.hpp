@@ -378,78 +378,83 @@ __device__ __forceinline__ void filter_entry(float a, uint32_t idx, uint32_t lo_
 // of it to the residual, which is read and written.
 template <bool STREAM>
 __global__ __launch_bounds__(kStreamThreads) void k_accumulate_filter(
-        const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ chunk_tensor,
+        const TensorDesc* __restrict__ desc, const uint2* __restrict__ sched,
         TensorState* __restrict__ st, uint2* __restrict__ cand, uint32_t* __restrict__ bitmap,
         uint32_t* __restrict__ stage, ResultBlock* __restrict__ result) {
     __shared__ FilterShared sh;
     const int tid = threadIdx.x;
-    const uint32_t c = blockIdx.x;
-    const int t = (int)chunk_tensor[c];
+    // sched[workgroup] = (first chunk in the call-wide numbering, tensor | consecutive chunks of it << 24)
+    const uint2 sc = sched[blockIdx.x];
+    const int t = (int)(sc.y & 0xFFFFFFu);
+    const uint32_t n_sub = sc.y >> 24;
     const TensorDesc d = desc[t];
     const uint32_t lo_p = st[t].lo_key[0], lo_n = st[t].lo_key[1];
-    const uint32_t cc = c - d.chunk0;
-    const uint32_t e0 = cc * (uint32_t)kChunk;
-    const uint32_t cnt = min((uint32_t)kChunk, d.n - e0);
     if (tid < 2) sh.qcnt[tid] = 0u;
-
-    if (!(d.flags & kDescFused)) {
-        bitmap[(uint64_t)c * kChunkWords + tid] = 0u;
-        const uint32_t per = (d.bound_words + d.nchunks - 1u) / d.nchunks;
-        const uint32_t lo = per * cc;
-        const uint32_t hi = (lo + per < d.bound_words) ? lo + per : d.bound_words;
-        for (uint32_t w = lo + tid; w < hi; w += kStreamThreads) stage[d.stage_off + w] = 0u;
-    }
     __syncthreads();
-
-    const gcfloat_ptr dw = as_global(d.dW + e0);
-    const gfloat_ptr r = as_global(d.R + e0);
     uint32_t bad = 0u;
-    const bool vec = (cnt == (uint32_t)kChunk) && ((((uintptr_t)(d.dW + e0) | (uintptr_t)(d.R + e0)) & 15u) == 0u);
-    if (vec) {
-        const gcf32x4_ptr dw4 = (gcf32x4_ptr)dw;
-        const gf32x4_ptr r4 = (gf32x4_ptr)r;
-        constexpr int IT = kChunk / 4 / kStreamThreads;   // 8
-        f32x4 dv[IT], rv[IT];
-#pragma unroll
-        for (int i = 0; i < IT; ++i) {
-            dv[i] = STREAM ? __builtin_nontemporal_load(&dw4[i * kStreamThreads + tid]) : dw4[i * kStreamThreads + tid];
-            rv[i] = r4[i * kStreamThreads + tid];
+
+#pragma unroll 1
+    for (uint32_t sub = 0; sub < n_sub; ++sub) {
+        const uint32_t c = sc.x + sub;
+        const uint32_t cc = c - d.chunk0;
+        const uint32_t e0 = cc * (uint32_t)kChunk;
+        const uint32_t cnt = min((uint32_t)kChunk, d.n - e0);
+        if (!(d.flags & kDescFused)) {
+            bitmap[(uint64_t)c * kChunkWords + tid] = 0u;
+            const uint32_t per = (d.bound_words + d.nchunks - 1u) / d.nchunks;
+            const uint32_t lo = per * cc;
+            const uint32_t hi = (lo + per < d.bound_words) ? lo + per : d.bound_words;
+            for (uint32_t w = lo + tid; w < hi; w += kStreamThreads) stage[d.stage_off + w] = 0u;
         }
+        const gcfloat_ptr dw = as_global(d.dW + e0);
+        const gfloat_ptr r = as_global(d.R + e0);
+        const bool vec = (cnt == (uint32_t)kChunk) && ((((uintptr_t)(d.dW + e0) | (uintptr_t)(d.R + e0)) & 15u) == 0u);
+        if (vec) {
+            const gcf32x4_ptr dw4 = (gcf32x4_ptr)dw;
+            const gf32x4_ptr r4 = (gf32x4_ptr)r;
+            constexpr int IT = kChunk / 4 / kStreamThreads;   // 8
+            f32x4 dv[IT], rv[IT];
 #pragma unroll
-        for (int i = 0; i < IT; ++i) {
-            f32x4 a;
-            a.x = rv[i].x + dv[i].x;
-            a.y = rv[i].y + dv[i].y;
-            a.z = rv[i].z + dv[i].z;
-            a.w = rv[i].w + dv[i].w;
-            r4[i * kStreamThreads + tid] = a;
-            const uint32_t idx = e0 + (i * kStreamThreads + tid) * 4;
-            filter_entry(a.x, idx + 0, lo_p, lo_n, sh, bad);
-            filter_entry(a.y, idx + 1, lo_p, lo_n, sh, bad);
-            filter_entry(a.z, idx + 2, lo_p, lo_n, sh, bad);
-            filter_entry(a.w, idx + 3, lo_p, lo_n, sh, bad);
-        }
-    } else {
-        // a tensor's last, partial chunk, or operands that are only 4-byte aligned: eight entries per
-        // thread in flight at a time (later loads may not pass earlier stores to the same array,
-        // so a plain loop would pay the memory latency once per entry)
-        constexpr int IT = 8;
-        for (uint32_t base = 0; base < cnt; base += IT * kStreamThreads) {
-            float dv[IT], rv[IT];
-#pragma unroll
-            for (int j = 0; j < IT; ++j) {
-                const uint32_t i = base + j * kStreamThreads + tid;
-                const uint32_t ii = i < cnt ? i : 0u;
-                dv[j] = dw[ii];
-                rv[j] = r[ii];
+            for (int i = 0; i < IT; ++i) {
+                dv[i] = STREAM ? __builtin_nontemporal_load(&dw4[i * kStreamThreads + tid]) : dw4[i * kStreamThreads + tid];
+                rv[i] = r4[i * kStreamThreads + tid];
             }
 #pragma unroll
-            for (int j = 0; j < IT; ++j) {
-                const uint32_t i = base + j * kStreamThreads + tid;
-                if (i < cnt) {
-                    const float a = rv[j] + dv[j];
-                    r[i] = a;
-                    filter_entry(a, e0 + i, lo_p, lo_n, sh, bad);
+            for (int i = 0; i < IT; ++i) {
+                f32x4 a;
+                a.x = rv[i].x + dv[i].x;
+                a.y = rv[i].y + dv[i].y;
+                a.z = rv[i].z + dv[i].z;
+                a.w = rv[i].w + dv[i].w;
+                r4[i * kStreamThreads + tid] = a;
+                const uint32_t idx = e0 + (i * kStreamThreads + tid) * 4;
+                filter_entry(a.x, idx + 0, lo_p, lo_n, sh, bad);
+                filter_entry(a.y, idx + 1, lo_p, lo_n, sh, bad);
+                filter_entry(a.z, idx + 2, lo_p, lo_n, sh, bad);
+                filter_entry(a.w, idx + 3, lo_p, lo_n, sh, bad);
+            }
+        } else {
+            // a tensor's last, partial chunk, or operands that are only 4-byte aligned: eight entries per
+            // thread in flight at a time (later loads may not pass earlier stores to the same array,
+            // so a plain loop would pay the memory latency once per entry)
+            constexpr int IT = 8;
+            for (uint32_t base = 0; base < cnt; base += IT * kStreamThreads) {
+                float dv[IT], rv[IT];
+#pragma unroll
+                for (int j = 0; j < IT; ++j) {
+                    const uint32_t i = base + j * kStreamThreads + tid;
+                    const uint32_t ii = i < cnt ? i : 0u;
+                    dv[j] = dw[ii];
+                    rv[j] = r[ii];
+                }
+#pragma unroll
+                for (int j = 0; j < IT; ++j) {
+                    const uint32_t i = base + j * kStreamThreads + tid;
+                    if (i < cnt) {
+                        const float a = rv[j] + dv[j];
+                        r[i] = a;
+                        filter_entry(a, e0 + i, lo_p, lo_n, sh, bad);
+                    }
                 }
             }
         }
@@ -478,19 +483,25 @@ __global__ __launch_bounds__(kStreamThreads) void k_accumulate_filter(
         for (uint32_t i = tid; i < qn; i += kStreamThreads) cn[i] = sh.queue[1][i];
         return;
     }
-    // queue overflow: append this chunk's candidates from a second read of A, 1024 entries at a time
-    for (uint32_t off = 0; off < cnt; off += 4 * kStreamThreads) {
-        uint32_t key[4];
-        uint32_t mp = 0u, mn = 0u;
+    // queue overflow: append the candidates of this workgroup's chunks from a second read of A,
+    // 1024 entries at a time (the barrier above ordered the workgroup's stores of A before these loads)
+    for (uint32_t sub = 0; sub < n_sub; ++sub) {
+        const uint32_t e0 = (sc.x + sub - d.chunk0) * (uint32_t)kChunk;
+        const uint32_t cnt = min((uint32_t)kChunk, d.n - e0);
+        const gcfloat_ptr r = as_global(d.R + e0);
+        for (uint32_t off = 0; off < cnt; off += 4 * kStreamThreads) {
+            uint32_t key[4];
+            uint32_t mp = 0u, mn = 0u;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const uint32_t i = off + s * kStreamThreads + tid;
-            const bool in = i < cnt;
-            key[s] = key_of_bits(__float_as_uint(r[in ? i : 0u]));
-            if (in && key[s] >= lo_p) mp |= 1u << s;
-            if (in && ~key[s] >= lo_n) mn |= 1u << s;
+            for (int s = 0; s < 4; ++s) {
+                const uint32_t i = off + s * kStreamThreads + tid;
+                const bool in = i < cnt;
+                key[s] = key_of_bits(__float_as_uint(r[in ? i : 0u]));
+                if (in && key[s] >= lo_p) mp |= 1u << s;
+                if (in && ~key[s] >= lo_n) mn |= 1u << s;
+            }
+            append_candidates<4>(key, mp, mn, e0 + off, d, &st[t], cand, result, sh.scratch, sh.base);
         }
-        append_candidates<4>(key, mp, mn, e0 + off, d, &st[t], cand, result, sh.scratch, sh.base);
     }
 }
 

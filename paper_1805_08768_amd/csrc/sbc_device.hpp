@@ -59,7 +59,8 @@ constexpr int kBucketBits = 11;          // index sort of the fused encoder: buc
 constexpr int kBuckets = 1 << kBucketBits;
 constexpr uint32_t kFusedMaxK = 6144;    // a tensor with k up to this, and a stream bound of up to
 constexpr uint32_t kFusedMaxWords = 4096; // this many words, is sorted and encoded inside the select kernel
-constexpr int kFilterQueue = 1024;       // candidates per side a chunk can queue in LDS
+constexpr int kFilterQueue = 1024;       // candidates per side a workgroup of the streaming kernel can queue in LDS
+constexpr uint32_t kMaxChunksPerWorkgroup = 8;   // consecutive chunks of one very long tensor per such workgroup
 
 // error bits raised by kernels (word 0 of the result block)
 constexpr uint32_t kErrNonFinite = 1u;

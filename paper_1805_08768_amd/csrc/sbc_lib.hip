@@ -62,6 +62,7 @@ struct sbc_ctx {
     uint2* d_sched = nullptr;             // workgroup of the streaming kernel -> (chunk, tensor)
     GroupState* d_group = nullptr;        // per group of chunks: candidate and completion counters
     uint64_t max_groups = 0;
+    uint32_t n_sched = 0;                 // workgroups of the streaming kernel
     uint32_t* d_order = nullptr;
     uint32_t* d_hist = nullptr;
     TensorState* d_state = nullptr;
@@ -72,6 +73,7 @@ struct sbc_ctx {
     ChunkSummary* d_sum = nullptr;
     uint32_t* d_prev_end = nullptr;
     uint64_t* d_bitoff = nullptr;
+    TileSummary* d_tile = nullptr;        // per tile of kScanTile chunks of a tensor encoded from the bitmap
     ResultBlock* d_result = nullptr;      // two for compress, two for decode, used in turn; [4] collects the
                                           // errors of decode calls whose status is deferred, [5] is a spare
     // grid-wide selection
@@ -111,6 +113,7 @@ struct sbc_ctx {
     bool cache_valid = false; int cache_T = 0; double cache_p = 0.0;
     std::vector<int64_t> cache_numel;
     uint64_t cache_total = 0, cache_chunks = 0, cache_stage_words = 0, cache_kept_total = 0, cache_max_bound = 0;
+    uint32_t cache_scan_tiles = 1;        // most tiles of the chunk scan among the tensors encoded from the bitmap
     bool cache_any_bitmap = false;
     bool cache_all_inline = false;        // every tensor is finished inside the streaming kernel
     int cache_force_exact = 0;
@@ -172,7 +175,7 @@ struct sbc_ctx {
         uint8_t* msg8 = nullptr;
         size_t msg_capacity = 0, need = 0;
         uint32_t n_chunks = 0;
-        unsigned gather_y = 1;
+        unsigned gather_y = 1, scan_tiles = 1;
     } pend;
 
     // last compress call, for the inspection entry points
@@ -231,7 +234,7 @@ hipError_t host_alloc(T** p, size_t count) { return hipHostMalloc(reinterpret_ca
 void free_all(sbc_ctx* c) {
     (void)hipFree(c->d_desc); (void)hipFree(c->d_chunk_tensor); (void)hipFree(c->d_sched); (void)hipFree(c->d_group); (void)hipFree(c->d_order); (void)hipFree(c->d_hist);
     (void)hipFree(c->d_state); (void)hipFree(c->d_cand); (void)hipFree(c->d_bitmap); (void)hipFree(c->d_stage);
-    (void)hipFree(c->d_kept); (void)hipFree(c->d_sum); (void)hipFree(c->d_prev_end); (void)hipFree(c->d_bitoff);
+    (void)hipFree(c->d_kept); (void)hipFree(c->d_sum); (void)hipFree(c->d_prev_end); (void)hipFree(c->d_bitoff); (void)hipFree(c->d_tile);
     (void)hipFree(c->d_result); (void)hipFree(c->d_dec); (void)hipFree(c->d_dec_blocks);
     if (c->h_dec_blocks) (void)hipHostFree(c->h_dec_blocks);
     (void)hipFree(c->d_dec_wide); (void)hipFree(c->d_seg_fn); (void)hipFree(c->d_seg_pack); (void)hipFree(c->d_tile_fn);
@@ -285,12 +288,28 @@ void launch_encode_and_gather(sbc_ctx* c, bool profile) {
     bool* timed = P.timed;
     const int T = P.T, b = P.b;
     if (P.any_bitmap) {
-        SBC_LAUNCH(kStChunkSummary, profile, k_chunk_summary, dim3(P.n_chunks), dim3(kChunkWords), P.d_desc,
-                   c->d_chunk_tensor, c->d_bitmap, c->d_sum, b);
-        SBC_LAUNCH(kStTensorScan, profile, k_tensor_scan, dim3(T), dim3(kScanThreads), P.d_desc, c->d_sum, c->d_prev_end,
-                   c->d_bitoff, c->d_state, b);
-        SBC_LAUNCH(kStPack, profile, k_pack, dim3(P.n_chunks), dim3(kChunkWords), P.d_desc, c->d_chunk_tensor,
-                   c->d_bitmap, c->d_sum, c->d_prev_end, c->d_bitoff, b, c->d_stage, P.res_now);
+        // (with very many chunks a workgroup takes four of them: see the kernels)
+        const bool batch = P.n_chunks > 8192u;
+        const dim3 per_chunk(batch ? (P.n_chunks + 3u) / 4u : P.n_chunks);
+        if (batch) {
+            SBC_LAUNCH(kStChunkSummary, profile, k_chunk_summary<4>, per_chunk, dim3(kChunkWords), P.d_desc,
+                       c->d_chunk_tensor, c->d_bitmap, c->d_sum, b, P.n_chunks);
+        } else {
+            SBC_LAUNCH(kStChunkSummary, profile, k_chunk_summary<1>, per_chunk, dim3(kChunkWords), P.d_desc,
+                       c->d_chunk_tensor, c->d_bitmap, c->d_sum, b, P.n_chunks);
+        }
+        if (P.scan_tiles > 1)
+            hipLaunchKernelGGL(k_tile_summary, dim3(T, P.scan_tiles), dim3(kScanThreads), 0, stream, P.d_desc, c->d_sum,
+                               c->d_tile, b);
+        SBC_LAUNCH(kStTensorScan, profile, k_tensor_scan, dim3(T, P.scan_tiles), dim3(kScanThreads), P.d_desc, c->d_sum,
+                   c->d_tile, c->d_prev_end, c->d_bitoff, c->d_state, b);
+        if (batch) {
+            SBC_LAUNCH(kStPack, profile, k_pack<4>, per_chunk, dim3(kChunkWords), P.d_desc, c->d_chunk_tensor,
+                       c->d_bitmap, c->d_sum, c->d_prev_end, c->d_bitoff, b, c->d_stage, P.res_now, P.n_chunks);
+        } else {
+            SBC_LAUNCH(kStPack, profile, k_pack<1>, per_chunk, dim3(kChunkWords), P.d_desc, c->d_chunk_tensor,
+                       c->d_bitmap, c->d_sum, c->d_prev_end, c->d_bitoff, b, c->d_stage, P.res_now, P.n_chunks);
+        }
     }
     SBC_LAUNCH(kStGather, profile, k_finish_message, dim3(T, P.gather_y), dim3(256), P.d_desc, c->d_state, T, b,
                c->d_stage, c->d_kept, c->d_group, P.msg8, (uint64_t)P.msg_capacity, P.res_now, P.res_next,
@@ -485,7 +504,7 @@ size_t sbc_msg_bound(const int64_t* numel, int n_tensors, double p) { return msg
 size_t sbc_msg_bound_sampled(const int64_t* numel, int n_tensors, double p) { return msg_bound(numel, n_tensors, p, true); }
 
 int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tensors) {
-    if (!out || max_total_elems < 1 || max_tensors < 1) return SBC_EINVAL;
+    if (!out || max_total_elems < 1 || max_tensors < 1 || max_tensors >= (1 << 24)) return SBC_EINVAL;
     *out = nullptr;
     int n_dev = 0;
     if (hipGetDeviceCount(&n_dev) != hipSuccess) return SBC_EHIP;
@@ -521,6 +540,7 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     ok = ok && dev_alloc(&c->d_sum, (size_t)c->max_chunks) == hipSuccess;
     ok = ok && dev_alloc(&c->d_prev_end, (size_t)c->max_chunks) == hipSuccess;
     ok = ok && dev_alloc(&c->d_bitoff, (size_t)c->max_chunks) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_tile, (size_t)(c->max_chunks / kScanTile) + T + 1) == hipSuccess;
     ok = ok && dev_alloc(&c->d_result, 6) == hipSuccess;
     ok = ok && dev_alloc(&c->d_dec, T) == hipSuccess;
     ok = ok && dev_alloc(&c->d_dec_blocks, T + kMaxDecExtra) == hipSuccess;
@@ -639,6 +659,7 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
     // that alternates between a few sets of buffers uploads nothing in the steady state.
     uint64_t total = 0, chunks = 0, stage_words = 0, kept_total = 0, max_bound = 0, groups = 0;
     bool any_bitmap = false, all_inline = true;
+    uint32_t scan_tiles = 1;
     // in the subsampled variant the keys must come from this call's sample
     const bool sampled = c->sampled != 0;
     const int force_exact = sampled ? 0 : c->force_exact;
@@ -656,6 +677,7 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
     if (sizes_same) {
         total = c->cache_total; chunks = c->cache_chunks; stage_words = c->cache_stage_words;
         kept_total = c->cache_kept_total; max_bound = c->cache_max_bound; any_bitmap = c->cache_any_bitmap;
+        scan_tiles = c->cache_scan_tiles;
         all_inline = c->cache_all_inline;
         if (use_history)
             for (int t = 0; t < T; ++t) if (c->hist_n[t] != c->plan[t].n) { use_history = false; break; }
@@ -711,6 +733,7 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
             chunks += d.nchunks;
             stage_words += bw;
             max_bound = std::max<uint64_t>(max_bound, bw);
+            if (!fused) scan_tiles = std::max<uint32_t>(scan_tiles, (d.nchunks + kScanTile - 1u) / kScanTile);
             if (total > (uint64_t)c->max_elems || chunks > c->max_chunks || kept_total > c->kept_cap ||
                 stage_words > c->stage_cap || groups > c->max_groups)
                 return SBC_ECAPACITY;
@@ -741,7 +764,7 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
         // go first (their selection then runs beside the streaming of everything else), the others
         // follow by decreasing size, so that the tensors whose completion costs most complete early
         // and the last workgroups to finish belong to tensors with little left to do.
-        {
+        if (c->fused_step) {
             uint64_t w = 0;
             for (int pass = 0; pass < 2; ++pass)
                 for (int i = 0; i < T; ++i) {
@@ -750,10 +773,24 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
                     if (first != (pass == 0)) continue;
                     for (uint32_t j = 0; j < d.nchunks; ++j) c->h_sched[w++] = make_uint2(d.chunk0 + j, c->plan_order[i]);
                 }
+            c->n_sched = (uint32_t)w;
+        } else {
+            // k_accumulate_filter: chunks in memory order.  Every workgroup reserves room in its
+            // tensor's candidate lists with one atomic on one address, and those of one tensor queue
+            // up there (about 20 ns each): a tensor of very many chunks gives each workgroup several
+            // consecutive chunks, so that the queue is no longer what bounds the pass.
+            uint64_t w = 0;
+            for (int t = 0; t < T; ++t) {
+                const TensorDesc& d = c->plan[t];
+                const uint32_t m = std::min<uint32_t>(kMaxChunksPerWorkgroup, std::max<uint32_t>(1u, d.nchunks / 4096u));
+                for (uint32_t j = 0; j < d.nchunks; j += m)
+                    c->h_sched[w++] = make_uint2(d.chunk0 + j, (uint32_t)t | (std::min(m, d.nchunks - j) << 24));
+            }
+            c->n_sched = (uint32_t)w;
         }
         if ((c->n_wide > 0 && hipMemcpyAsync(c->d_wide_ids, c->h_wide_ids, sizeof(uint32_t) * c->n_wide, hipMemcpyHostToDevice, stream) != hipSuccess) ||
             hipMemcpyAsync(c->d_order, c->h_order, sizeof(uint32_t) * T, hipMemcpyHostToDevice, stream) != hipSuccess ||
-            hipMemcpyAsync(c->d_sched, c->h_sched, sizeof(uint2) * chunks, hipMemcpyHostToDevice, stream) != hipSuccess ||
+            hipMemcpyAsync(c->d_sched, c->h_sched, sizeof(uint2) * c->n_sched, hipMemcpyHostToDevice, stream) != hipSuccess ||
             hipMemcpyAsync(c->d_chunk_tensor, c->h_chunk_tensor, sizeof(uint32_t) * chunks, hipMemcpyHostToDevice, stream) != hipSuccess) {
             (void)hipGetLastError();
             return SBC_EHIP;
@@ -762,6 +799,7 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
         c->cache_T = T; c->cache_p = p;
         c->cache_total = total; c->cache_chunks = chunks; c->cache_stage_words = stage_words;
         c->cache_kept_total = kept_total; c->cache_max_bound = max_bound; c->cache_any_bitmap = any_bitmap;
+        c->cache_scan_tiles = scan_tiles;
         c->cache_all_inline = all_inline; c->cache_force_exact = force_exact;
         // (cache_valid is set once this call has completed: the uploads above must have happened)
     }
@@ -815,7 +853,7 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
     P.all_inline = all_inline;
     for (int st = 0; st < kNumStages; ++st) P.timed[st] = false;
     P.res_now = res_now; P.res_next = res_next; P.d_desc = d_desc; P.msg8 = msg8;
-    P.msg_capacity = msg_capacity; P.need = need; P.n_chunks = n_chunks; P.gather_y = gather_y;
+    P.msg_capacity = msg_capacity; P.need = need; P.n_chunks = n_chunks; P.gather_y = gather_y; P.scan_tiles = scan_tiles;
     P.wait_on_event = wait_on_event;
     const int lvl = c->profile_level;
     bool* timed = P.timed;
@@ -834,11 +872,11 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
     P.carry = carry;
     if (!c->fused_step) {
         if (total * 12ull > (512ull << 20)) {
-            SBC_LAUNCH(kStAccumulate, true, k_accumulate_filter<true>, dim3(n_chunks), dim3(kStreamThreads), d_desc,
-                       c->d_chunk_tensor, c->d_state, c->d_cand, c->d_bitmap, c->d_stage, res_now);
+            SBC_LAUNCH(kStAccumulate, true, k_accumulate_filter<true>, dim3(c->n_sched), dim3(kStreamThreads), d_desc,
+                       c->d_sched, c->d_state, c->d_cand, c->d_bitmap, c->d_stage, res_now);
         } else {
-            SBC_LAUNCH(kStAccumulate, true, k_accumulate_filter<false>, dim3(n_chunks), dim3(kStreamThreads), d_desc,
-                       c->d_chunk_tensor, c->d_state, c->d_cand, c->d_bitmap, c->d_stage, res_now);
+            SBC_LAUNCH(kStAccumulate, true, k_accumulate_filter<false>, dim3(c->n_sched), dim3(kStreamThreads), d_desc,
+                       c->d_sched, c->d_state, c->d_cand, c->d_bitmap, c->d_stage, res_now);
         }
     } else if (total * 12ull > (512ull << 20)) {
         SBC_LAUNCH(kStAccumulate, true, k_client_step<true>, dim3(n_chunks), dim3(kStepThreads), d_desc, c->d_sched,

@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 
 # tests that only run with the default setting of SBC_OPT_FUSED_STEP (the largest inputs, and calls
 # that create their contexts themselves)
-DEFAULT_ONLY = ("test_config5b", "test_config5a", "test_more_wide_tensors", "test_config2_companion", "test_tensor_of_many_chunks", "test_unaligned_views",
+DEFAULT_ONLY = ("test_config5b", "test_config5a", "test_more_wide_tensors", "test_tensor_of_several_scan_tiles", "test_config2_companion", "test_tensor_of_many_chunks", "test_unaligned_views",
                 "test_inspection_requires", "test_same_input_twice")
 
 
@@ -576,6 +576,18 @@ def test_tensor_of_many_chunks():
             R = [x.R_new for x in res]
         dWs = [synth.palette_update(n), synth.palette_update(70000, tensor=1)]
         check_round(run, dWs, R, 0.001, check_decode=False)
+
+
+def test_tensor_of_several_scan_tiles():
+    """A tensor encoded from the bitmap whose chunks span several tiles of the per-tensor scan
+    (4096 chunks each), next to one of a single tile: bit offsets carry across tiles."""
+    sizes = [8192 * 8200 + 77, 8192 * 900 + 1]
+    with DeviceRun(sizes) as run:
+        dWs = [synth.gaussian_update(n, tensor=i) for i, n in enumerate(sizes)]
+        # a stretch of several tiles without any kept entry, and a tile whose first chunks are empty
+        dWs[0][8192 * 1000: 8192 * 5200] = 0.0
+        res = check_round(run, dWs, [np.zeros(n, np.float32) for n in sizes], 0.001)
+        assert res[0].k > 6144 and res[1].k > 6144
 
 
 def test_deferred_decode_status():
