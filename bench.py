@@ -163,8 +163,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--breakdown", action="store_true", help="also print per-kernel times to stderr")
-    ap.add_argument("--carry-keys", action="store_true",
-                    help="set SBC_OPT_CARRY_FILTER_KEYS (filter keys from the previous round instead of sampling)")
+    ap.add_argument("--no-carry-keys", action="store_true",
+                    help="clear SBC_OPT_CARRY_FILTER_KEYS (every round estimates its filter keys from a sample "
+                         "instead of starting from the previous round's)")
     ap.add_argument("--fused-step", action="store_true", help="set SBC_OPT_FUSED_STEP")
     ap.add_argument("--sampled-threshold", action="store_true",
                     help="set SBC_OPT_SAMPLED_THRESHOLD (the subsampled variant with a noisy amount of sparsity; "
@@ -251,8 +252,8 @@ def main() -> int:
             self.stream_obj = torch.cuda.current_stream() if index == 0 else torch.cuda.Stream()
             self.stream = self.stream_obj.cuda_stream     # raw handle, looked up once
             self.ctx = sbc.sbc_create(0, N, T)
-            if args.carry_keys:
-                sbc.sbc_set_option(self.ctx, sbc.SBC_OPT_CARRY_FILTER_KEYS, 1)
+            if args.no_carry_keys:
+                sbc.sbc_set_option(self.ctx, sbc.SBC_OPT_CARRY_FILTER_KEYS, 0)
             if args.fused_step:
                 sbc.sbc_set_option(self.ctx, sbc.SBC_OPT_FUSED_STEP, 1)
             if args.sampled_threshold:

@@ -180,12 +180,14 @@ int sbc_decompress_accumulate_noalloc(int device, void* hip_stream,
  * of a second read of that tensor.
  *   SBC_OPT_FORCE_EXACT_PATH   (0/1, default 0)  1 makes every tensor take the histogram route
  *       (to exercise and to time it).
- *   SBC_OPT_CARRY_FILTER_KEYS  (0/1, default 0)  0 estimates the filter keys from a sample of
- *       the new data in every call.  1 lets a call start from keys derived from the exact
- *       thresholds of the previous successful call on this context when tensor sizes and p
- *       are unchanged (successive rounds of one training run) and skips the sampling kernel;
- *       it pays off when the thresholds move by less than a few percent from round to round,
- *       and costs time when they move more (a flood of candidates, then a sampled round).
+ *   SBC_OPT_CARRY_FILTER_KEYS  (0/1, default 1)  1 lets a call start from filter keys that the
+ *       previous successful call on this context left behind, when tensor sizes and p are
+ *       unchanged (successive rounds of one training run), and skips the sampling kernel: per
+ *       tensor and side the key of that call's entry of rank about 9/8 k.  Only a filter: a
+ *       tensor for which it keeps fewer than k entries (the data shrank, the residual was
+ *       cleared) is redone exactly through the histogram route, and the next call samples; so
+ *       does the call after one that saw many times k candidates (the data grew).  0 estimates
+ *       the keys from a sample of the new data in every call.
  *   SBC_OPT_WIDE_MIN_KEPT      (default 0 = 8192)  a tensor that keeps at least this many entries
  *       per side is selected by grid-wide kernels instead of one workgroup (a 1.5e9-entry tensor
  *       at p = 0.001 keeps 1.5e6); tests lower it to send small tensors that way.

@@ -169,6 +169,11 @@ __device__ __forceinline__ uint32_t carried_key(uint32_t tau_side_key, uint32_t 
     return lo > tau_side_key ? tau_side_key : lo;
 }
 
+// Rank of the entry whose key a following call starts from (see k_select).
+__device__ __forceinline__ uint32_t carried_rank(uint32_t k) {
+    return k + k / 8u + 4u * (uint32_t)sqrtf((float)k) + 16u;
+}
+
 // A side key moved towards less extreme values by the fraction `margin` of its value.
 __device__ __forceinline__ uint32_t lowered_key(uint32_t side_key, float margin) {
     const float x = __uint_as_float(bits_of_key(side_key));

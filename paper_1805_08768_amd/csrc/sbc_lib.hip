@@ -133,7 +133,7 @@ struct sbc_ctx {
 
     // ---- options ----
     int force_exact = 0;
-    int carry_keys = 0;
+    int carry_keys = 1;
     int fused_step = 0;                   // the streaming kernel finishes the tensors it can by itself
     int sampled = 0;                      // subsampled variant: the sampled threshold decides what is kept
     int defer_decode = 0;                 // decode calls return once enqueued; sbc_decode_status reports

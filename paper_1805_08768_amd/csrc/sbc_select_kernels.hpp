@@ -296,7 +296,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     // entry, r = 2 k + 4 sqrt(k) + 16 (if the next update is small beside the residual, the k
     // entries kept now are gone from above that key, and k more must remain).  A list shorter
     // than r says nothing about that entry: its place is extrapolated from the k-th.
-    const uint32_t r_next = 2u * k + 4u * (uint32_t)sqrtf((float)k) + 16u;
+    const uint32_t r_next = carried_rank(k);
     uint32_t digit2[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};
     if (pick) {
         const uint32_t rank2[2] = {r_next, r_next};
@@ -506,9 +506,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
                 st[t].lo_key[s] = digit2[s] != 0xFFFFFFFFu ? (wbase[s] + digit2[s]) << kWinShift
                                                            : extrapolated_key(tau[s], s ? lo_key_n : lo_key_p, k, r_next, n, s ? cnt_n : cnt_p);
         }
-        // far more candidates than needed (the lists no longer fit in LDS, or many times k):
-        // the next call should estimate its keys afresh
-        const uint32_t many = min(kSelLds, 8u * k + 4096u);
+        // many times more candidates than needed: the next call should estimate its keys afresh
+        // (lists somewhat too long for LDS only cost one more sweep here)
+        const uint32_t many = 8u * k + 4096u;
         if (cnt_p > many || cnt_n > many) atomicOr(&result->err, kErrLoose);
     }
     if (!ok) return;

@@ -280,7 +280,7 @@ __device__ __forceinline__ Decision select_tensor(StepShared& sh, int& parity, c
     pick_wide_both<kStepWindow, kStepThreads>(sh.whist(), need, both, sh.res[0], sh.scratch64, digit, found);
     uint32_t next_key[2] = {lo_cur[0], lo_cur[1]};
     bool short_list[2] = {false, false};
-    const uint32_t r_next = 2u * k + 4u * (uint32_t)sqrtf((float)k) + 16u;
+    const uint32_t r_next = carried_rank(k);
     if (carry) {                                          // uniform
         // With the residual carried over, the k-th entry sits at the edge of a cliff (everything above
         // it has just been cut down to about mu), so a margin in value below it lets a flood of
