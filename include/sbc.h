@@ -189,8 +189,10 @@ int sbc_decompress_accumulate_noalloc(int device, void* hip_stream,
  *       does the call after one that saw many times k candidates (the data grew).  0 estimates
  *       the keys from a sample of the new data in every call.
  *   SBC_OPT_WIDE_MIN_KEPT      (default 0 = 8192)  a tensor that keeps at least this many entries
- *       per side is selected by grid-wide kernels instead of one workgroup (a 1.5e9-entry tensor
- *       at p = 0.001 keeps 1.5e6); tests lower it to send small tensors that way.
+ *       per side is selected by grid-wide kernels instead of one workgroup, and its stream is
+ *       decoded tile by tile by many workgroups instead of one (a 1.5e9-entry tensor at
+ *       p = 0.001 keeps 1.5e6); tests lower it to send small tensors that way, or raise it (one
+ *       workgroup selects and encodes up to 16384 kept entries by itself).
  *   SBC_OPT_SAMPLED_THRESHOLD  (0/1, default 0)  1 selects the subsampled variant of
  *       "Sparse Binarization" (the threshold is estimated from a random subsample, which makes
  *       the amount of sparsity noisy).  Per tensor t of the call a stratified sample of at most

@@ -59,6 +59,11 @@ constexpr int kBucketBits = 11;          // index sort of the fused encoder: buc
 constexpr int kBuckets = 1 << kBucketBits;
 constexpr uint32_t kFusedMaxK = 6144;    // a tensor with k up to this, and a stream bound of up to
 constexpr uint32_t kFusedMaxWords = 4096; // this many words, is sorted and encoded inside the select kernel
+// ... and so is one that keeps up to kFusedBigK entries, if that is below the threshold of the
+// grid-wide kernels: beyond kSelLds kept entries the candidate lists cannot be staged in LDS,
+// which leaves their space to the sort.  (One workgroup reads such lists from memory in every
+// sweep; by default the grid-wide kernels take over from 8192 kept entries.)
+constexpr uint32_t kFusedBigK = 16384;
 constexpr int kFilterQueue = 1024;       // candidates per side a workgroup of the streaming kernel can queue in LDS
 constexpr uint32_t kMaxChunksPerWorkgroup = 8;   // consecutive chunks of one very long tensor per such workgroup
 

@@ -515,7 +515,7 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     c->max_elems = max_total_elems;
     c->max_tensors = max_tensors;
     c->max_chunks = (uint64_t)max_total_elems / kChunk + (uint64_t)max_tensors;
-    c->kept_cap = std::min<uint64_t>((uint64_t)max_total_elems, (uint64_t)kFusedMaxK * (uint64_t)max_tensors);
+    c->kept_cap = std::min<uint64_t>((uint64_t)max_total_elems, (uint64_t)kFusedBigK * (uint64_t)max_tensors);
     // A tensor's stream is at most k(1+b*) + (n-k)/2^b* bits, which stays below 1.3 n for every p
     // (b* shrinks as p grows); n/16 words plus rounding per tensor is ample, and sbc_compress
     // checks the actual need against this capacity.
@@ -710,7 +710,8 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
             const uint64_t bw = bound_words_of(n, d.kcap, b);
             if (bw >= (1ull << 32)) return SBC_ECAPACITY;
             d.bound_words = (uint32_t)bw;
-            const bool fused = d.kcap <= kFusedMaxK && bw <= kFusedMaxWords;
+            const bool fused = (d.kcap <= kFusedMaxK && bw <= kFusedMaxWords) ||
+                               (d.kcap <= kFusedBigK && d.kcap < c->wide_min_kept && bw + 1u <= fused_sort_capacity(d.kcap));
             // finished inside the streaming kernel: exact mode, and few enough kept entries and stream
             // words for one workgroup's LDS (a one-chunk tensor: any k, encoded from a bitmap)
             const uint32_t n_groups = (d.nchunks + kGroupChunks - 1u) / kGroupChunks;

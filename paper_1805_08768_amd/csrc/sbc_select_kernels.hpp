@@ -55,6 +55,12 @@ constexpr int kWinShift = 11;                            // it counts key >> kWi
 constexpr uint32_t kRankMax = 512;                       // threshold buckets up to this size are ranked directly
 static_assert(2 * kFusedMaxK * 4 <= kSelLds * 8, "sort arrays reuse one side's candidate space");
 static_assert(kFusedMaxWords <= kFusedMaxK, "stream words reuse the grouping array");
+static_assert(kFusedBigK == 2 * kSelLds, "a large tensor's sort arrays take one side's candidate space each");
+
+// Capacity (entries, and stream words + 1) of each of the two sort arrays of the fused encoder for
+// a tensor that keeps k entries per side: lists that keep more than kSelLds entries are never
+// staged in LDS, so both sides' space is free.
+__host__ __device__ inline uint32_t fused_sort_capacity(uint32_t k) { return k > kSelLds ? 2u * kSelLds : kSelLds; }
 
 struct SelectShared {
     uint2 cand[2][kSelLds];                              // both sides' lists when they fit
@@ -536,8 +542,14 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     SBC_TS(1, 6);
     // ---- fused: sort the k kept indices, encode their gaps (Alg. 3), write the stream ----
     // the LDS space of the side that was not chosen holds the sort arrays
-    uint32_t* grp = reinterpret_cast<uint32_t*>(sh.cand[chosen ^ 1]);   // kept indices grouped by bucket
-    uint32_t* sorted = grp + kFusedMaxK;                                // kept indices ascending
+    // (both sides' space if the lists are read from memory: see fused_sort_capacity)
+    const uint32_t sort_cap = list.staged ? kSelLds : 2u * kSelLds;
+    uint32_t* grp = reinterpret_cast<uint32_t*>(list.staged ? sh.cand[chosen ^ 1] : sh.cand[0]);   // kept indices grouped by bucket
+    uint32_t* sorted = grp + sort_cap;                                  // kept indices ascending
+    if (kk > sort_cap) {                              // uniform; cannot happen: staged lists hold at most kSelLds entries
+        if (tid == 0) atomicOr(&result->err, kErrInternal);
+        return;
+    }
     int shift = 32 - __clz((int)(n - 1u | 1u)) - kBucketBits;           // bucket = idx >> shift, below kBuckets
     if (shift < 0) shift = 0;
     for (int i = tid; i < kBuckets; i += kSelThreads) { sh.bucket_cnt[i] = 0u; sh.bucket_fill[i] = 0u; }
@@ -599,7 +611,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     unsigned long long total_bits;
     unsigned long long pos = block_excl_sum<unsigned long long, kSelThreads>(bits, &total_bits, sh.scratch64);
     const uint32_t n_words = (uint32_t)((total_bits + 31ull) >> 5);
-    if (n_words > d.bound_words || n_words > kFusedMaxWords) {   // uniform; cannot happen
+    if (n_words > d.bound_words || n_words + 1u > sort_cap) {    // uniform; cannot happen
         if (tid == 0) atomicOr(&result->err, kErrInternal);
         return;
     }

@@ -531,11 +531,12 @@ def test_histogram_fallback_bitmap_and_grid_wide_tensors_in_one_call():
     """One call whose tensors take every route at once: tensor 0 keeps enough entries for the
     grid-wide kernels; tensor 1 keeps too many for the fused encoder and too few for those (one
     workgroup selects, positions go through the bitmap); tensor 2 has its large entries exactly
-    where the sampler looks, so its filter keeps too few and the histogram route redoes it."""
-    sizes = [100000, 70000, 50000, 300]
+    where the sampler looks, so its filter keeps too few and the histogram route redoes it; tensor
+    3 keeps more than the lists staged in LDS hold and is sorted and encoded by one workgroup."""
+    sizes = [250000, 170000, 50000, 100000, 300]
     p = 0.1
     with DeviceRun(sizes) as run:
-        sbc.sbc_set_option(run.ctx, sbc.SBC_OPT_WIDE_MIN_KEPT, 9000)
+        sbc.sbc_set_option(run.ctx, sbc.SBC_OPT_WIDE_MIN_KEPT, 20000)
         R = [np.zeros(n, np.float32) for n in sizes]
         for r in range(2):
             dWs = [synth.gaussian_update(n, round_=r, tensor=i) for i, n in enumerate(sizes)]
@@ -547,7 +548,7 @@ def test_histogram_fallback_bitmap_and_grid_wide_tensors_in_one_call():
             res = check_round(run, dWs, R, p)
             route = sbc.sbc_last_route(run.ctx)
             assert route & sbc.SBC_ROUTE_HISTOGRAM and route & sbc.SBC_ROUTE_WIDE, route
-            assert res[1].k > 6144 and res[1].k < 9000 and res[0].k >= 9000
+            assert 16384 < res[1].k < 20000 <= res[0].k and 8192 < res[3].k <= 16384
             R = [x.R_new for x in res]
 
 
