@@ -216,8 +216,8 @@ def main() -> int:
         gen = lambda r: [synth.student_t_update(4194304, round_=r)]
         name = "one tensor, 4,194,304 entries, Student-t(3), p=0.001"
     else:
-        sizes = [1_500_000_000]; n_sets = 1
-        gen = lambda r: [np.concatenate([c for _, c in synth.flat_gaussian_chunks(sizes[0])])]
+        sizes = [1_500_000_000]; n_sets = 2
+        gen = lambda r: [np.concatenate([c for _, c in synth.flat_gaussian_chunks(sizes[0], round_=r)])]
         name = "one flat tensor, 1.5e9 entries, N(0,1e-6), p=0.001"
     N = sum(sizes)
     T = len(sizes)

@@ -99,7 +99,7 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
         z.kc[0] = z.kc[1] = 0u;
         z.S[0] = z.S[1] = 0.0;
         z.side = 0; z.mu_signed = 0.f; z.nnz = 0u; z.flags = 0u; z.bit_len = 0ull;
-        z.done = 0u; z.pad = 0u; z.cand_seen[0] = z.cand_seen[1] = 0u;
+        z.done = 0u; z.pad = 0u; z.cand_seen[0] = z.cand_seen[1] = 0u; z.expect[0] = z.expect[1] = 0u;
         st[t] = z;
     }
     if (force_exact) return;

@@ -124,6 +124,8 @@ struct alignas(8) TensorState {
     uint32_t done;         // chunks (or groups of chunks) of this tensor that the streaming kernel has completed
     uint32_t pad;
     uint32_t cand_seen[2]; // candidates per side the finishing workgroup found (inspection)
+    uint32_t expect[2];    // carried keys: entries per side known to lie at or beyond lo_key before the next update
+                           // is added (0: not known)
 };
 
 // Per group of kGroupChunks consecutive chunks of a tensor that the streaming kernel finishes
@@ -174,9 +176,20 @@ __device__ __forceinline__ uint32_t carried_key(uint32_t tau_side_key, uint32_t 
     return lo > tau_side_key ? tau_side_key : lo;
 }
 
-// Rank of the entry whose key a following call starts from (see k_select).
+// Rank of the entry whose key a following call starts from (see k_select): the k entries kept now
+// are gone from above that key in the next call (on the side that is sent), and k more must
+// remain even if the next update moves nothing across the key.
 __device__ __forceinline__ uint32_t carried_rank(uint32_t k) {
-    return k + k / 8u + 4u * (uint32_t)sqrtf((float)k) + 16u;
+    return 2u * k + 4u * (uint32_t)sqrtf((float)k) + 16u;
+}
+// The same when this call could see how many entries the update moved across the key it started
+// from: `net` more than were known to lie beyond it (net < 0: fewer).  Half of that gain is
+// counted on again; at least k / 8 entries beside the k-th stay in reserve.
+__device__ __forceinline__ uint32_t carried_rank(uint32_t k, long long net) {
+    long long spare = (long long)k - net / 2;
+    const long long lo = (long long)(k / 8u), hi = 2ll * (long long)k;
+    spare = spare < lo ? lo : (spare > hi ? hi : spare);
+    return k + (uint32_t)spare + 4u * (uint32_t)sqrtf((float)k) + 16u;
 }
 
 // A side key moved towards less extreme values by the fraction `margin` of its value.
@@ -213,25 +226,46 @@ __device__ __forceinline__ uint32_t extrapolated_key(uint32_t tau_side_key, uint
 
 // ----------------------------------------------------------------- scans ----
 
-template <typename T>
-__device__ __forceinline__ T wave_incl_sum(T v) {
-    const int lane = threadIdx.x & 63;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        T o = __shfl_up(v, d, 64);
-        if (lane >= d) v += o;
+// Wavefront scans through the data-parallel primitives of the vector ALU (a lane reads the
+// register of another lane of its row of 16, or a row's last lane is broadcast to the rows after
+// it) instead of the LDS crossbar: six steps of a few cycles each.  A lane without a source lane
+// in a step receives the identity (0).
+//   row_shr:d (d = 1, 2, 4, 8): lane i of a row reads lane i - d of the same row
+//   row_bcast:15 to rows 1 and 3, row_bcast:31 to rows 2 and 3
+template <int CTRL, int ROW_MASK, typename T>
+__device__ __forceinline__ T dpp_fetch(T v) {
+    static_assert(sizeof(T) == 4 || sizeof(T) == 8, "32- or 64-bit values");
+    if constexpr (sizeof(T) == 4) {
+        return (T)(uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, CTRL, ROW_MASK, 0xf, false);
+    } else {
+        const unsigned long long x = (unsigned long long)v;
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)x, CTRL, ROW_MASK, 0xf, false);
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(x >> 32), CTRL, ROW_MASK, 0xf, false);
+        return (T)(((unsigned long long)hi << 32) | lo);
     }
-    return v;
 }
 
 template <typename T>
+__device__ __forceinline__ T wave_incl_sum(T v) {
+    v += dpp_fetch<0x111, 0xf>(v);
+    v += dpp_fetch<0x112, 0xf>(v);
+    v += dpp_fetch<0x114, 0xf>(v);
+    v += dpp_fetch<0x118, 0xf>(v);
+    v += dpp_fetch<0x142, 0xa>(v);
+    v += dpp_fetch<0x143, 0xc>(v);
+    return v;
+}
+
+// (unsigned values: the identity 0 never wins)
+template <typename T>
 __device__ __forceinline__ T wave_incl_max(T v) {
-    const int lane = threadIdx.x & 63;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        T o = __shfl_up(v, d, 64);
-        if (lane >= d && o > v) v = o;
-    }
+    T o;
+    o = dpp_fetch<0x111, 0xf>(v); v = o > v ? o : v;
+    o = dpp_fetch<0x112, 0xf>(v); v = o > v ? o : v;
+    o = dpp_fetch<0x114, 0xf>(v); v = o > v ? o : v;
+    o = dpp_fetch<0x118, 0xf>(v); v = o > v ? o : v;
+    o = dpp_fetch<0x142, 0xa>(v); v = o > v ? o : v;
+    o = dpp_fetch<0x143, 0xc>(v); v = o > v ? o : v;
     return v;
 }
 

@@ -218,6 +218,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     const uint32_t cnt_p = __builtin_amdgcn_readfirstlane(st[t].cand_cnt[0]);
     const uint32_t cnt_n = __builtin_amdgcn_readfirstlane(st[t].cand_cnt[1]);
     const uint32_t lo_key_p = st[t].lo_key[0], lo_key_n = st[t].lo_key[1];
+    const uint32_t expect_p = st[t].expect[0], expect_n = st[t].expect[1];
     if (pass == 1 && !(st_flags & (kStExact | kStDeferred))) return;
     if (pass == 0 && (d.flags & kDescWide) && (st_flags & kStWideDone)) return;   // done by the grid-wide kernels
     if (pass == 0 && (st_flags & kStInlineDone)) return;                          // done by the streaming kernel
@@ -302,10 +303,13 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     // entry, r = 2 k + 4 sqrt(k) + 16 (if the next update is small beside the residual, the k
     // entries kept now are gone from above that key, and k more must remain).  A list shorter
     // than r says nothing about that entry: its place is extrapolated from the k-th.
-    const uint32_t r_next = carried_rank(k);
+    // (a call that started from carried keys sees how many entries its update moved across them,
+    // and counts on half as many again: see carried_rank)
+    const bool net_known = pass == 0 && carry && expect_p != 0u && expect_n != 0u;
+    const uint32_t rank2[2] = {net_known ? carried_rank(k, (long long)cnt_p - (long long)expect_p) : carried_rank(k),
+                               net_known ? carried_rank(k, (long long)cnt_n - (long long)expect_n) : carried_rank(k)};
     uint32_t digit2[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};
     if (pick) {
-        const uint32_t rank2[2] = {r_next, r_next};
         pick_wide_both<kWindow, kSelThreads>(sh.whist, need, both, sh.res[0], sh.scratch64, digit, found,
                                              carry ? rank2 : nullptr, sh.res[1], digit2);
         // entries in each side's threshold bucket (same leading key bits as the k-th entry)
@@ -508,9 +512,13 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         // filter keys a following round may start from instead of sampling
         if (carry) {
 #pragma unroll
-            for (int s = 0; s < 2; ++s)
-                st[t].lo_key[s] = digit2[s] != 0xFFFFFFFFu ? (wbase[s] + digit2[s]) << kWinShift
-                                                           : extrapolated_key(tau[s], s ? lo_key_n : lo_key_p, k, r_next, n, s ? cnt_n : cnt_p);
+            for (int s = 0; s < 2; ++s) {
+                const bool ranked = digit2[s] != 0xFFFFFFFFu;
+                st[t].lo_key[s] = ranked ? (wbase[s] + digit2[s]) << kWinShift
+                                         : extrapolated_key(tau[s], s ? lo_key_n : lo_key_p, k, rank2[s], n, s ? cnt_n : cnt_p);
+                // at least rank2[s] entries lie at or beyond that key now; the side that is sent loses k of them
+                st[t].expect[s] = ranked ? rank2[s] - (s == chosen ? kk : 0u) : 0u;
+            }
         }
         // many times more candidates than needed: the next call should estimate its keys afresh
         // (lists somewhat too long for LDS only cost one more sweep here)

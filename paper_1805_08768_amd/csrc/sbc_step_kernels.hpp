@@ -433,8 +433,10 @@ __device__ __forceinline__ Decision select_tensor(StepShared& sh, int& parity, c
         st_t->mu_signed = dec.mu_signed;
         if (carry) {
 #pragma unroll
-            for (int s = 0; s < 2; ++s)
+            for (int s = 0; s < 2; ++s) {
                 st_t->lo_key[s] = short_list[s] ? extrapolated_key(tau[s], lo_cur[s], k, r_next, d.n, cnt[s]) : next_key[s];
+                st_t->expect[s] = 0u;
+            }
         }
     }
     return dec;

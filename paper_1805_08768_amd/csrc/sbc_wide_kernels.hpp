@@ -4,8 +4,8 @@
 // over the tensor's two candidate lists with a one-workgroup step in between.
 //
 //   k_wide_count (pass 0,1,2)  histogram of the next key digit over the entries that match the
-//                              digits fixed so far: 21 leading bits in a window above the filter
-//                              key, then 8 bits, then the last 3
+//                              digits fixed so far: 19 leading bits in a window above the filter
+//                              key, then 8 bits, then the last 5
 //   k_wide_pick  (pass 0,1,2)  the digit that holds the k-th entry of each side; after pass 2 the
 //                              threshold key tau, the number of entries equal to it and how many
 //                              of those are kept
@@ -26,7 +26,12 @@ namespace sbc {
 
 constexpr int kWideThreads = 256;        // sweep kernels
 constexpr uint32_t kWideTieMax = 1024;   // tied entries whose indices can be ranked
-constexpr int kWideLastBits = kWinShift - 8;   // key bits left for the third pass (the second takes 8)
+// First pass: the leading 19 key bits (1024 steps per octave) counted in a window of two octaves
+// above the filter key.  Wider than k_select's half octave on purpose: a filter key carried over
+// from the previous call may lie far below this call's k-th entry while the data still grows, and
+// a tensor whose k-th entry lies beyond the window falls to one workgroup.
+constexpr int kWideShift = 13;
+constexpr int kWideLastBits = kWideShift - 8;   // key bits left for the third pass (the second takes 8)
 static_assert(kWideLastBits >= 1 && kWideLastBits <= 11, "the last two digits fit the histogram");
 
 struct WideState {
@@ -39,6 +44,7 @@ struct WideState {
     uint32_t tie_cnt[2];  // indices collected by k_wide_ties
     uint32_t kc[2];       // entries kept per side: k, or (subsampled variant) the candidates up to the cap
     uint32_t all;         // 1: every candidate is kept (subsampled variant), tau is the filter key
+    uint32_t next_key[2]; // filter keys a following call may start from (see k_select)
 };
 
 // Entries kept per side of a tensor, from its candidate counts.
@@ -76,18 +82,18 @@ __global__ __launch_bounds__(kWideThreads) void k_wide_count(
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
         const uint2* __restrict__ list = cand + d.cand_off + (s ? d.n : 0u);
-        const uint32_t base = st[t].lo_key[s] >> kWinShift;
+        const uint32_t base = st[t].lo_key[s] >> kWideShift;
         const uint32_t prefix = ws[w].prefix[s];
         const uint64_t stride = (uint64_t)gridDim.x * kWideThreads;
 #pragma unroll 4
         for (uint64_t i = (uint64_t)blockIdx.x * kWideThreads + tid; i < cnt[s]; i += stride) {
             const uint32_t key = list[i].x;
             if (pass == 0) {
-                const uint32_t v = key >> kWinShift;
+                const uint32_t v = key >> kWideShift;
                 const uint32_t o = v >= base ? v - base : 0u;
                 atomicAdd(&hist[s][o < (uint32_t)(kWindow - 1) ? o : (uint32_t)(kWindow - 1)], 1u);
             } else if (pass == 1) {
-                if ((key >> kWinShift) == prefix) atomicAdd(&hist[s][(key >> kWideLastBits) & 255u], 1u);
+                if ((key >> kWideShift) == prefix) atomicAdd(&hist[s][(key >> kWideLastBits) & 255u], 1u);
             } else {
                 if ((key >> kWideLastBits) == prefix) atomicAdd(&hist[s][key & ((1u << kWideLastBits) - 1u)], 1u);
             }
@@ -105,7 +111,7 @@ __global__ __launch_bounds__(kSelThreads) void k_wide_pick(
         const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ wide_ids,
         const TensorState* __restrict__ st, WideState* __restrict__ ws, uint32_t* __restrict__ whist, int pass) {
     __shared__ uint32_t hist[2][kWindow];
-    __shared__ uint32_t res[8];
+    __shared__ uint32_t res[8], res2[2];
     __shared__ unsigned long long scratch64[kSelThreads / 64];
     const int w = blockIdx.x, tid = threadIdx.x;
     const int t = (int)wide_ids[w];
@@ -123,6 +129,7 @@ __global__ __launch_bounds__(kSelThreads) void k_wide_pick(
             z.itau[0] = z.itau[1] = 0xFFFFFFFFu;
             z.ties[0] = z.ties[1] = 0u; z.tie_cnt[0] = z.tie_cnt[1] = 0u;
             z.kc[0] = kc[0]; z.kc[1] = kc[1]; z.all = all ? 1u : 0u;
+            z.next_key[0] = st[t].lo_key[0]; z.next_key[1] = st[t].lo_key[1];
             ws[w] = z;
         }
         if (!enough) return;                           // k_select flags the tensor for the histogram path
@@ -137,14 +144,23 @@ __global__ __launch_bounds__(kSelThreads) void k_wide_pick(
     const bool both[2] = {true, true};
     uint32_t digit[2];
     bool found[2];
-    pick_wide_both<kWindow, kSelThreads>(hist, need, both, res, scratch64, digit, found);
+    // (first pass: the same scan also finds the bin of the entry a following call's key sits at)
+    const uint32_t r_next = carried_rank(kc[0] > kc[1] ? kc[0] : kc[1]);
+    const uint32_t rank2[2] = {r_next, r_next};
+    uint32_t digit2[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};
+    pick_wide_both<kWindow, kSelThreads>(hist, need, both, res, scratch64, digit, found, pass == 0 ? rank2 : nullptr, res2,
+                                         digit2);
     if (tid == 0) {
         bool ok = found[0] && found[1];
         if (pass == 0) {
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+                ws[w].next_key[s] = digit2[s] != 0xFFFFFFFFu ? ((st[t].lo_key[s] >> kWideShift) + digit2[s]) << kWideShift
+                                                              : lowered_key(st[t].lo_key[s], 0.1f);
             ok = ok && digit[0] != (uint32_t)(kWindow - 1) && digit[1] != (uint32_t)(kWindow - 1);
             if (ok) {
 #pragma unroll
-                for (int s = 0; s < 2; ++s) ws[w].prefix[s] = (st[t].lo_key[s] >> kWinShift) + digit[s];
+                for (int s = 0; s < 2; ++s) ws[w].prefix[s] = (st[t].lo_key[s] >> kWideShift) + digit[s];
             }
         } else if (ok) {
             const int bits = pass == 1 ? 8 : kWideLastBits;
@@ -311,15 +327,12 @@ __global__ __launch_bounds__(128) void k_wide_decide(
     st[t].flags |= kStWideDone;
     atomicOr(&result->err, kErrWide);
     // filter keys a following call may start from (same rule as in k_select)
-    const float margin = fminf(0.75f, fmaxf(0.04f, 3.0f * rsqrtf((float)k)));
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        const float x = __uint_as_float(bits_of_key(ws[w].tau[s]));
-        const float lo_x = x - margin * fabsf(x) - 1.17549435e-38f;
-        uint32_t lo = key_of_bits(__float_as_uint(lo_x));
-        if (lo > ws[w].tau[s]) lo = ws[w].tau[s];
-        st[t].lo_key[s] = lo;
-    }
+    st[t].lo_key[0] = ws[w].next_key[0];
+    st[t].lo_key[1] = ws[w].next_key[1];
+    st[t].expect[0] = 0u; st[t].expect[1] = 0u;
+    // many times more candidates than needed: the next call should estimate its keys afresh
+    const uint32_t many = 8u * k + 4096u;
+    if (st[t].cand_cnt[0] > many || st[t].cand_cnt[1] > many) atomicOr(&result->err, kErrLoose);
 }
 
 __global__ __launch_bounds__(kWideThreads) void k_wide_apply(
