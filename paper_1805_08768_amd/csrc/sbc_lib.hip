@@ -134,6 +134,7 @@ struct sbc_ctx {
     // ---- options ----
     int force_exact = 0;
     int carry_keys = 1;
+    int carry_backoff = 0, carry_hold = 0;   // sampled calls after a call whose carried keys let a flood pass
     int fused_step = 0;                   // the streaming kernel finishes the tensors it can by itself
     int sampled = 0;                      // subsampled variant: the sampled threshold decides what is kept
     int defer_decode = 0;                 // decode calls return once enqueued; sbc_decode_status reports
@@ -533,6 +534,7 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     ok = ok && dev_alloc(&c->d_order, T) == hipSuccess;
     ok = ok && dev_alloc(&c->d_hist, T * kL1Bins) == hipSuccess;
     ok = ok && dev_alloc(&c->d_state, T) == hipSuccess;
+    ok = ok && hipMemset(c->d_state, 0, sizeof(TensorState) * T) == hipSuccess;
     ok = ok && dev_alloc(&c->d_cand, 2 * (size_t)max_total_elems) == hipSuccess;
     ok = ok && dev_alloc(&c->d_bitmap, (size_t)c->max_chunks * kChunkWords) == hipSuccess;
     ok = ok && dev_alloc(&c->d_stage, (size_t)c->stage_cap) == hipSuccess;
@@ -612,7 +614,9 @@ int sbc_set_option(sbc_ctx* c, int option, int value) {
             c->hist_valid = false;
             c->cache_valid = false;                    // which tensors the streaming kernel finishes is part of the plan
             return SBC_OK;
-        case SBC_OPT_CARRY_FILTER_KEYS: c->carry_keys = value ? 1 : 0; c->hist_valid = false; return SBC_OK;
+        case SBC_OPT_CARRY_FILTER_KEYS:
+            c->carry_keys = value ? 1 : 0; c->hist_valid = false; c->carry_backoff = c->carry_hold = 0;
+            return SBC_OK;
         case SBC_OPT_FUSED_STEP:
             c->fused_step = value ? 1 : 0;
             c->hist_valid = false;
@@ -973,6 +977,17 @@ int sbc_compress_end(sbc_ctx* c, size_t* msg_bytes) {
     c->result_dirty = false;
     // the next call may start from this call's thresholds unless they proved unhelpful
     c->hist_valid = c->carry_keys && !P.sampled && !P.force_exact && !c->last_used_exact_path && !(err & kErrLoose);
+    // While the data still grows from call to call (the first rounds of a run, when the residual
+    // builds up) carried keys let floods of candidates pass again and again: every such call
+    // doubles the number of sampled calls that follow it, and a carried call that goes well ends that.
+    if (err & kErrLoose) {
+        c->carry_backoff = std::min(64, std::max(1, 2 * c->carry_backoff));
+        c->carry_hold = c->carry_backoff;
+    } else if (P.use_history) {
+        c->carry_backoff = 0;
+    } else if (c->carry_hold > 0 && --c->carry_hold > 0) {
+        c->hist_valid = false;
+    }
     if (c->hist_valid) {
         c->hist_p = P.p;
         c->hist_n.resize(T);
