@@ -117,7 +117,12 @@ size_t sbc_msg_bound_sampled(const int64_t* numel, int n_tensors, double p);
  *              *msg_bytes are not written
  * msg_bytes    host, receives the message size in bytes
  * Errors: SBC_EINVAL, SBC_ECAPACITY (nothing was enqueued), SBC_EHIP, SBC_ENONFINITE and
- * SBC_EINTERNAL (residual and msg contents are then unspecified). */
+ * SBC_EINTERNAL (residual and msg contents are then unspecified).
+ * Completion: the call returns as soon as the step's last kernel has reported the message size
+ * (it writes status and size to pinned host memory, where the call looks for them), which may be
+ * a few microseconds before hip_stream is idle.  msg and residual are complete for everything
+ * enqueued on hip_stream afterwards; whoever reads them outside that order (another stream, a
+ * blocking copy while hip_stream is a non-blocking stream) synchronises with hip_stream first. */
 int sbc_compress(sbc_ctx* ctx, void* hip_stream,
                  const float* const* dW, float* const* residual,
                  const int64_t* numel, int n_tensors, double p,
@@ -126,8 +131,9 @@ int sbc_compress(sbc_ctx* ctx, void* hip_stream,
 /* The same step in two calls, for callers that keep several independent client steps in flight
  * (one context, one stream and one set of buffers per client): sbc_compress_begin checks its
  * arguments (same meaning and errors as above) and enqueues the step on hip_stream without
- * waiting; sbc_compress_end waits for that step (not for work the caller has enqueued behind it
- * on the stream), completes the rare tensors that need a second pass, and returns the status
+ * waiting; sbc_compress_end waits until that step has reported its result (not for work the
+ * caller has enqueued behind it on the stream; see "Completion" above for what may be read
+ * when), completes the rare tensors that need a second pass, and returns the status
  * and the message size.  Between the two calls the context accepts
  * sbc_decompress_accumulate and nothing else (SBC_EINVAL), dW, residual and msg must not be
  * touched, and the host arrays passed to begin are no longer needed.  sbc_compress_end without

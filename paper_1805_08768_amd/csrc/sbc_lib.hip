@@ -7,6 +7,7 @@
 #include <hip/hip_ext.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -102,6 +103,7 @@ struct sbc_ctx {
     uint32_t* h_wide_ids = nullptr;
     ResultBlock* h_result_dev = nullptr;  // h_result as the device addresses it
     ResultBlock* h_result = nullptr;      // compress
+    uint32_t result_seq = 0;              // number of the latest launch of the message-assembly kernel
     ResultBlock* h_result_dec = nullptr;  // decode (its own block: a decode call may come between begin and end)
     DecDesc* h_dec = nullptr;
     uint2* h_dec_blocks = nullptr;
@@ -187,6 +189,7 @@ struct sbc_ctx {
     bool last_used_wide = false;
     bool last_loose = false;
     bool last_deferred = false;
+    hipStream_t last_stream = nullptr;    // stream of the last client step (its last kernel may still be draining)
 };
 
 namespace {
@@ -314,7 +317,7 @@ void launch_encode_and_gather(sbc_ctx* c, bool profile) {
     }
     SBC_LAUNCH(kStGather, profile, k_finish_message, dim3(T, P.gather_y), dim3(256), P.d_desc, c->d_state, T, b,
                c->d_stage, c->d_kept, c->d_group, P.msg8, (uint64_t)P.msg_capacity, P.res_now, P.res_next,
-               c->h_result_dev);
+               c->h_result_dev, ++c->result_seq);
 }
 
 // Alg. 2 for the pending step's tensors that keep very many entries, as grid-wide sweeps over
@@ -371,6 +374,20 @@ int enqueue_result_copy(sbc_ctx* c) {
 }
 
 int wait_result(sbc_ctx* c) {
+    // The message-assembly kernel writes the result block to pinned host memory and its sequence
+    // number last.  Looking for the number takes a microsecond or two once it is there, where the
+    // runtime's wait returns several microseconds after the stream has drained; calls that run
+    // longer than a fraction of a millisecond fall through to the runtime's wait.  (Not while
+    // kernels carry timing events: those are read right after this, and must be complete.)
+    if (c->profile_level == 0) {
+        const uint32_t want = c->result_seq;
+        const auto t0 = std::chrono::steady_clock::now();
+        for (int spin = 0;; ++spin) {
+            if (__atomic_load_n(&c->h_result->pad, __ATOMIC_ACQUIRE) == want) return SBC_OK;
+            if ((spin & 63) == 63 &&
+                std::chrono::steady_clock::now() - t0 > std::chrono::microseconds(300)) break;
+        }
+    }
     if ((c->pend.wait_on_event ? hipEventSynchronize(c->ev_result) : hipStreamSynchronize(c->pend.stream)) != hipSuccess) {
         (void)hipGetLastError();
         return SBC_EHIP;
@@ -571,6 +588,8 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     ok = ok && host_alloc(&c->h_order, T) == hipSuccess;
     ok = ok && host_alloc(&c->h_result, 1) == hipSuccess;
     ok = ok && hipHostGetDevicePointer(reinterpret_cast<void**>(&c->h_result_dev), c->h_result, 0) == hipSuccess;
+    // (a pinned block may come back from an earlier context with that context's sequence number in it)
+    if (ok) std::memset(c->h_result, 0, sizeof(ResultBlock));
     ok = ok && host_alloc(&c->h_result_dec, 1) == hipSuccess;
     ok = ok && host_alloc(&c->h_dec, T) == hipSuccess;
     ok = ok && host_alloc(&c->h_state, T) == hipSuccess;
@@ -925,6 +944,7 @@ int sbc_compress_end(sbc_ctx* c, size_t* msg_bytes) {
     c->cache_valid = true;
     if (P.slot_is_new) c->slot[P.slot].valid = true;
     c->last_T = T;
+    c->last_stream = stream;
     for (int st = 0; st < kNumStages; ++st) {
         if (!P.timed[st]) continue;
         float ms = 0.f;
@@ -1179,7 +1199,8 @@ int sbc_last_tensor_stats(sbc_ctx* c, int tensor, double* mu_pos, double* mu_neg
                           int64_t* nnz, int64_t* bit_len) {
     if (!c || !c->last_ok || tensor < 0 || tensor >= c->last_T) return SBC_EINVAL;
     DeviceGuard guard(c->device);
-    if (hipMemcpy(c->h_state, c->d_state + tensor, sizeof(TensorState), hipMemcpyDeviceToHost) != hipSuccess) {
+    if (hipStreamSynchronize(c->last_stream) != hipSuccess ||
+        hipMemcpy(c->h_state, c->d_state + tensor, sizeof(TensorState), hipMemcpyDeviceToHost) != hipSuccess) {
         (void)hipGetLastError();
         return SBC_EHIP;
     }
@@ -1196,7 +1217,8 @@ int sbc_last_tensor_stats(sbc_ctx* c, int tensor, double* mu_pos, double* mu_neg
 int sbc_last_candidates(sbc_ctx* c, int tensor, int64_t* positive, int64_t* negative) {
     if (!c || !c->last_ok || tensor < 0 || tensor >= c->last_T) return SBC_EINVAL;
     DeviceGuard guard(c->device);
-    if (hipMemcpy(c->h_state, c->d_state + tensor, sizeof(TensorState), hipMemcpyDeviceToHost) != hipSuccess) {
+    if (hipStreamSynchronize(c->last_stream) != hipSuccess ||
+        hipMemcpy(c->h_state, c->d_state + tensor, sizeof(TensorState), hipMemcpyDeviceToHost) != hipSuccess) {
         (void)hipGetLastError();
         return SBC_EHIP;
     }
@@ -1210,6 +1232,7 @@ int sbc_last_mask(sbc_ctx* c, int tensor, uint32_t* mask_words, size_t n_words) 
     const TensorDesc& d = c->plan[tensor];
     if (n_words != ((size_t)d.n + 31) / 32) return SBC_EINVAL;
     DeviceGuard guard(c->device);
+    if (hipStreamSynchronize(c->last_stream) != hipSuccess) { (void)hipGetLastError(); return SBC_EHIP; }
     if (d.flags & kDescFused) {
         // the select kernel left the sorted kept indices in scratch
         if (hipMemcpy(c->h_state, c->d_state + tensor, sizeof(TensorState), hipMemcpyDeviceToHost) != hipSuccess) {

@@ -964,6 +964,13 @@ __global__ __launch_bounds__(kStepThreads, 4) void k_client_step(
 // memory.  If some tensor still has to be redone by the kernels of the other routes, nothing but
 // the result block is written: the host launches those kernels and this one again.
 // --------------------------------------------------------------------------
+// The call's result block in pinned host memory is complete: its sequence number goes out last, so
+// that a host that polls for the number finds size and error word in place.
+__device__ __forceinline__ void publish_result(ResultBlock* host_result, uint32_t seq) {
+    __threadfence_system();
+    __hip_atomic_store(&host_result->pad, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 __global__ __launch_bounds__(256) void k_finish_message(const TensorDesc* __restrict__ desc,
                                                         TensorState* __restrict__ st, int T, int b,
                                                         const uint32_t* __restrict__ stage,
@@ -972,13 +979,13 @@ __global__ __launch_bounds__(256) void k_finish_message(const TensorDesc* __rest
                                                         uint8_t* __restrict__ msg, uint64_t msg_capacity,
                                                         ResultBlock* __restrict__ result,
                                                         ResultBlock* __restrict__ next_result,
-                                                        ResultBlock* __restrict__ host_result) {
+                                                        ResultBlock* __restrict__ host_result, uint32_t seq) {
     __shared__ unsigned long long part[2][4];
     const int t = blockIdx.x, tid = threadIdx.x;
     const bool lead = (blockIdx.y == 0);
     const uint32_t err_in = result->err;
     if (err_in & (kErrPrefilter | kErrDeferred | kErrInternal | kErrNonFinite)) {
-        if (t == 0 && lead && tid == 0) { host_result->msg_bytes = 0ull; host_result->pad = 0u; host_result->err = err_in; }
+        if (t == 0 && lead && tid == 0) { host_result->msg_bytes = 0ull; host_result->err = err_in; publish_result(host_result, seq); }
         return;
     }
     const TensorDesc d = desc[t];
@@ -1044,7 +1051,8 @@ __global__ __launch_bounds__(256) void k_finish_message(const TensorDesc* __rest
                 *reinterpret_cast<uint64_t*>(msg + 24) = 0ull;
                 const unsigned long long bytes = table_end + 4ull * tot_all;
                 result->msg_bytes = bytes;
-                host_result->msg_bytes = bytes; host_result->pad = 0u; host_result->err = err_in;
+                host_result->msg_bytes = bytes; host_result->err = err_in;
+                publish_result(host_result, seq);
                 // the result block of the next call starts out clean
                 next_result->err = 0u; next_result->pad = 0u; next_result->msg_bytes = 0ull;
             }

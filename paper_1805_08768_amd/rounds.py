@@ -48,8 +48,11 @@ class Client:
         sbc.sbc_compress_begin(self.ctx, self._dW_list, self._R_list, self.p, self.msg, self.stream)
 
     def end_upload(self):
-        """Waits for begin_upload; returns (msg, nbytes)."""
+        """Waits for begin_upload; returns (msg, nbytes).  The size is known as soon as the step's
+        last kernel has reported it, which may be before the client's stream is idle: whatever the
+        caller's current stream does next (the server's decoding) is ordered behind the client's."""
         self.nbytes = sbc.sbc_compress_end(self.ctx)
+        torch.cuda.current_stream().wait_stream(self.stream)
         return self.msg, self.nbytes
 
     def upload(self, update: Sequence[np.ndarray]):

@@ -672,6 +672,9 @@ def test_compress_begin_end_interleaved_clients():
                 sbc.sbc_set_option(runs[0].ctx, sbc.SBC_OPT_CARRY_FILTER_KEYS, 1)
             for c in (1, 0, 2):
                 nbytes = sbc.sbc_compress_end(runs[c].ctx)
+                # (the size is known before the client's stream is idle; the copies below run on
+                # another stream, so that stream is waited for first, as the header asks)
+                streams[c].synchronize()
                 res = o.compress_model(dWs[c], R[c], p)
                 assert msgs[c][:nbytes].cpu().numpy().tobytes() == o.build_message(res), (rnd, c)
                 for t, x in enumerate(res):
