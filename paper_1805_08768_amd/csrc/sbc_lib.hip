@@ -773,6 +773,12 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
 
     DeviceGuard guard(c->device);
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    // The previous step returned when its size was known, possibly before its last kernel had
+    // ended: a step on another stream must not touch the context's scratch before that.
+    if (c->last_T > 0 && c->last_stream != stream && hipStreamSynchronize(c->last_stream) != hipSuccess) {
+        (void)hipGetLastError();
+        return SBC_EHIP;
+    }
     if (!sizes_same) {
         // tables that depend on the sizes only: tensors by decreasing size, chunk -> tensor
         c->plan_order.resize(T);

@@ -456,9 +456,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         part[1] = common[1] ? exponent_sums<1, false>(sh, list, tau[1], itau[1], true, e_ref[1]) : 0ll;
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) part[s] += __shfl_down(part[s], off, 64);
-            if ((tid & 63) == 0) sh.fast_sum[s][tid >> 6] = part[s];
+            // (integer sums wrap consistently: the scan's last lane holds the wavefront's total)
+            const long long total = (long long)wave_incl_sum<unsigned long long>((unsigned long long)part[s]);
+            if ((tid & 63) == 63) sh.fast_sum[s][tid >> 6] = total;
         }
     }
     __syncthreads();

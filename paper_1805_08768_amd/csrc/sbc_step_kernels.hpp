@@ -1001,12 +1001,9 @@ __global__ __launch_bounds__(256) void k_finish_message(const TensorDesc* __rest
         all += words;
         if (i < t) mine += words;
     }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        mine += __shfl_down(mine, off, 64);
-        all += __shfl_down(all, off, 64);
-    }
-    if ((tid & 63) == 0) { part[0][tid >> 6] = mine; part[1][tid >> 6] = all; }
+    mine = wave_incl_sum(mine);                         // (the scan's last lane holds the wavefront's total)
+    all = wave_incl_sum(all);
+    if ((tid & 63) == 63) { part[0][tid >> 6] = mine; part[1][tid >> 6] = all; }
     __syncthreads();
     const unsigned long long word_off = part[0][0] + part[0][1] + part[0][2] + part[0][3];
     const unsigned long long tot_all = part[1][0] + part[1][1] + part[1][2] + part[1][3];
