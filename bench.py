@@ -167,6 +167,9 @@ def main() -> int:
                     help="clear SBC_OPT_CARRY_FILTER_KEYS (every round estimates its filter keys from a sample "
                          "instead of starting from the previous round's)")
     ap.add_argument("--fused-step", action="store_true", help="set SBC_OPT_FUSED_STEP")
+    ap.add_argument("--compact-context", action="store_true",
+                    help="contexts from sbc_create_compact (candidate lists of a quarter of each tensor per side: about 5 "
+                         "bytes of scratch per entry instead of 17)")
     ap.add_argument("--sampled-threshold", action="store_true",
                     help="set SBC_OPT_SAMPLED_THRESHOLD (the subsampled variant with a noisy amount of sparsity; "
                          "reported for reference, not the benchmark's mode)")
@@ -251,7 +254,7 @@ def main() -> int:
             self.msg = self.msgs[0]
             self.stream_obj = torch.cuda.current_stream() if index == 0 else torch.cuda.Stream()
             self.stream = self.stream_obj.cuda_stream     # raw handle, looked up once
-            self.ctx = sbc.sbc_create(0, N, T)
+            self.ctx = (sbc.sbc_create_compact if args.compact_context else sbc.sbc_create)(0, N, T)
             if args.no_carry_keys:
                 sbc.sbc_set_option(self.ctx, sbc.SBC_OPT_CARRY_FILTER_KEYS, 0)
             if args.fused_step:

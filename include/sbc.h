@@ -79,6 +79,24 @@ typedef struct sbc_ctx sbc_ctx;
  * allocation fails (nothing is leaked). */
 int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tensors);
 
+/* The same with candidate lists that hold a quarter of a tensor's entries per side instead of all
+ * of them (Alg. 2's top_p% only ever needs the entries near the k-th; "Sparse Binarization"):
+ * about 5 bytes per entry of max_total_elems instead of 17.  What it costs:
+ *   - a list holds max(n/4, 4 k + 1024) entries (k as sbc_num_kept gives it for the call's p,
+ *     never more than n); a call whose lists do not fit half an entry per entry of
+ *     max_total_elems in all (plus 2048 per tensor) returns SBC_ECAPACITY before anything is
+ *     enqueued (p above about 0.06 on a context sized for the model);
+ *   - a tensor whose filter lets more candidates pass than its lists hold is redone through the
+ *     histogram route, like one whose filter lets too few pass; if even that route's candidates
+ *     (the entries of the histogram bins at and beyond the k-th entry's) do not fit, as happens
+ *     when more than a quarter of the tensor's entries are about equal to the k-th (a constant
+ *     tensor), sbc_compress returns
+ *     SBC_ECAPACITY after the fact: no message was produced, and residual and msg contents are
+ *     unspecified as after the other late errors (the tensors that completed have had their kept
+ *     entries taken out of the residual).  Data like that needs a context from sbc_create.
+ * Results are the same as on a context from sbc_create whenever the call succeeds. */
+int sbc_create_compact(sbc_ctx** out, int device, int64_t max_total_elems, int max_tensors);
+
 /* Frees the context's scratch memory.  NULL is allowed.  The caller must have
  * no work of this context in flight. */
 void sbc_destroy(sbc_ctx* ctx);
@@ -116,8 +134,9 @@ size_t sbc_msg_bound_sampled(const int64_t* numel, int n_tensors, double p);
  * msg          device, 8-byte aligned, msg_capacity >= sbc_msg_bound(...) bytes; bytes past
  *              *msg_bytes are not written
  * msg_bytes    host, receives the message size in bytes
- * Errors: SBC_EINVAL, SBC_ECAPACITY (nothing was enqueued), SBC_EHIP, SBC_ENONFINITE and
- * SBC_EINTERNAL (residual and msg contents are then unspecified).
+ * Errors: SBC_EINVAL, SBC_ECAPACITY (nothing was enqueued; on a context from sbc_create_compact
+ * see there), SBC_EHIP, SBC_ENONFINITE and SBC_EINTERNAL (residual and msg contents are then
+ * unspecified).
  * Completion: the call returns as soon as the step's last kernel has reported the message size
  * (it writes status and size to pinned host memory, where the call looks for them), which may be
  * a few microseconds before hip_stream is idle.  msg and residual are complete for everything

@@ -36,7 +36,7 @@ SBC_ROUTE_LOOSE_KEYS = 8
 SBC_ROUTE_TAKEN_OVER = 16
 
 EXPORTS = (
-    "sbc_create", "sbc_destroy", "sbc_golomb_bstar", "sbc_num_kept", "sbc_msg_bound", "sbc_msg_bound_sampled",
+    "sbc_create", "sbc_create_compact", "sbc_destroy", "sbc_golomb_bstar", "sbc_num_kept", "sbc_msg_bound", "sbc_msg_bound_sampled",
     "sbc_compress", "sbc_compress_begin", "sbc_compress_end", "sbc_decompress_accumulate", "sbc_last_tensor_stats", "sbc_last_mask",
     "sbc_profile_enable", "sbc_profile_level", "sbc_profile_read", "sbc_copy_baseline", "sbc_set_option",
     "sbc_last_route", "sbc_strerror", "sbc_decode_status", "sbc_decompress_accumulate_noalloc", "sbc_last_candidates",
@@ -61,6 +61,8 @@ def load() -> ctypes.CDLL:
     vp, i64, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
     lib.sbc_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, ctypes.c_int]
     lib.sbc_create.restype = ctypes.c_int
+    lib.sbc_create_compact.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, ctypes.c_int]
+    lib.sbc_create_compact.restype = ctypes.c_int
     lib.sbc_destroy.argtypes = [vp]
     lib.sbc_destroy.restype = None
     lib.sbc_golomb_bstar.argtypes = [ctypes.c_double]
@@ -207,6 +209,15 @@ def sbc_create(device: int, max_total_elems: int, max_tensors: int) -> ctypes.c_
     rc = load().sbc_create(ctypes.byref(ctx), int(device), int(max_total_elems), int(max_tensors))
     if rc != SBC_OK:
         raise SbcError(rc, "sbc_create")
+    return ctx
+
+
+def sbc_create_compact(device: int, max_total_elems: int, max_tensors: int) -> ctypes.c_void_p:
+    """A context with candidate lists of a quarter of each tensor per side (about 5 bytes of scratch per entry)."""
+    ctx = ctypes.c_void_p()
+    rc = load().sbc_create_compact(ctypes.byref(ctx), int(device), int(max_total_elems), int(max_tensors))
+    if rc != SBC_OK:
+        raise SbcError(rc, "sbc_create_compact")
     return ctx
 
 

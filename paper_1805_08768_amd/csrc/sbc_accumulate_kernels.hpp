@@ -328,12 +328,11 @@ __device__ __forceinline__ void append_candidates(const uint32_t (&key)[PER], ui
     uint32_t op = base[0] + (ex & 0xFFFFu);
     uint32_t on = base[1] + (ex >> 16);
     __syncthreads();                                  // base may be rewritten by the next call
-    if (op + __popc(mp) > d.n || on + __popc(mn) > d.n) {   // cannot happen: a list holds at most n
-        atomicOr(&result->err, kErrInternal);
-        return;
-    }
+    // (beyond a list's capacity nothing is stored: the counters then show that the tensor's lists
+    // are not usable, see k_select; a list of a full context holds every entry)
+    if (op + __popc(mp) > d.cand_cap || on + __popc(mn) > d.cand_cap) return;
     uint2* __restrict__ cp = cand + d.cand_off;
-    uint2* __restrict__ cn = cand + d.cand_off + d.n;
+    uint2* __restrict__ cn = cand + d.cand_off + d.cand_cap;
 #pragma unroll
     for (int s = 0; s < PER; ++s) {
         const uint32_t idx = e_first + s * kStreamThreads + tid;
@@ -473,12 +472,10 @@ __global__ __launch_bounds__(kStreamThreads) void k_accumulate_filter(
             sh.base[1] = (uint32_t)(old >> 32);
         }
         __syncthreads();
-        if ((uint64_t)sh.base[0] + qp > d.n || (uint64_t)sh.base[1] + qn > d.n) {   // cannot happen
-            if (tid == 0) atomicOr(&result->err, kErrInternal);
-            return;
-        }
+        // (beyond a list's capacity nothing is stored: see append_candidates)
+        if ((uint64_t)sh.base[0] + qp > d.cand_cap || (uint64_t)sh.base[1] + qn > d.cand_cap) return;
         uint2* __restrict__ cp = cand + d.cand_off + sh.base[0];
-        uint2* __restrict__ cn = cand + d.cand_off + d.n + sh.base[1];
+        uint2* __restrict__ cn = cand + d.cand_off + d.cand_cap + sh.base[1];
         for (uint32_t i = tid; i < qp; i += kStreamThreads) cp[i] = sh.queue[0][i];
         for (uint32_t i = tid; i < qn; i += kStreamThreads) cn[i] = sh.queue[1][i];
         return;

@@ -71,6 +71,7 @@ constexpr uint32_t kMaxChunksPerWorkgroup = 8;   // consecutive chunks of one ve
 constexpr uint32_t kErrNonFinite = 1u;
 constexpr uint32_t kErrInternal = 2u;
 constexpr uint32_t kErrCorrupt = 4u;
+constexpr uint32_t kErrOverflow = 128u;  // a candidate list of a compact context cannot hold what the histogram route extracts
 constexpr uint32_t kErrPrefilter = 8u;   // not an error: some tensor needs the histogram path
 constexpr uint32_t kErrWide = 32u;       // not an error: the grid-wide selection kernels completed some tensor
 constexpr uint32_t kErrLoose = 16u;      // not an error: a carried-over filter key let far too many entries pass
@@ -97,14 +98,14 @@ struct TensorDesc {
     uint32_t k;           // entries kept per side
     uint32_t chunk0;      // first chunk of this tensor in the call-wide chunk numbering
     uint32_t nchunks;
-    uint64_t cand_off;    // candidate list of the positive side starts here; negative side at +n
+    uint64_t cand_off;    // candidate list of the positive side starts here; negative side at +cand_cap
     uint64_t stage_off;   // first word of this tensor's stream in the staging area
     uint32_t bound_words; // worst-case stream length in words
     uint32_t kept_off;    // first entry of this tensor in the kept-index scratch
     uint32_t flags;
     uint32_t kcap;        // most entries a side may keep: k, or min(n, 2k + 64) in the subsampled variant
     uint32_t grp0;        // first of this tensor's chunk groups
-    uint32_t pad;
+    uint32_t cand_cap;    // entries each side's candidate list holds: n, or fewer in a compact context
 };
 
 // Per-tensor results, written on the device.

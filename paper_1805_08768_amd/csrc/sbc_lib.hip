@@ -63,6 +63,8 @@ struct sbc_ctx {
     uint2* d_sched = nullptr;             // workgroup of the streaming kernel -> (chunk, tensor)
     GroupState* d_group = nullptr;        // per group of chunks: candidate and completion counters
     uint64_t max_groups = 0;
+    bool compact = false;                 // candidate lists of a few times k entries instead of n
+    uint64_t cand_entries = 0;            // entries d_cand holds
     uint32_t n_sched = 0;                 // workgroups of the streaming kernel
     uint32_t* d_order = nullptr;
     uint32_t* d_hist = nullptr;
@@ -264,6 +266,7 @@ void free_all(sbc_ctx* c) {
 int status_of_err(uint32_t err) {
     if (err & kErrInternal) return SBC_EINTERNAL;
     if (err & kErrNonFinite) return SBC_ENONFINITE;
+    if (err & kErrOverflow) return SBC_ECAPACITY;
     if (err & kErrCorrupt) return SBC_ECORRUPT;
     return SBC_OK;
 }
@@ -521,7 +524,7 @@ size_t sbc_msg_bound(const int64_t* numel, int n_tensors, double p) { return msg
 
 size_t sbc_msg_bound_sampled(const int64_t* numel, int n_tensors, double p) { return msg_bound(numel, n_tensors, p, true); }
 
-int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tensors) {
+static int create_context(sbc_ctx** out, int device, int64_t max_total_elems, int max_tensors, bool compact) {
     if (!out || max_total_elems < 1 || max_tensors < 1 || max_tensors >= (1 << 24)) return SBC_EINVAL;
     *out = nullptr;
     int n_dev = 0;
@@ -532,6 +535,10 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     c->device = device;
     c->max_elems = max_total_elems;
     c->max_tensors = max_tensors;
+    c->compact = compact;
+    // full: both sides' lists of every tensor hold every entry; compact: half an entry per entry in all
+    // (plus the lists' fixed part), shared out by the plan of each call
+    c->cand_entries = compact ? (uint64_t)max_total_elems / 2 + 2048ull * (uint64_t)max_tensors : 2ull * (uint64_t)max_total_elems;
     c->max_chunks = (uint64_t)max_total_elems / kChunk + (uint64_t)max_tensors;
     c->kept_cap = std::min<uint64_t>((uint64_t)max_total_elems, (uint64_t)kFusedBigK * (uint64_t)max_tensors);
     // A tensor's stream is at most k(1+b*) + (n-k)/2^b* bits, which stays below 1.3 n for every p
@@ -552,7 +559,7 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     ok = ok && dev_alloc(&c->d_hist, T * kL1Bins) == hipSuccess;
     ok = ok && dev_alloc(&c->d_state, T) == hipSuccess;
     ok = ok && hipMemset(c->d_state, 0, sizeof(TensorState) * T) == hipSuccess;
-    ok = ok && dev_alloc(&c->d_cand, 2 * (size_t)max_total_elems) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_cand, (size_t)c->cand_entries) == hipSuccess;
     ok = ok && dev_alloc(&c->d_bitmap, (size_t)c->max_chunks * kChunkWords) == hipSuccess;
     ok = ok && dev_alloc(&c->d_stage, (size_t)c->stage_cap) == hipSuccess;
     ok = ok && dev_alloc(&c->d_kept, (size_t)c->kept_cap) == hipSuccess;
@@ -618,6 +625,14 @@ int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tenso
     return SBC_OK;
 }
 
+int sbc_create(sbc_ctx** out, int device, int64_t max_total_elems, int max_tensors) {
+    return create_context(out, device, max_total_elems, max_tensors, false);
+}
+
+int sbc_create_compact(sbc_ctx** out, int device, int64_t max_total_elems, int max_tensors) {
+    return create_context(out, device, max_total_elems, max_tensors, true);
+}
+
 void sbc_destroy(sbc_ctx* c) {
     if (!c) return;
     DeviceGuard guard(c->device);
@@ -680,7 +695,7 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
     // to call while those stay the same.  The tensor table itself (sizes, offsets and the
     // pointers) lives in one of kDescSlots device copies keyed by the pointer lists, so a caller
     // that alternates between a few sets of buffers uploads nothing in the steady state.
-    uint64_t total = 0, chunks = 0, stage_words = 0, kept_total = 0, max_bound = 0, groups = 0;
+    uint64_t total = 0, chunks = 0, stage_words = 0, kept_total = 0, max_bound = 0, groups = 0, cand_total = 0;
     bool any_bitmap = false, all_inline = true;
     uint32_t scan_tiles = 1;
     // in the subsampled variant the keys must come from this call's sample
@@ -728,7 +743,12 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
             d.kcap = (uint32_t)cap_of(n, d.k, sampled);
             d.chunk0 = (uint32_t)chunks;
             d.nchunks = (uint32_t)((n + kChunk - 1) / kChunk);
-            d.cand_off = 2 * total;
+            // compact: a quarter of the tensor per side (the whole budget of half an entry per entry), more
+            // if k asks for it (then the budget may not do, and the call is refused below)
+            d.cand_cap = c->compact ? (uint32_t)std::min<uint64_t>((uint64_t)n, std::max<uint64_t>((uint64_t)n / 4u, 4ull * d.kcap + 1024ull))
+                                    : (uint32_t)n;
+            d.cand_off = cand_total;
+            cand_total += 2ull * d.cand_cap;
             d.stage_off = stage_words;
             const uint64_t bw = bound_words_of(n, d.kcap, b);
             if (bw >= (1ull << 32)) return SBC_ECAPACITY;
@@ -758,7 +778,7 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
             stage_words += bw;
             max_bound = std::max<uint64_t>(max_bound, bw);
             if (!fused) scan_tiles = std::max<uint32_t>(scan_tiles, (d.nchunks + kScanTile - 1u) / kScanTile);
-            if (total > (uint64_t)c->max_elems || chunks > c->max_chunks || kept_total > c->kept_cap ||
+            if (total > (uint64_t)c->max_elems || cand_total > c->cand_entries || chunks > c->max_chunks || kept_total > c->kept_cap ||
                 stage_words > c->stage_cap || groups > c->max_groups)
                 return SBC_ECAPACITY;
             c->plan[t] = d;
@@ -970,7 +990,7 @@ int sbc_compress_end(sbc_ctx* c, size_t* msg_bytes) {
     // and k_select for the tensors the streaming kernel left to it ----
     const uint32_t loose = err & kErrLoose;
     c->last_deferred = (err & kErrDeferred) != 0u;
-    if ((err & (kErrPrefilter | kErrDeferred)) && !(err & (kErrInternal | kErrNonFinite))) {
+    if ((err & (kErrPrefilter | kErrDeferred)) && !(err & (kErrInternal | kErrNonFinite | kErrOverflow))) {
         c->last_used_exact_path = (err & kErrPrefilter) != 0u;
         hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, stream, reinterpret_cast<uint32_t*>(res_now),
                            (uint64_t)(sizeof(ResultBlock) / 4));

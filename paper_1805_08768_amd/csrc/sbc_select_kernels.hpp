@@ -229,6 +229,16 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         if (tid == 0) atomicOr(&result->err, kErrInternal);
         return;
     }
+    if (cnt_p > d.cand_cap || cnt_n > d.cand_cap) {
+        // compact context: more candidates than a list holds (nothing was stored beyond its end).  The
+        // histogram route extracts a tighter set; if that does not fit either, the call fails.
+        if (tid == 0) {
+            st[t].flags = kStFailed;
+            st[t].bit_len = 0ull; st[t].nnz = 0u;
+            atomicOr(&result->err, pass == 0 && !sampled ? kErrPrefilter : kErrOverflow);
+        }
+        return;
+    }
     if (!sampled && (cnt_p < k || cnt_n < k)) {
         // the filter kept too few entries on a side: the histogram path redoes this tensor
         if (tid == 0) {
@@ -243,7 +253,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     SBC_TS_VAL(1, 13, cnt_p); SBC_TS_VAL(1, 14, cnt_n); SBC_TS_VAL(1, 15, (unsigned)t);
     CandLists list;
     list.g[0] = cand + d.cand_off; list.cnt[0] = cnt_p;
-    list.g[1] = cand + d.cand_off + n; list.cnt[1] = cnt_n;
+    list.g[1] = cand + d.cand_off + d.cand_cap; list.cnt[1] = cnt_n;
     list.staged = cnt_p <= kSelLds && cnt_n <= kSelLds;
 
     // Leading 21 key bits of the k-th most extreme entry of each side.  Every candidate's key is at

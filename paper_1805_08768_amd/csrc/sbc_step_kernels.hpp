@@ -812,7 +812,7 @@ __global__ __launch_bounds__(kStepThreads, 4) void k_client_step(
         overflow = overflow || x > (uint32_t)kWaveQueue || y > (uint32_t)kWaveQueue;
     }
     uint2* __restrict__ lp = cand + d.cand_off;
-    uint2* __restrict__ ln = cand + d.cand_off + d.n;
+    uint2* __restrict__ ln = cand + d.cand_off + d.cand_cap;
     unsigned long long* const counter = reinterpret_cast<unsigned long long*>(&st[t].cand_cnt[0]);
     const uint32_t grp = cc / (uint32_t)kGroupChunks;
     const uint32_t n_groups = (d.nchunks + kGroupChunks - 1u) / kGroupChunks;
@@ -834,8 +834,8 @@ __global__ __launch_bounds__(kStepThreads, 4) void k_client_step(
             }
             __syncthreads();
             const uint32_t bp0 = sh.base[0], bn0 = sh.base[1];
-            if ((uint64_t)bp0 + qp > d.n || (uint64_t)bn0 + qn > d.n) {   // cannot happen: a list holds at most n
-                fatal = true;
+            if ((uint64_t)bp0 + qp > d.cand_cap || (uint64_t)bn0 + qn > d.cand_cap) {
+                // (beyond a list's capacity nothing is stored: the counters then show that the lists are not usable)
             } else {
                 for (uint32_t i = lane; i < wc_p; i += 64u) { const uint2 e = sh.wq(wave, 0)[i]; store_cand(lp + bp0 + before_p + i, e.x, e.y); }
                 for (uint32_t i = lane; i < wc_n; i += 64u) { const uint2 e = sh.wq(wave, 1)[i]; store_cand(ln + bn0 + before_n + i, e.x, e.y); }
@@ -880,7 +880,7 @@ __global__ __launch_bounds__(kStepThreads, 4) void k_client_step(
             __syncthreads();
             uint32_t op = sh.base[0] + (ex & 0xFFFFu), on = sh.base[1] + (ex >> 16);
             __syncthreads();                              // base is rewritten in the next round
-            if ((uint64_t)op + __popc(mp) > d.n || (uint64_t)on + __popc(mn) > d.n) { fatal = true; continue; }
+            if ((uint64_t)op + __popc(mp) > d.cand_cap || (uint64_t)on + __popc(mn) > d.cand_cap) continue;   // (nothing is stored beyond a list's capacity)
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const uint32_t pos = base0 + (uint32_t)j * kStepThreads + tid;
@@ -907,6 +907,11 @@ __global__ __launch_bounds__(kStepThreads, 4) void k_client_step(
     if (tid == 0) { st[t].cand_seen[0] = cnt_p; st[t].cand_seen[1] = cnt_n; }
     if (cnt_p > d.n || cnt_n > d.n) {
         if (tid == 0) atomicOr(&result->err, kErrInternal);
+        return;
+    }
+    if (cnt_p > d.cand_cap || cnt_n > d.cand_cap) {
+        // compact context: more candidates than a list holds; the histogram route extracts a tighter set
+        if (tid == 0) { st[t].flags = kStFailed; atomicOr(&result->err, kErrPrefilter); }
         return;
     }
     if (cnt_p < d.k || cnt_n < d.k) {
@@ -984,7 +989,7 @@ __global__ __launch_bounds__(256) void k_finish_message(const TensorDesc* __rest
     const int t = blockIdx.x, tid = threadIdx.x;
     const bool lead = (blockIdx.y == 0);
     const uint32_t err_in = result->err;
-    if (err_in & (kErrPrefilter | kErrDeferred | kErrInternal | kErrNonFinite)) {
+    if (err_in & (kErrPrefilter | kErrDeferred | kErrInternal | kErrNonFinite | kErrOverflow)) {
         if (t == 0 && lead && tid == 0) { host_result->msg_bytes = 0ull; host_result->err = err_in; publish_result(host_result, seq); }
         return;
     }

@@ -52,11 +52,11 @@ __device__ __forceinline__ void wide_kept(const TensorDesc& d, const TensorState
     const uint32_t cp = s.cand_cnt[0], cn = s.cand_cnt[1];
     if (d.flags & kDescSampled) {
         kc[0] = min(cp, d.kcap); kc[1] = min(cn, d.kcap);
-        enough = cp >= 1u && cn >= 1u && cp <= d.n && cn <= d.n;
+        enough = cp >= 1u && cn >= 1u && cp <= d.cand_cap && cn <= d.cand_cap;
         all = cp <= d.kcap && cn <= d.kcap;
     } else {
         kc[0] = kc[1] = d.k;
-        enough = cp >= d.k && cn >= d.k && cp <= d.n && cn <= d.n;
+        enough = cp >= d.k && cn >= d.k && cp <= d.cand_cap && cn <= d.cand_cap;
         all = false;
     }
 }
@@ -70,7 +70,7 @@ __global__ __launch_bounds__(kWideThreads) void k_wide_count(
     const int t = (int)wide_ids[w];
     if (pass > 0 && !ws[w].ok) return;
     const TensorDesc d = desc[t];
-    const uint32_t cnt[2] = {min(st[t].cand_cnt[0], d.n), min(st[t].cand_cnt[1], d.n)};
+    const uint32_t cnt[2] = {min(st[t].cand_cnt[0], d.cand_cap), min(st[t].cand_cnt[1], d.cand_cap)};
     {
         uint32_t kc[2];
         bool enough, all;
@@ -81,7 +81,7 @@ __global__ __launch_bounds__(kWideThreads) void k_wide_count(
     __syncthreads();
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-        const uint2* __restrict__ list = cand + d.cand_off + (s ? d.n : 0u);
+        const uint2* __restrict__ list = cand + d.cand_off + (s ? d.cand_cap : 0u);
         const uint32_t base = st[t].lo_key[s] >> kWideShift;
         const uint32_t prefix = ws[w].prefix[s];
         const uint64_t stride = (uint64_t)gridDim.x * kWideThreads;
@@ -193,9 +193,9 @@ __global__ __launch_bounds__(kWideThreads) void k_wide_ties(
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
         if (ws[w].need[s] >= ws[w].ties[s]) continue;          // all ties are kept
-        const uint32_t cnt = min(st[t].cand_cnt[s], d.n);
+        const uint32_t cnt = min(st[t].cand_cnt[s], d.cand_cap);
         const uint32_t tau = ws[w].tau[s];
-        const uint2* __restrict__ list = cand + d.cand_off + (s ? d.n : 0u);
+        const uint2* __restrict__ list = cand + d.cand_off + (s ? d.cand_cap : 0u);
         uint32_t* __restrict__ out = wtie + ((size_t)w * 2 + s) * kWideTieMax;
         const uint64_t stride = (uint64_t)gridDim.x * kWideThreads;
 #pragma unroll 4
@@ -255,9 +255,9 @@ __global__ __launch_bounds__(kWideThreads) void k_wide_sums(
     __syncthreads();
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-        const uint32_t cnt = min(st[t].cand_cnt[s], d.n);
+        const uint32_t cnt = min(st[t].cand_cnt[s], d.cand_cap);
         const uint32_t tau = ws[w].tau[s], itau = ws[w].itau[s];
-        const uint2* __restrict__ list = cand + d.cand_off + (s ? d.n : 0u);
+        const uint2* __restrict__ list = cand + d.cand_off + (s ? d.cand_cap : 0u);
         const uint64_t stride = (uint64_t)gridDim.x * kWideThreads;
         uint32_t cur_ex = 0u;
         long long cur = 0ll;
@@ -345,9 +345,9 @@ __global__ __launch_bounds__(kWideThreads) void k_wide_apply(
     const TensorDesc d = desc[t];
     const int s = st[t].side < 0 ? 1 : 0;
     const float mu_signed = st[t].mu_signed;
-    const uint32_t cnt = min(st[t].cand_cnt[s], d.n);
+    const uint32_t cnt = min(st[t].cand_cnt[s], d.cand_cap);
     const uint32_t tau = ws[w].tau[s], itau = ws[w].itau[s];
-    const uint2* __restrict__ list = cand + d.cand_off + (s ? d.n : 0u);
+    const uint2* __restrict__ list = cand + d.cand_off + (s ? d.cand_cap : 0u);
     const gfloat_ptr R = as_global(d.R);
     uint32_t* __restrict__ bm = bitmap + (uint64_t)d.chunk0 * kChunkWords;
     const uint64_t stride = (uint64_t)gridDim.x * kWideThreads;

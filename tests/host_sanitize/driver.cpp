@@ -213,6 +213,22 @@ int main(int argc, char** argv) {
         }
     }
 
+    // ---- a context with short candidate lists: the plan shares them out, large p does not fit ----
+    {
+        CHECK(sbc_create_compact(nullptr, 0, 10, 1) == SBC_EINVAL);
+        CHECK(sbc_create_compact(&c, 0, m.total(), m.T()) == SBC_OK);
+        for (double q : {0.001, 0.01, 0.05}) {
+            const size_t nb = sbc_msg_bound(m.numel.data(), m.T(), q);
+            CHECK(compress(c, m, q, nb, &nbytes) == SBC_OK);
+            CHECK(sbc_decompress_accumulate(c, nullptr, kMsg, nb, m.numel.data(), m.T(), q, 1.f, m.out.data()) == SBC_OK);
+        }
+        const long launched = stub_launches();
+        CHECK(compress(c, m, 0.3, sbc_msg_bound(m.numel.data(), m.T(), 0.3), &nbytes) == SBC_ECAPACITY);
+        CHECK(stub_launches() == launched);
+        sbc_destroy(c); c = nullptr;
+        CHECK(stub_live_blocks() == 0);
+    }
+
     // ---- the server step that allocates nothing ----
     {
         int32_t* const status = reinterpret_cast<int32_t*>(0x500000000000ull);

@@ -24,12 +24,13 @@ def mask_to_positions(words: torch.Tensor, n: int) -> np.ndarray:
 class DeviceRun:
     """One sbc context plus device copies of a model's update and residual."""
 
-    def __init__(self, sizes: Sequence[int], device: str = "cuda:0", slack: int = 0, sampled: bool = False):
+    def __init__(self, sizes: Sequence[int], device: str = "cuda:0", slack: int = 0, sampled: bool = False,
+                 compact: bool = False):
         self.sizes = [int(s) for s in sizes]
         self.device = device
         self.sampled = sampled
         dev_index = 0 if device == "cpu" else torch.device(device).index or 0
-        self.ctx = sbc.sbc_create(dev_index, sum(self.sizes) + slack, len(self.sizes))
+        self.ctx = (sbc.sbc_create_compact if compact else sbc.sbc_create)(dev_index, sum(self.sizes) + slack, len(self.sizes))
         if sampled:
             sbc.sbc_set_option(self.ctx, sbc.SBC_OPT_SAMPLED_THRESHOLD, 1)
         if FUSED_STEP:

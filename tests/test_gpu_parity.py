@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 
 # tests that only run with the default setting of SBC_OPT_FUSED_STEP (the largest inputs, and calls
 # that create their contexts themselves)
-DEFAULT_ONLY = ("test_config5b", "test_config5a", "test_more_wide_tensors", "test_tensor_of_several_scan_tiles", "test_config2_companion", "test_tensor_of_many_chunks", "test_unaligned_views",
+DEFAULT_ONLY = ("test_config5b", "test_compact_context", "test_config5a", "test_more_wide_tensors", "test_tensor_of_several_scan_tiles", "test_config2_companion", "test_tensor_of_many_chunks", "test_unaligned_views",
                 "test_inspection_requires", "test_same_input_twice")
 
 
@@ -322,7 +322,7 @@ def test_config5b_flat_1p5e9_properties():
         dW[off:off + len(chunk)].copy_(torch.from_numpy(chunk))
     print("generated", flush=True)
     R = torch.zeros(n, dtype=torch.float32, device="cuda:0")
-    ctx = sbc.sbc_create(0, n, 1)
+    ctx = sbc.sbc_create_compact(0, n, 1)                    # 5 bytes of scratch per entry instead of 17
     try:
         bound = sbc.sbc_msg_bound([n], p)
         msg = torch.zeros(bound, dtype=torch.uint8, device="cuda:0")
@@ -593,6 +593,48 @@ def test_tensor_of_several_scan_tiles():
         dWs[0][8192 * 1000: 8192 * 5200] = 0.0
         res = check_round(run, dWs, [np.zeros(n, np.float32) for n in sizes], 0.001)
         assert res[0].k > 6144 and res[1].k > 6144
+
+
+def test_compact_context():
+    """A context whose candidate lists hold a few times k entries instead of every entry: same
+    results on ordinary data (also when carried keys let a flood pass that overflows the lists
+    and sends the tensors through the histogram route), SBC_ECAPACITY before anything runs when p
+    needs longer lists than the context has, and after the fact for data whose threshold value is
+    shared by more entries than a list holds."""
+    sizes = synth.numels(synth.resnet50_shapes())
+    with DeviceRun(sizes, compact=True) as run:
+        R = [np.zeros(n, np.float32) for n in sizes]
+        for r in range(3):
+            res = check_round(run, synth.resnet50_update(round_=r), R, 0.001, check_decode=(r == 0))
+            R = [x.R_new for x in res]
+        with pytest.raises(sbc.SbcError) as e:              # p = 0.2: the lists would need 1.6 entries per entry
+            run.compress(synth.resnet50_update(round_=3), 0.2)
+        assert e.value.code == sbc.SBC_ECAPACITY
+    sizes = [300000, 64, 20000, 8193, 1]
+    scales = [1.0, 1.0, 3000.0, 1.0, 1.0]                    # a jump in scale floods the lists behind carried keys
+    with DeviceRun(sizes, compact=True) as run:
+        R = [np.zeros(n, np.float32) for n in sizes]
+        routes = []
+        for r, sc in enumerate(scales):
+            dWs = [(d * np.float32(sc)).astype(np.float32) for d in synth.small_model_update(sizes, round_=r)]
+            res = check_round(run, dWs, R, 0.001)
+            routes.append(main_route(run.ctx))
+            R = [x.R_new for x in res]
+        print("routes", routes)
+        # (300000 entries: the lists hold 75000 per side; a flood beyond that is redone through the histogram route)
+        assert routes[2] & sbc.SBC_ROUTE_HISTOGRAM and routes[2] & sbc.SBC_ROUTE_CARRIED_KEYS
+    # a constant tensor: every entry equals the k-th, no list of a quarter of the entries holds them
+    sizes = [200000, 3000]
+    with DeviceRun(sizes, compact=True) as run:
+        dWs = [np.full(200000, 0.5, np.float32), synth.gaussian_update(3000, tensor=1)]
+        with pytest.raises(sbc.SbcError) as e:
+            run.compress(dWs, 0.001)
+        assert e.value.code == sbc.SBC_ECAPACITY
+        # the context is usable afterwards
+        for x in run.R:
+            x.zero_()
+        dWs = [synth.gaussian_update(n, tensor=i) for i, n in enumerate(sizes)]
+        check_round(run, dWs, [np.zeros(n, np.float32) for n in sizes], 0.001)
 
 
 def test_deferred_decode_status():
