@@ -173,7 +173,9 @@ int sbc_compress_end(sbc_ctx* ctx, size_t* msg_bytes);
  * out[t]       device, read/write, numel[t] floats
  * Errors: SBC_EINVAL, SBC_ECAPACITY, SBC_EHIP; SBC_ECORRUPT if the message fails
  * validation: no write outside out_t[0..numel_t) ever happens, but accumulators may have
- * received part of the message. */
+ * received part of the message.
+ * Completion: as for sbc_compress, the call returns when the status is known; out is complete
+ * for everything enqueued on hip_stream afterwards. */
 int sbc_decompress_accumulate(sbc_ctx* ctx, void* hip_stream,
                               const void* msg, size_t msg_bytes,
                               const int64_t* numel, int n_tensors, double p,

@@ -42,13 +42,16 @@ __global__ __launch_bounds__(256) void k_zero_words(uint32_t* __restrict__ p, ui
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0u;
 }
 
-// The result block of a call, copied to pinned host memory (one small dispatch; the runtime's own
-// device-to-host copy of 16 bytes takes longer).
-__global__ void k_publish(ResultBlock* __restrict__ host_dst, const ResultBlock* __restrict__ src) {
+// The result block of a server call, copied to pinned host memory by a dispatch of its own behind
+// the decode kernels (the runtime's own device-to-host copy of 16 bytes and its wait for the
+// stream take longer); the sequence number goes out last, so that a host that looks for it finds
+// the status in place.
+__global__ void k_publish(ResultBlock* __restrict__ host_dst, const ResultBlock* __restrict__ src, uint32_t seq) {
     if (threadIdx.x == 0) {
         host_dst->msg_bytes = src->msg_bytes;
-        host_dst->pad = src->pad;
         host_dst->err = src->err;
+        __threadfence_system();
+        __hip_atomic_store(&host_dst->pad, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }
 

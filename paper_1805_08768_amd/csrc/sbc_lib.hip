@@ -107,6 +107,8 @@ struct sbc_ctx {
     ResultBlock* h_result = nullptr;      // compress
     uint32_t result_seq = 0;              // number of the latest launch of the message-assembly kernel
     ResultBlock* h_result_dec = nullptr;  // decode (its own block: a decode call may come between begin and end)
+    ResultBlock* h_result_dec_dev = nullptr;
+    uint32_t dec_seq = 0;
     DecDesc* h_dec = nullptr;
     uint2* h_dec_blocks = nullptr;
     uint32_t n_dec_blocks = 0;
@@ -376,21 +378,22 @@ int enqueue_result_copy(sbc_ctx* c) {
     return SBC_OK;
 }
 
+// Looks for sequence number `want` in a result block in pinned host memory for up to 0.3 ms.
+bool result_arrived(const ResultBlock* block, uint32_t want) {
+    const auto t0 = std::chrono::steady_clock::now();
+    for (int spin = 0;; ++spin) {
+        if (__atomic_load_n(&block->pad, __ATOMIC_ACQUIRE) == want) return true;
+        if ((spin & 63) == 63 && std::chrono::steady_clock::now() - t0 > std::chrono::microseconds(300)) return false;
+    }
+}
+
 int wait_result(sbc_ctx* c) {
     // The message-assembly kernel writes the result block to pinned host memory and its sequence
     // number last.  Looking for the number takes a microsecond or two once it is there, where the
     // runtime's wait returns several microseconds after the stream has drained; calls that run
     // longer than a fraction of a millisecond fall through to the runtime's wait.  (Not while
     // kernels carry timing events: those are read right after this, and must be complete.)
-    if (c->profile_level == 0) {
-        const uint32_t want = c->result_seq;
-        const auto t0 = std::chrono::steady_clock::now();
-        for (int spin = 0;; ++spin) {
-            if (__atomic_load_n(&c->h_result->pad, __ATOMIC_ACQUIRE) == want) return SBC_OK;
-            if ((spin & 63) == 63 &&
-                std::chrono::steady_clock::now() - t0 > std::chrono::microseconds(300)) break;
-        }
-    }
+    if (c->profile_level == 0 && result_arrived(c->h_result, c->result_seq)) return SBC_OK;
     if ((c->pend.wait_on_event ? hipEventSynchronize(c->ev_result) : hipStreamSynchronize(c->pend.stream)) != hipSuccess) {
         (void)hipGetLastError();
         return SBC_EHIP;
@@ -598,6 +601,8 @@ static int create_context(sbc_ctx** out, int device, int64_t max_total_elems, in
     // (a pinned block may come back from an earlier context with that context's sequence number in it)
     if (ok) std::memset(c->h_result, 0, sizeof(ResultBlock));
     ok = ok && host_alloc(&c->h_result_dec, 1) == hipSuccess;
+    ok = ok && hipHostGetDevicePointer(reinterpret_cast<void**>(&c->h_result_dec_dev), c->h_result_dec, 0) == hipSuccess;
+    if (ok) std::memset(c->h_result_dec, 0, sizeof(ResultBlock));
     ok = ok && host_alloc(&c->h_dec, T) == hipSuccess;
     ok = ok && host_alloc(&c->h_state, T) == hipSuccess;
     if (ok) {
@@ -1162,8 +1167,12 @@ int sbc_decompress_accumulate(sbc_ctx* c, void* hip_stream, const void* msg, siz
         c->dev_dec_valid = true;
         return SBC_OK;
     }
-    if (hipMemcpyAsync(c->h_result_dec, res_dec, sizeof(ResultBlock), hipMemcpyDeviceToHost, stream) != hipSuccess ||
-        hipStreamSynchronize(stream) != hipSuccess) {
+    // the status goes to pinned host memory by a small dispatch, and the call looks for it there (as
+    // the client step does): it returns when the status is known; `out` is complete for everything
+    // enqueued on the stream afterwards
+    hipLaunchKernelGGL(k_publish, dim3(1), dim3(64), 0, stream, c->h_result_dec_dev, res_dec, ++c->dec_seq);
+    if (hipGetLastError() != hipSuccess) return SBC_EHIP;
+    if (!result_arrived(c->h_result_dec, c->dec_seq) && hipStreamSynchronize(stream) != hipSuccess) {
         (void)hipGetLastError();
         return SBC_EHIP;
     }
