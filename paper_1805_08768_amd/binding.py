@@ -135,6 +135,9 @@ def _i64_array(values: Sequence[int]):
     return (ctypes.c_int64 * len(values))(*[int(v) for v in values])
 
 
+_NUMEL_KEYS: dict = {}
+
+
 class TensorList:
     """A list of contiguous fp32 device tensors marshalled once into the pointer and size arrays
     the C ABI takes.  Keeps the tensors alive.  Pass it instead of a plain list when the same
@@ -145,7 +148,9 @@ class TensorList:
         self.tensors = list(tensors)
         self.ptrs = _ptr_array(self.tensors, torch.float32)
         self.numel = [t.numel() for t in self.tensors]
-        self.numel_key = tuple(self.numel)
+        # (lists of the same sizes share one key object, so that comparing two lists is one pointer test)
+        key = tuple(self.numel)
+        self.numel_key = _NUMEL_KEYS.setdefault(key, key)
         self.numel_arr = _i64_array(self.numel)
 
     def __len__(self):
@@ -231,7 +236,7 @@ def sbc_compress(ctx, dW, residual, p: float,
     returns the message size in bytes.  `residual` is updated in place, `msg` (uint8 device
     tensor) receives the message."""
     dW, residual, msg = _as_list(dW), _as_list(residual), _as_msg(msg)
-    if dW.numel_key != residual.numel_key:
+    if dW.numel_key is not residual.numel_key and dW.numel_key != residual.numel_key:
         raise ValueError("dW and residual must list tensors of the same sizes")
     out_bytes = ctypes.c_size_t(0)
     rc = load().sbc_compress(ctx, _stream_handle(stream), dW.ptrs, residual.ptrs, dW.numel_arr, len(dW.tensors),
@@ -245,7 +250,7 @@ def sbc_compress_begin(ctx, dW, residual, p: float, msg: torch.Tensor, stream=No
     """Enqueues the client step without waiting; sbc_compress_end(ctx) completes it.  The tensors
     and `msg` must stay alive and untouched until then."""
     dW, residual, msg = _as_list(dW), _as_list(residual), _as_msg(msg)
-    if dW.numel_key != residual.numel_key:
+    if dW.numel_key is not residual.numel_key and dW.numel_key != residual.numel_key:
         raise ValueError("dW and residual must list tensors of the same sizes")
     rc = load().sbc_compress_begin(ctx, _stream_handle(stream), dW.ptrs, residual.ptrs, dW.numel_arr,
                                    len(dW.tensors), p, msg.ptr, msg.capacity)

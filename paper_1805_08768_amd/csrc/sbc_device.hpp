@@ -378,18 +378,19 @@ struct RunCounter {
 // must call it.
 // Same for a wide digit: hist[s][0..NB-1], PER = NB/NT consecutive bins per thread.  If rank2
 // is given, the same scan also finds the digit at which the count from the top reaches
-// rank2[s] (digit2[s]; 0xFFFFFFFF if the total is smaller); res2: two more words of LDS.
+// rank2[s] (digit2[s]; 0xFFFFFFFF if the total is smaller) if want2 is set; res2: two more words
+// of LDS.  (Values and references, no pointers to the caller's arrays: those would live in memory.)
 template <int NB, int NT>
 __device__ __forceinline__ void pick_wide_both(const uint32_t (*hist)[NB], uint32_t (&need)[2],
                                                const bool (&active)[2], uint32_t* res,
                                                unsigned long long* scratch, uint32_t (&digit)[2], bool (&found)[2],
-                                               const uint32_t* rank2 = nullptr, uint32_t* res2 = nullptr,
-                                               uint32_t* digit2 = nullptr) {
+                                               bool want2, const uint32_t (&rank2)[2], uint32_t* res2,
+                                               uint32_t (&digit2)[2]) {
     constexpr int PER = NB / NT;
     static_assert(PER >= 1 && PER * NT == NB, "bins divide evenly over the threads");
     const int t = threadIdx.x;
     if (t < 8) res[t] = (t & 3) == 0 ? 0xFFFFFFFFu : 0u;       // res[4*s + {0: digit, 1: above}]
-    if (rank2 && t < 2) res2[t] = 0xFFFFFFFFu;
+    if (want2 && t < 2) res2[t] = 0xFFFFFFFFu;
     uint32_t h[2][PER], loc0 = 0u, loc1 = 0u;
 #pragma unroll
     for (int j = 0; j < PER; ++j) {                            // walking from the top digit down
@@ -408,7 +409,7 @@ __device__ __forceinline__ void pick_wide_both(const uint32_t (*hist)[NB], uint3
             if (active[s] && cum[s] < need[s] && need[s] <= cum[s] + h[s][j]) {
                 res[4 * s] = (uint32_t)(NB - 1 - (t * PER + j)); res[4 * s + 1] = cum[s];
             }
-            if (rank2 && active[s] && cum[s] < rank2[s] && rank2[s] <= cum[s] + h[s][j])
+            if (want2 && active[s] && cum[s] < rank2[s] && rank2[s] <= cum[s] + h[s][j])
                 res2[s] = (uint32_t)(NB - 1 - (t * PER + j));
             cum[s] += h[s][j];
         }
@@ -419,8 +420,17 @@ __device__ __forceinline__ void pick_wide_both(const uint32_t (*hist)[NB], uint3
         digit[s] = res[4 * s];
         found[s] = active[s] && digit[s] != 0xFFFFFFFFu;
         if (found[s]) need[s] -= res[4 * s + 1];
-        if (rank2) digit2[s] = res2[s];
+        if (want2) digit2[s] = res2[s];
     }
+}
+
+template <int NB, int NT>
+__device__ __forceinline__ void pick_wide_both(const uint32_t (*hist)[NB], uint32_t (&need)[2],
+                                               const bool (&active)[2], uint32_t* res,
+                                               unsigned long long* scratch, uint32_t (&digit)[2], bool (&found)[2]) {
+    const uint32_t no_rank[2] = {0u, 0u};
+    uint32_t no_digit[2];
+    pick_wide_both<NB, NT>(hist, need, active, res, scratch, digit, found, false, no_rank, res, no_digit);
 }
 
 struct BytePick {

@@ -321,7 +321,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     uint32_t digit2[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};
     if (pick) {
         pick_wide_both<kWindow, kSelThreads>(sh.whist, need, both, sh.res[0], sh.scratch64, digit, found,
-                                             carry ? rank2 : nullptr, sh.res[1], digit2);
+                                             carry != 0, rank2, sh.res[1], digit2);
         // entries in each side's threshold bucket (same leading key bits as the k-th entry)
 #pragma unroll
         for (int s = 0; s < 2; ++s) bsize[s] = found[s] ? sh.whist[s][digit[s]] : 0u;
@@ -508,7 +508,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     const double Sp = Ssum[0], Sn = Ssum[1];
     // Alg. 2 compares the means (sums that differ may still give equal means: the positive side then)
     const int chosen = (Sp / (double)kc[0] >= Sn / (double)kc[1]) ? 0 : 1;
-    const uint32_t kk = kc[chosen];                   // entries this tensor sends
+    const uint32_t kk = chosen ? kc[1] : kc[0];       // entries this tensor sends
     const float mu32 = (float)((chosen ? Sn : Sp) / (double)kk);
     const float mu_signed = chosen ? -mu32 : mu32;
     if (tid == 0) {

@@ -148,8 +148,7 @@ __global__ __launch_bounds__(kSelThreads) void k_wide_pick(
     const uint32_t r_next = carried_rank(kc[0] > kc[1] ? kc[0] : kc[1]);
     const uint32_t rank2[2] = {r_next, r_next};
     uint32_t digit2[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};
-    pick_wide_both<kWindow, kSelThreads>(hist, need, both, res, scratch64, digit, found, pass == 0 ? rank2 : nullptr, res2,
-                                         digit2);
+    pick_wide_both<kWindow, kSelThreads>(hist, need, both, res, scratch64, digit, found, pass == 0, rank2, res2, digit2);
     if (tid == 0) {
         bool ok = found[0] && found[1];
         if (pass == 0) {
