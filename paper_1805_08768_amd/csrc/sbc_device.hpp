@@ -78,6 +78,20 @@ constexpr uint32_t kErrLoose = 16u;      // not an error: a carried-over filter 
 constexpr uint32_t kErrDeferred = 64u;   // not an error: a tensor the streaming kernel could not finish itself is left to k_select
 
 // TensorDesc::flags
+constexpr int kWindow = 2048;             // bins of the leading-bits histograms (k_select, grid-wide selection)
+// Grid-wide selection, first histogram: the leading 19 key bits (1024 steps per octave) counted in a window of two octaves
+// above the filter key.  Wider than k_select's half octave on purpose: a filter key carried over
+// from the previous call may lie far below this call's k-th entry while the data still grows, and
+// a tensor whose k-th entry lies beyond the window falls to one workgroup.
+constexpr int kWideShift = 13;
+
+// The window bin of a side key, given the side's filter key.
+__device__ __forceinline__ uint32_t wide_window_bin(uint32_t key, uint32_t lo_key) {
+    const uint32_t v = key >> kWideShift, base = lo_key >> kWideShift;
+    const uint32_t o = v >= base ? v - base : 0u;       // (no candidate lies below its filter key)
+    return o < (uint32_t)(kWindow - 1) ? o : (uint32_t)(kWindow - 1);
+}
+
 constexpr uint32_t kDescFused = 1u;      // sorted and encoded inside the select kernel
 constexpr uint32_t kDescWide = 2u;       // keeps so many entries that the grid-wide selection kernels take it
 constexpr uint32_t kDescSampled = 4u;    // subsampled variant: the sampled threshold decides what is kept

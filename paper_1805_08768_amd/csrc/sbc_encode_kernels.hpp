@@ -7,6 +7,8 @@
 //                     total bit length
 //   k_pack          : per chunk, writes q ones, a zero and the b-bit remainder of every
 //                     kept entry at its bit offset in the tensor's staging words
+//                     (SELF: for tensors of few chunks it also does the scan's work for its own
+//                     chunk, from the summaries of the chunks before it, and no scan is launched)
 // (the message is then assembled by k_finish_message)
 #pragma once
 
@@ -198,12 +200,50 @@ __global__ __launch_bounds__(kScanThreads) void k_tensor_scan(const TensorDesc* 
     if (tid == 0 && blockIdx.y == n_tiles - 1u) { st[t].bit_len = carry_bits + tile_bits; st[t].nnz = carry_cnt + tile_cnt; }
 }
 
-template <int B>
+// Most chunks a tensor may have for the workgroups of k_pack to do the scan's work themselves
+// (each reads the summaries of all chunks before its own: two per thread).
+constexpr uint32_t kSelfScanChunks = 2 * kChunkWords;
+
+// What precedes chunk cc of a tensor, from the summaries of its chunks 0 .. cc-1: position + 1 of
+// the last kept entry before the chunk (0: none), the code bits and the kept entries before it.
+// Contains barriers; every thread of the workgroup must call it.
+__device__ __forceinline__ void scan_before_chunk(const TensorDesc& d, uint32_t cc, const ChunkSummary* __restrict__ sum,
+                                                  int b, uint32_t* scratch32, unsigned long long* scratch64,
+                                                  uint32_t& prev_end, unsigned long long& bit_off, uint32_t& cnt_before) {
+    const int w = threadIdx.x;
+    ChunkSummary s[2];
+    uint32_t gend[2], my_end = 0u, my_cnt = 0u;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const uint32_t i = (uint32_t)w * 2u + (uint32_t)j;
+        s[j].cnt = 0u; s[j].first = 0u; s[j].last_end = 0u; s[j].inner_bits = 0u;
+        if (i < cc) s[j] = sum[d.chunk0 + i];
+        gend[j] = s[j].cnt ? i * (uint32_t)kChunk + s[j].last_end : 0u;
+        if (gend[j] > my_end) my_end = gend[j];
+        my_cnt += s[j].cnt;
+    }
+    uint32_t pe = block_excl_max<uint32_t, kChunkWords>(my_end, &prev_end, scratch32);
+    unsigned long long my_bits = 0ull;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        if (s[j].cnt) {
+            const uint32_t pos = ((uint32_t)w * 2u + (uint32_t)j) * (uint32_t)kChunk + s[j].first;
+            my_bits += (unsigned long long)s[j].inner_bits + (unsigned long long)golomb_len(pos - pe, b);
+            pe = gend[j];
+        }
+    }
+    (void)block_excl_sum<unsigned long long, kChunkWords>(my_bits, &bit_off, scratch64);
+    (void)block_excl_sum<uint32_t, kChunkWords>(my_cnt, &cnt_before, scratch32);
+}
+
+template <int B, bool SELF>
 __global__ __launch_bounds__(kChunkWords) void k_pack(
         const TensorDesc* __restrict__ desc, const uint32_t* __restrict__ chunk_tensor,
         const uint32_t* __restrict__ bitmap, const ChunkSummary* __restrict__ sum,
         const uint32_t* __restrict__ chunk_prev_end, const uint64_t* __restrict__ chunk_bitoff,
-        int b, uint32_t* __restrict__ stage, ResultBlock* __restrict__ result, uint32_t n_chunks) {
+        TensorState* __restrict__ st, int b, uint32_t* __restrict__ stage, ResultBlock* __restrict__ result,
+        uint32_t n_chunks) {
+    static_assert(!SELF || B == 1, "a workgroup that scans for itself takes one chunk");
     __shared__ uint32_t scratch32[kChunkWords / 64];
     __shared__ unsigned long long scratch64[kChunkWords / 64];
     const int w = threadIdx.x;
@@ -218,15 +258,25 @@ __global__ __launch_bounds__(kChunkWords) void k_pack(
         tensor[j] = chunk_tensor[cs];
         words[j] = bitmap[(uint64_t)cs * kChunkWords + w];
         chunk_cnt[j] = sum[cs].cnt;
-        prev_end[j] = chunk_prev_end[cs];
-        bit_off[j] = chunk_bitoff[cs];
+        prev_end[j] = SELF ? 0u : chunk_prev_end[cs];
+        bit_off[j] = SELF ? 0ull : chunk_bitoff[cs];
     }
 #pragma unroll
     for (int j = 0; j < B; ++j) {
         const uint32_t c = blockIdx.x * (uint32_t)B + (uint32_t)j;
         if (c >= n_chunks) continue;
         const TensorDesc d = desc[tensor[j]];           // (consecutive chunks mostly share it)
-        if ((d.flags & kDescFused) || chunk_cnt[j] == 0u) continue;    // uniform for the workgroup
+        if (d.flags & kDescFused) continue;             // uniform for the workgroup
+        const bool last_chunk = SELF && c - d.chunk0 == d.nchunks - 1u;
+        uint32_t cnt_before = 0u;
+        if (SELF) {
+            if (chunk_cnt[j] == 0u && !last_chunk) continue;
+            scan_before_chunk(d, c - d.chunk0, sum, b, scratch32, scratch64, prev_end[j], bit_off[j], cnt_before);
+        }
+        if (chunk_cnt[j] == 0u) {
+            if (last_chunk && w == 0) { st[tensor[j]].bit_len = bit_off[j]; st[tensor[j]].nnz = cnt_before; }
+            continue;
+        }
         const uint32_t word = words[j];
         const uint32_t end_w = word ? (uint32_t)(w * 32 + 32 - __clz(word)) : 0u;
         uint32_t last_end;
@@ -245,6 +295,7 @@ __global__ __launch_bounds__(kChunkWords) void k_pack(
         }
         unsigned long long chunk_bits;
         const unsigned long long ex = block_excl_sum<unsigned long long, kChunkWords>(bits, &chunk_bits, scratch64);
+        if (last_chunk && w == 0) { st[tensor[j]].bit_len = bit_off[j] + chunk_bits; st[tensor[j]].nnz = cnt_before + chunk_cnt[j]; }
         unsigned long long pos = bit_off[j] + ex;
         if (word && ((pos + bits + 31ull) >> 5) > d.bound_words) {    // would leave the tensor's staging words
             atomicOr(&result->err, kErrInternal);

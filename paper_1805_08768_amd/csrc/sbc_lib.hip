@@ -35,7 +35,6 @@ const char* const kStageNames[kNumStages] = {
 }  // namespace
 
 constexpr int kDescSlots = 4;             // device copies of the tensor table, keyed by the pointer lists
-constexpr int kMaxWide = 64;              // tensors per call that the grid-wide selection kernels can take
 constexpr int kMaxWideDec = 16;
 constexpr uint32_t kMaxDecExtra = 512;    // additional decode workgroups that share a stream's scatter
 constexpr uint32_t kDecSharePer = 384;    // kept entries per sharing workgroup
@@ -80,9 +79,10 @@ struct sbc_ctx {
     ResultBlock* d_result = nullptr;      // two for compress, two for decode, used in turn; [4] collects the
                                           // errors of decode calls whose status is deferred, [5] is a spare
     // grid-wide selection
-    uint32_t* d_wide_ids = nullptr;
     WideState* d_wide_state = nullptr;
     uint32_t* d_wide_hist = nullptr;
+    uint32_t* d_wide_hist2 = nullptr;
+    uint32_t* d_wide_tie_cnt = nullptr;
     long long* d_wide_acc = nullptr;
     uint32_t* d_wide_tie = nullptr;
 
@@ -120,6 +120,7 @@ struct sbc_ctx {
     std::vector<int64_t> cache_numel;
     uint64_t cache_total = 0, cache_chunks = 0, cache_stage_words = 0, cache_kept_total = 0, cache_max_bound = 0;
     uint32_t cache_scan_tiles = 1;        // most tiles of the chunk scan among the tensors encoded from the bitmap
+    uint32_t cache_bitmap_chunks_max = 0; // most chunks among those tensors
     bool cache_any_bitmap = false;
     bool cache_all_inline = false;        // every tensor is finished inside the streaming kernel
     int cache_force_exact = 0;
@@ -182,7 +183,7 @@ struct sbc_ctx {
         uint8_t* msg8 = nullptr;
         size_t msg_capacity = 0, need = 0;
         uint32_t n_chunks = 0;
-        unsigned gather_y = 1, scan_tiles = 1;
+        unsigned gather_y = 1, scan_tiles = 1, bitmap_chunks_max = 0;
     } pend;
 
     // last compress call, for the inspection entry points
@@ -248,8 +249,8 @@ void free_all(sbc_ctx* c) {
     (void)hipFree(c->d_dec_wide); (void)hipFree(c->d_seg_fn); (void)hipFree(c->d_seg_pack); (void)hipFree(c->d_tile_fn);
     (void)hipFree(c->d_tile_sum); (void)hipFree(c->d_tile_entry);
     if (c->h_dec_wide) (void)hipHostFree(c->h_dec_wide);
-    (void)hipFree(c->d_wide_ids); (void)hipFree(c->d_wide_state); (void)hipFree(c->d_wide_hist);
-    (void)hipFree(c->d_wide_acc); (void)hipFree(c->d_wide_tie);
+    (void)hipFree(c->d_wide_state); (void)hipFree(c->d_wide_hist);
+    (void)hipFree(c->d_wide_acc); (void)hipFree(c->d_wide_tie); (void)hipFree(c->d_wide_hist2); (void)hipFree(c->d_wide_tie_cnt);
     if (c->h_wide_ids) (void)hipHostFree(c->h_wide_ids);
     if (c->h_desc) (void)hipHostFree(c->h_desc);
     if (c->h_chunk_tensor) (void)hipHostFree(c->h_chunk_tensor);
@@ -296,7 +297,14 @@ void launch_encode_and_gather(sbc_ctx* c, bool profile) {
     hipStream_t stream = P.stream;
     bool* timed = P.timed;
     const int T = P.T, b = P.b;
-    if (P.any_bitmap) {
+    if (P.any_bitmap && P.bitmap_chunks_max <= kSelfScanChunks && P.n_chunks <= 8192u) {
+        // no tensor of many chunks among those encoded from the bitmap: the workgroups that write
+        // the codes scan the few summaries before their chunk themselves, one launch less
+        SBC_LAUNCH(kStChunkSummary, profile, k_chunk_summary<1>, dim3(P.n_chunks), dim3(kChunkWords), P.d_desc,
+                   c->d_chunk_tensor, c->d_bitmap, c->d_sum, b, P.n_chunks);
+        SBC_LAUNCH(kStPack, profile, (k_pack<1, true>), dim3(P.n_chunks), dim3(kChunkWords), P.d_desc, c->d_chunk_tensor,
+                   c->d_bitmap, c->d_sum, c->d_prev_end, c->d_bitoff, c->d_state, b, c->d_stage, P.res_now, P.n_chunks);
+    } else if (P.any_bitmap) {
         // (with very many chunks a workgroup takes four of them: see the kernels)
         const bool batch = P.n_chunks > 8192u;
         const dim3 per_chunk(batch ? (P.n_chunks + 3u) / 4u : P.n_chunks);
@@ -313,11 +321,11 @@ void launch_encode_and_gather(sbc_ctx* c, bool profile) {
         SBC_LAUNCH(kStTensorScan, profile, k_tensor_scan, dim3(T, P.scan_tiles), dim3(kScanThreads), P.d_desc, c->d_sum,
                    c->d_tile, c->d_prev_end, c->d_bitoff, c->d_state, b);
         if (batch) {
-            SBC_LAUNCH(kStPack, profile, k_pack<4>, per_chunk, dim3(kChunkWords), P.d_desc, c->d_chunk_tensor,
-                       c->d_bitmap, c->d_sum, c->d_prev_end, c->d_bitoff, b, c->d_stage, P.res_now, P.n_chunks);
+            SBC_LAUNCH(kStPack, profile, (k_pack<4, false>), per_chunk, dim3(kChunkWords), P.d_desc, c->d_chunk_tensor,
+                       c->d_bitmap, c->d_sum, c->d_prev_end, c->d_bitoff, c->d_state, b, c->d_stage, P.res_now, P.n_chunks);
         } else {
-            SBC_LAUNCH(kStPack, profile, k_pack<1>, per_chunk, dim3(kChunkWords), P.d_desc, c->d_chunk_tensor,
-                       c->d_bitmap, c->d_sum, c->d_prev_end, c->d_bitoff, b, c->d_stage, P.res_now, P.n_chunks);
+            SBC_LAUNCH(kStPack, profile, (k_pack<1, false>), per_chunk, dim3(kChunkWords), P.d_desc, c->d_chunk_tensor,
+                       c->d_bitmap, c->d_sum, c->d_prev_end, c->d_bitoff, c->d_state, b, c->d_stage, P.res_now, P.n_chunks);
         }
     }
     SBC_LAUNCH(kStGather, profile, k_finish_message, dim3(T, P.gather_y), dim3(256), P.d_desc, c->d_state, T, b,
@@ -327,40 +335,39 @@ void launch_encode_and_gather(sbc_ctx* c, bool profile) {
 
 // Alg. 2 for the pending step's tensors that keep very many entries, as grid-wide sweeps over
 // their candidate lists with one-workgroup steps in between (the tensors k_select then skips).
-void launch_wide_selection(sbc_ctx* c) {
+void launch_wide_selection(sbc_ctx* c, bool handback) {
     sbc_ctx::Pending& P = c->pend;
     const int lvl = c->profile_level;
     hipStream_t stream = P.stream;
     bool* timed = P.timed;
     TensorDesc* const d_desc = P.d_desc;
     ResultBlock* const res_now = P.res_now;
-    const dim3 sweep(c->wide_blocks, (unsigned)c->n_wide), one((unsigned)c->n_wide);
+    // (the sweeps that carry the second histogram have four times the threads per workgroup)
+    const dim3 sweep(c->wide_blocks, (unsigned)c->n_wide), sweep4(std::max(16u, c->wide_blocks / 4u), (unsigned)c->n_wide);
     const bool time_wide = lvl >= 2;
-    for (int pass = 0; pass < 3; ++pass) {
-        if (pass == 0 && time_wide) {
-            hipExtLaunchKernelGGL(k_wide_count, sweep, dim3(kWideThreads), 0, stream, c->ev[2 * kStWide], nullptr, 0,
-                                  d_desc, c->d_wide_ids, c->d_state, c->d_cand, c->d_wide_state, c->d_wide_hist, pass);
-        } else {
-            hipLaunchKernelGGL(k_wide_count, sweep, dim3(kWideThreads), 0, stream, d_desc, c->d_wide_ids, c->d_state,
-                               c->d_cand, c->d_wide_state, c->d_wide_hist, pass);
-        }
-        hipLaunchKernelGGL(k_wide_pick, one, dim3(kSelThreads), 0, stream, d_desc, c->d_wide_ids, c->d_state,
-                           c->d_wide_state, c->d_wide_hist, pass);
+    WideIds ids = {};
+    std::memcpy(ids.id, c->h_wide_ids, sizeof(uint32_t) * (size_t)c->n_wide);
+    if (time_wide) {
+        hipExtLaunchKernelGGL(k_wide_count, sweep, dim3(kWideThreads), 0, stream, c->ev[2 * kStWide], nullptr, 0,
+                              d_desc, ids, c->d_state, c->d_cand, c->d_wide_hist);
+    } else {
+        hipLaunchKernelGGL(k_wide_count, sweep, dim3(kWideThreads), 0, stream, d_desc, ids, c->d_state,
+                           c->d_cand, c->d_wide_hist);
     }
-    hipLaunchKernelGGL(k_wide_ties, sweep, dim3(kWideThreads), 0, stream, d_desc, c->d_wide_ids, c->d_state,
-                       c->d_cand, c->d_wide_state, c->d_wide_tie);
-    hipLaunchKernelGGL(k_wide_rank, one, dim3(kSelThreads), 0, stream, c->d_wide_ids, c->d_wide_state, c->d_wide_tie);
-    hipLaunchKernelGGL(k_wide_sums, sweep, dim3(kWideThreads), 0, stream, d_desc, c->d_wide_ids, c->d_state,
-                       c->d_cand, c->d_wide_state, c->d_wide_acc);
-    hipLaunchKernelGGL(k_wide_decide, one, dim3(128), 0, stream, d_desc, c->d_wide_ids, c->d_state,
-                       c->d_wide_state, c->d_wide_acc, res_now);
+    hipLaunchKernelGGL(k_wide_refine, sweep4, dim3(kWideSweepThreads), 0, stream, d_desc, ids, c->d_state,
+                       c->d_cand, c->d_wide_state, c->d_wide_hist, c->d_wide_hist2, c->d_wide_acc, c->d_wide_tie_cnt);
+    hipLaunchKernelGGL(k_wide_sums, sweep4, dim3(kWideSweepThreads), 0, stream, d_desc, ids, c->d_state,
+                       c->d_cand, c->d_wide_state, c->d_wide_hist, c->d_wide_hist2, c->d_wide_acc, c->d_wide_tie,
+                       c->d_wide_tie_cnt);
     if (time_wide) {
         hipExtLaunchKernelGGL(k_wide_apply, sweep, dim3(kWideThreads), 0, stream, nullptr, c->ev[2 * kStWide + 1], 0,
-                              d_desc, c->d_wide_ids, c->d_state, c->d_cand, c->d_wide_state, c->d_bitmap, res_now);
+                              d_desc, ids, c->d_state, c->d_cand, c->d_wide_state, c->d_wide_hist2, c->d_wide_acc,
+                              c->d_wide_tie, c->d_wide_tie_cnt, c->d_bitmap, handback ? 1 : 0, res_now);
         timed[kStWide] = true;
     } else {
-        hipLaunchKernelGGL(k_wide_apply, sweep, dim3(kWideThreads), 0, stream, d_desc, c->d_wide_ids, c->d_state,
-                           c->d_cand, c->d_wide_state, c->d_bitmap, res_now);
+        hipLaunchKernelGGL(k_wide_apply, sweep, dim3(kWideThreads), 0, stream, d_desc, ids, c->d_state,
+                           c->d_cand, c->d_wide_state, c->d_wide_hist2, c->d_wide_acc, c->d_wide_tie, c->d_wide_tie_cnt,
+                           c->d_bitmap, handback ? 1 : 0, res_now);
     }
 }
 
@@ -584,14 +591,16 @@ static int create_context(sbc_ctx** out, int device, int64_t max_total_elems, in
     ok = ok && dev_alloc(&c->d_tile_fn, (size_t)c->dec_tile_cap) == hipSuccess;
     ok = ok && dev_alloc(&c->d_tile_sum, (size_t)c->dec_tile_cap) == hipSuccess;
     ok = ok && dev_alloc(&c->d_tile_entry, (size_t)c->dec_tile_cap) == hipSuccess;
-    ok = ok && dev_alloc(&c->d_wide_ids, (size_t)kMaxWide) == hipSuccess;
     ok = ok && dev_alloc(&c->d_wide_state, (size_t)kMaxWide) == hipSuccess;
     ok = ok && dev_alloc(&c->d_wide_hist, (size_t)kMaxWide * 2 * kWindow) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_wide_hist2, (size_t)kMaxWide * 2 * kWideRefine) == hipSuccess;
+    ok = ok && dev_alloc(&c->d_wide_tie_cnt, (size_t)kMaxWide * 2) == hipSuccess;
     ok = ok && dev_alloc(&c->d_wide_acc, (size_t)kMaxWide * 512) == hipSuccess;
     ok = ok && dev_alloc(&c->d_wide_tie, (size_t)kMaxWide * 2 * kWideTieMax) == hipSuccess;
     ok = ok && host_alloc(&c->h_wide_ids, (size_t)kMaxWide) == hipSuccess;
     // the histograms and accumulators start out zero; the kernels that read them leave them zero
     ok = ok && hipMemset(c->d_wide_hist, 0, sizeof(uint32_t) * kMaxWide * 2 * kWindow) == hipSuccess;
+    ok = ok && hipMemset(c->d_wide_hist2, 0, sizeof(uint32_t) * kMaxWide * 2 * kWideRefine) == hipSuccess;
     ok = ok && hipMemset(c->d_wide_acc, 0, sizeof(long long) * kMaxWide * 512) == hipSuccess;
     ok = ok && host_alloc(&c->h_desc, T) == hipSuccess;
     ok = ok && host_alloc(&c->h_chunk_tensor, (size_t)c->max_chunks) == hipSuccess;
@@ -702,11 +711,14 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
     // that alternates between a few sets of buffers uploads nothing in the steady state.
     uint64_t total = 0, chunks = 0, stage_words = 0, kept_total = 0, max_bound = 0, groups = 0, cand_total = 0;
     bool any_bitmap = false, all_inline = true;
-    uint32_t scan_tiles = 1;
+    uint32_t scan_tiles = 1, bitmap_chunks_max = 0;
     // in the subsampled variant the keys must come from this call's sample
     const bool sampled = c->sampled != 0;
     const int force_exact = sampled ? 0 : c->force_exact;
-    bool use_history = !sampled && c->hist_valid && !force_exact && c->hist_p == p && c->hist_n.size() == (size_t)T;
+    bool use_history = !sampled && c->hist_valid && !force_exact && !c->result_dirty && c->hist_p == p &&
+                       c->hist_n.size() == (size_t)T;
+    if (use_history)
+        for (int t = 0; t < T; ++t) if ((int64_t)c->hist_n[t] != numel[t]) { use_history = false; break; }
     const bool sizes_same = c->cache_valid && c->cache_T == T && c->cache_p == p && c->cache_force_exact == force_exact &&
                             std::memcmp(c->cache_numel.data(), numel, sizeof(int64_t) * T) == 0;
     auto pointers_ok = [&](int t) -> bool {
@@ -720,10 +732,8 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
     if (sizes_same) {
         total = c->cache_total; chunks = c->cache_chunks; stage_words = c->cache_stage_words;
         kept_total = c->cache_kept_total; max_bound = c->cache_max_bound; any_bitmap = c->cache_any_bitmap;
-        scan_tiles = c->cache_scan_tiles;
+        scan_tiles = c->cache_scan_tiles; bitmap_chunks_max = c->cache_bitmap_chunks_max;
         all_inline = c->cache_all_inline;
-        if (use_history)
-            for (int t = 0; t < T; ++t) if (c->hist_n[t] != c->plan[t].n) { use_history = false; break; }
         for (int i = 0; i < kDescSlots; ++i) {
             const DescSlot& sl = c->slot[i];
             if (sl.valid && std::memcmp(sl.dW.data(), dW, sizeof(float*) * T) == 0 &&
@@ -777,12 +787,12 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
             }
             d.kept_off = (uint32_t)kept_total;
             if (fused) kept_total += d.kcap; else any_bitmap = true;
-            if (use_history && c->hist_n[t] != d.n) use_history = false;
             total += (uint64_t)n;
             chunks += d.nchunks;
             stage_words += bw;
             max_bound = std::max<uint64_t>(max_bound, bw);
             if (!fused) scan_tiles = std::max<uint32_t>(scan_tiles, (d.nchunks + kScanTile - 1u) / kScanTile);
+            if (!fused) bitmap_chunks_max = std::max<uint32_t>(bitmap_chunks_max, d.nchunks);
             if (total > (uint64_t)c->max_elems || cand_total > c->cand_entries || chunks > c->max_chunks || kept_total > c->kept_cap ||
                 stage_words > c->stage_cap || groups > c->max_groups)
                 return SBC_ECAPACITY;
@@ -843,8 +853,7 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
             }
             c->n_sched = (uint32_t)w;
         }
-        if ((c->n_wide > 0 && hipMemcpyAsync(c->d_wide_ids, c->h_wide_ids, sizeof(uint32_t) * c->n_wide, hipMemcpyHostToDevice, stream) != hipSuccess) ||
-            hipMemcpyAsync(c->d_order, c->h_order, sizeof(uint32_t) * T, hipMemcpyHostToDevice, stream) != hipSuccess ||
+        if (hipMemcpyAsync(c->d_order, c->h_order, sizeof(uint32_t) * T, hipMemcpyHostToDevice, stream) != hipSuccess ||
             hipMemcpyAsync(c->d_sched, c->h_sched, sizeof(uint2) * c->n_sched, hipMemcpyHostToDevice, stream) != hipSuccess ||
             hipMemcpyAsync(c->d_chunk_tensor, c->h_chunk_tensor, sizeof(uint32_t) * chunks, hipMemcpyHostToDevice, stream) != hipSuccess) {
             (void)hipGetLastError();
@@ -854,7 +863,7 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
         c->cache_T = T; c->cache_p = p;
         c->cache_total = total; c->cache_chunks = chunks; c->cache_stage_words = stage_words;
         c->cache_kept_total = kept_total; c->cache_max_bound = max_bound; c->cache_any_bitmap = any_bitmap;
-        c->cache_scan_tiles = scan_tiles;
+        c->cache_scan_tiles = scan_tiles; c->cache_bitmap_chunks_max = bitmap_chunks_max;
         c->cache_all_inline = all_inline; c->cache_force_exact = force_exact;
         // (cache_valid is set once this call has completed: the uploads above must have happened)
     }
@@ -892,7 +901,9 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
                            (uint64_t)(2 * sizeof(ResultBlock) / 4));
         hipLaunchKernelGGL(k_zero_words, dim3(64), dim3(256), 0, stream, reinterpret_cast<uint32_t*>(c->d_group),
                            (uint64_t)c->max_groups * (sizeof(GroupState) / 4));
-        use_history = false;
+        // (the grid-wide kernels leave their histograms clean only if all of them have run)
+        hipLaunchKernelGGL(k_zero_words, dim3(64), dim3(256), 0, stream, c->d_wide_hist, (uint64_t)kMaxWide * 2 * kWindow);
+        hipLaunchKernelGGL(k_zero_words, dim3(256), dim3(256), 0, stream, c->d_wide_hist2, (uint64_t)kMaxWide * 2 * kWideRefine);
     }
     c->result_dirty = true;                           // until this call has completed normally
     c->hist_valid = false;
@@ -908,7 +919,7 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
     P.all_inline = all_inline;
     for (int st = 0; st < kNumStages; ++st) P.timed[st] = false;
     P.res_now = res_now; P.res_next = res_next; P.d_desc = d_desc; P.msg8 = msg8;
-    P.msg_capacity = msg_capacity; P.need = need; P.n_chunks = n_chunks; P.gather_y = gather_y; P.scan_tiles = scan_tiles;
+    P.msg_capacity = msg_capacity; P.need = need; P.n_chunks = n_chunks; P.gather_y = gather_y; P.scan_tiles = scan_tiles; P.bitmap_chunks_max = bitmap_chunks_max;
     P.wait_on_event = wait_on_event;
     const int lvl = c->profile_level;
     bool* timed = P.timed;
@@ -942,9 +953,14 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
     }
     if (!all_inline) {
         // the tensors the streaming kernel does not finish itself
-        if (c->n_wide > 0) launch_wide_selection(c);
-        SBC_LAUNCH(kStSelect, true, k_select, dim3(T), dim3(kSelThreads), d_desc, c->d_order,
-                   c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 0, carry, res_now);
+        // (if every tensor goes through the grid-wide kernels, k_select has nothing to do unless one of
+        // them is handed back: the last of those kernels then asks for the second pass below)
+        const bool only_wide = c->n_wide == T;
+        if (c->n_wide > 0) launch_wide_selection(c, only_wide);
+        if (!only_wide) {
+            SBC_LAUNCH(kStSelect, true, k_select, dim3(T), dim3(kSelThreads), d_desc, c->d_order,
+                       c->d_state, c->d_cand, c->d_bitmap, c->d_stage, c->d_kept, b, 0, carry, res_now);
+        }
     }
     launch_encode_and_gather(c, true);
     SBC_HOST_TS(2);

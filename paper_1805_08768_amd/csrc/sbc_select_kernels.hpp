@@ -50,7 +50,6 @@ __device__ __forceinline__ void put_ones(uint32_t* words, unsigned long long pos
 }
 
 constexpr uint32_t kSelLds = 8192;                       // candidates per side staged in LDS
-constexpr int kWindow = 2048;                            // bins of the leading-bits histogram
 constexpr int kWinShift = 11;                            // it counts key >> kWinShift: 2^12 steps per octave, half an octave
 constexpr uint32_t kRankMax = 512;                       // threshold buckets up to this size are ranked directly
 static_assert(2 * kFusedMaxK * 4 <= kSelLds * 8, "sort arrays reuse one side's candidate space");
@@ -200,6 +199,39 @@ __device__ __forceinline__ long long exponent_sums(SelectShared& sh, const CandL
     return scaled;
 }
 
+// What a tensor's candidate counts rule out before any selection: true if the tensor cannot be
+// selected from its lists (the thread with `lead` set has then flagged it, for the histogram route
+// or as an error).
+__device__ __forceinline__ bool lists_unusable(const TensorDesc& d, TensorState* __restrict__ st, int t, uint32_t cnt_p,
+                                               uint32_t cnt_n, int pass, bool lead, ResultBlock* __restrict__ result) {
+    const bool sampled = (d.flags & kDescSampled) != 0u;
+    if (cnt_p > d.n || cnt_n > d.n || (sampled && (cnt_p == 0u || cnt_n == 0u))) {
+        // (a sampled threshold is the key of an entry of the tensor, so that entry is a candidate)
+        if (lead) atomicOr(&result->err, kErrInternal);
+        return true;
+    }
+    if (cnt_p > d.cand_cap || cnt_n > d.cand_cap) {
+        // compact context: more candidates than a list holds (nothing was stored beyond its end).  The
+        // histogram route extracts a tighter set; if that does not fit either, the call fails.
+        if (lead) {
+            st[t].flags = kStFailed;
+            st[t].bit_len = 0ull; st[t].nnz = 0u;
+            atomicOr(&result->err, pass == 0 && !sampled ? kErrPrefilter : kErrOverflow);
+        }
+        return true;
+    }
+    if (!sampled && (cnt_p < d.k || cnt_n < d.k)) {
+        // the filter kept too few entries on a side: the histogram path redoes this tensor
+        if (lead) {
+            st[t].flags = kStFailed;
+            st[t].bit_len = 0ull; st[t].nnz = 0u;
+            atomicOr(&result->err, pass == 0 ? kErrPrefilter : kErrInternal);
+        }
+        return true;
+    }
+    return false;
+}
+
 // One workgroup per tensor; `order` lists the tensors by decreasing size so that the
 // long-running workgroups start first.  pass 0: every tensor; pass 1: only tensors handed to
 // the histogram path (kStExact).
@@ -224,30 +256,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
     if (pass == 0 && (st_flags & kStInlineDone)) return;                          // done by the streaming kernel
     const uint32_t k = d.k, n = d.n;
     const bool sampled = (d.flags & kDescSampled) != 0u;
-    if (cnt_p > n || cnt_n > n || (sampled && (cnt_p == 0u || cnt_n == 0u))) {
-        // (a sampled threshold is the key of an entry of the tensor, so that entry is a candidate)
-        if (tid == 0) atomicOr(&result->err, kErrInternal);
-        return;
-    }
-    if (cnt_p > d.cand_cap || cnt_n > d.cand_cap) {
-        // compact context: more candidates than a list holds (nothing was stored beyond its end).  The
-        // histogram route extracts a tighter set; if that does not fit either, the call fails.
-        if (tid == 0) {
-            st[t].flags = kStFailed;
-            st[t].bit_len = 0ull; st[t].nnz = 0u;
-            atomicOr(&result->err, pass == 0 && !sampled ? kErrPrefilter : kErrOverflow);
-        }
-        return;
-    }
-    if (!sampled && (cnt_p < k || cnt_n < k)) {
-        // the filter kept too few entries on a side: the histogram path redoes this tensor
-        if (tid == 0) {
-            st[t].flags = kStFailed;
-            st[t].bit_len = 0ull; st[t].nnz = 0u;
-            atomicOr(&result->err, pass == 0 ? kErrPrefilter : kErrInternal);
-        }
-        return;
-    }
+    if (lists_unusable(d, st, t, cnt_p, cnt_n, pass, tid == 0, result)) return;
     if (tid == 0) { st[t].cand_seen[0] = cnt_p; st[t].cand_seen[1] = cnt_n; }    // (inspection only)
     SBC_TS(1, 1);                                     // descriptor and counts read
     SBC_TS_VAL(1, 13, cnt_p); SBC_TS_VAL(1, 14, cnt_n); SBC_TS_VAL(1, 15, (unsigned)t);

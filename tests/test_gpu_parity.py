@@ -527,6 +527,45 @@ def test_grid_wide_selection():
         check_round(run, dWs, [np.zeros(n, np.float32) for n in sizes], p)
 
 
+def test_grid_wide_selection_four_rounds_at_the_default_threshold():
+    """The 2^20-entry Gaussian tensor of configuration 1 (10485 kept entries: grid-wide kernels at
+    the default threshold) over four rounds with the residual carried, alone (no other selection
+    kernel runs in the call) and with a small tensor beside it."""
+    p = 0.01
+    for sizes in ([1 << 20], [1 << 20, 5000]):
+        with DeviceRun(sizes) as run:
+            R = [np.zeros(n, np.float32) for n in sizes]
+            for r in range(4):
+                dWs = [synth.gaussian_update(n, round_=r, tensor=i) for i, n in enumerate(sizes)]
+                res = check_round(run, dWs, R, p, check_decode=(r in (0, 3)))
+                assert res[0].k == 10485
+                assert sbc.sbc_last_route(run.ctx) & sbc.SBC_ROUTE_WIDE
+                R = [x.R_new for x in res]
+
+
+def test_calls_of_grid_wide_tensors_only_that_need_the_second_pass():
+    """A call whose tensors all take the grid-wide kernels runs no other selection kernel unless one
+    of them cannot be finished there: a misleading sample (too few candidates: histogram route),
+    and tie-heavy data (more equal entries at the threshold than those kernels rank: one workgroup)."""
+    n = 400000
+    x = (np.abs(synth.small_model_update([n], round_=4)[0]) * 1e-3).astype(np.float32)
+    pos = sampled_positions(n, 0)
+    x[pos[::200]] = 5.0                                      # every large entry lies where the sampler looks
+    x[pos[1::200]] = -7.0
+    with DeviceRun([n]) as run:
+        sbc.sbc_set_option(run.ctx, sbc.SBC_OPT_WIDE_MIN_KEPT, 300)
+        check_round(run, [x], [np.zeros(n, np.float32)], 0.001)               # k = 400
+        assert main_route(run.ctx) & sbc.SBC_ROUTE_HISTOGRAM
+    sizes = [200000, 80000]
+    with DeviceRun(sizes) as run:
+        sbc.sbc_set_option(run.ctx, sbc.SBC_OPT_WIDE_MIN_KEPT, 6500)
+        R = [np.zeros(m, np.float32) for m in sizes]
+        for r in range(2):
+            dWs = [synth.palette_update(m, round_=r, tensor=i) for i, m in enumerate(sizes)]
+            res = check_round(run, dWs, R, 0.1)
+            R = [v.R_new for v in res]
+
+
 def test_histogram_fallback_bitmap_and_grid_wide_tensors_in_one_call():
     """One call whose tensors take every route at once: tensor 0 keeps enough entries for the
     grid-wide kernels; tensor 1 keeps too many for the fused encoder and too few for those (one
