@@ -453,6 +453,37 @@ def main() -> int:
         sbc.sbc_destroy(c.ctx)
     torch.cuda.synchronize()
 
+    # untimed extra: Alg. 1's round loop with everything resident in device memory: four clients
+    # (each: its update written into its buffer, sbc_compress), the server's four decodes into the
+    # average, W <- W + dW; per round, with a device synchronisation after each
+    round_loop = None
+    if C == 1 and args.workload == "resnet50" and not args.no_pipelined_extra:
+        from paper_1805_08768_amd import rounds as rounds_mod
+        n_cl = 4
+        ups = []
+        for i in range(n_cl):
+            flat, views = rounds_mod.flat_buffer(sizes, dev)
+            for v, x in zip(views, gen(100 + i)):
+                v.copy_(torch.from_numpy(x))
+            ups.append(flat)
+
+        def on_device_update(client, rnd, W, out_views):
+            out_views.flat.copy_(ups[(client + rnd) % n_cl])
+
+        stamps = []
+
+        def stamp(rnd):
+            torch.cuda.synchronize()
+            stamps.append(time.perf_counter())
+
+        rounds_mod.run_rounds(sizes, P, n_cl, 24, on_device_update, device=dev, on_device=True, on_round_end=stamp)
+        per_round = sorted(b_ - a_ for a_, b_ in zip(stamps[3:-1], stamps[4:]))      # (the first rounds: warm-up)
+        round_loop = {"clients": n_cl, "ms_per_round_median": per_round[len(per_round) // 2] * 1e3,
+                      "ms_per_round_min": per_round[0] * 1e3, "rounds": len(per_round),
+                      "what": "update copied into each client's buffer, 4 x sbc_compress, 4 x sbc_decompress_accumulate, W += average; all in device memory"}
+        del ups
+    torch.cuda.synchronize()
+
     # the GPU part is over: the waiting CPU processes get their work
     cpu = None
     if cpu_pool is not None:
@@ -509,6 +540,7 @@ def main() -> int:
         "cold_cache": cold,
         "pipelined": pipelined,
         "server_average_32": server32,
+        "round_loop": round_loop,
         "copy_kernel_GBs": copy_gbs,
         "message_bytes": msg_bytes / args.steps,
         "routes": {"sampled": sum(v for k, v in routes.items() if not k & 1),

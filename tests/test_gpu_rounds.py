@@ -64,3 +64,29 @@ def test_rounds_match_the_oracle_loop_and_converge():
     d0 = sum(float(np.sum(m.astype(np.float64) ** 2)) for m in mean_t)
     d1 = sum(float(np.sum((w.astype(np.float64) - m) ** 2)) for w, m in zip(W_gpu, mean_t))
     assert d1 < d0
+
+
+def test_rounds_with_everything_resident_on_the_device():
+    """The same loop with the weights, the updates and the averaging in device memory gives the
+    weights of the loop that goes through host memory, bit for bit (that one is compared with the
+    oracle's loop above)."""
+    import torch
+    sizes = [5000, 64, 20000, 8193]
+    p, n_clients, n_rounds = 0.05, 4, 6
+    targets, local_update = _toy_problem(sizes, n_clients)
+    participants = lambda rnd: [i for i in range(n_clients) if i != rnd % n_clients]
+    W_host, up_host = rounds.run_rounds(sizes, p, n_clients, n_rounds, local_update, participants=participants)
+    dev_targets = [[torch.from_numpy(t).cuda() for t in per_client] for per_client in targets]
+
+    def local_update_dev(client, rnd, W, out):
+        for w, t, dst in zip(W, dev_targets[client], out):
+            wi = w.clone()
+            for _ in range(3):
+                wi = wi - 0.25 * (wi - t)            # fp32 throughout, as in the host callback
+            torch.sub(wi, w, out=dst)
+
+    W_dev, up_dev = rounds.run_rounds(sizes, p, n_clients, n_rounds, local_update_dev, participants=participants,
+                                      on_device=True)
+    assert up_dev == up_host
+    for a, b in zip(W_dev, W_host):
+        assert np.array_equal(a.cpu().numpy(), b)
