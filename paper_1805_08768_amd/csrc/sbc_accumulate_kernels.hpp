@@ -484,23 +484,32 @@ __global__ __launch_bounds__(kStreamThreads) void k_accumulate_filter(
         return;
     }
     // queue overflow: append the candidates of this workgroup's chunks from a second read of A,
-    // 1024 entries at a time (the barrier above ordered the workgroup's stores of A before these loads)
+    // 4096 entries at a time (the barrier above ordered the workgroup's stores of A before these
+    // loads).  Filter keys that let a flood pass send most workgroups of a call this way, so a step
+    // takes as many entries as the scan's 16-bit counts per side allow.
+    constexpr int kRedo = 16;
+    static_assert(kRedo * kStreamThreads <= 65535, "the per-side counts of one step fit their 16-bit fields");
     for (uint32_t sub = 0; sub < n_sub; ++sub) {
         const uint32_t e0 = (sc.x + sub - d.chunk0) * (uint32_t)kChunk;
         const uint32_t cnt = min((uint32_t)kChunk, d.n - e0);
         const gcfloat_ptr r = as_global(d.R + e0);
-        for (uint32_t off = 0; off < cnt; off += 4 * kStreamThreads) {
-            uint32_t key[4];
+        for (uint32_t off = 0; off < cnt; off += kRedo * kStreamThreads) {
+            uint32_t key[kRedo];
             uint32_t mp = 0u, mn = 0u;
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
+            for (int s = 0; s < kRedo; ++s) {
+                const uint32_t i = off + s * kStreamThreads + tid;
+                key[s] = __float_as_uint(r[i < cnt ? i : 0u]);
+            }
+#pragma unroll
+            for (int s = 0; s < kRedo; ++s) {
                 const uint32_t i = off + s * kStreamThreads + tid;
                 const bool in = i < cnt;
-                key[s] = key_of_bits(__float_as_uint(r[in ? i : 0u]));
+                key[s] = key_of_bits(key[s]);
                 if (in && key[s] >= lo_p) mp |= 1u << s;
                 if (in && ~key[s] >= lo_n) mn |= 1u << s;
             }
-            append_candidates<4>(key, mp, mn, e0 + off, d, &st[t], cand, result, sh.scratch, sh.base);
+            append_candidates<kRedo>(key, mp, mn, e0 + off, d, &st[t], cand, result, sh.scratch, sh.base);
         }
     }
 }
