@@ -69,7 +69,10 @@ __device__ __forceinline__ uint32_t mix32(uint32_t x) {
 // 16-bit key bucket holding the sample's r-th most extreme entry, r = lambda + 4*sqrt(lambda)
 // + 3, so that the chance of cutting into the true top k is negligible (and harmless: the
 // histogram path then redoes the tensor).  Both sides are selected together, the negative side
-// on complemented keys.  The kernel also clears the per-tensor state and the result block.
+// on complemented keys.  The kernel also clears the per-tensor state, and
+// it tells whether the keys the previous call left for this one (they are still in the state when
+// the kernel starts) would have held: if the sample says that far more entries than a selection
+// wants lie at or above them, kErrStaleKeys is raised, and the host goes on sampling.
 // For tensors flagged kDescSampled ("Sparse Binarization": the threshold is estimated from a
 // random subsample, which makes the amount of sparsity noisy) the key is instead the full 32-bit
 // key of the sample's r-th most extreme entry, r = max(1, floor(p*m)): the threshold itself.
@@ -84,6 +87,7 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
     __shared__ uint32_t hist[4][2][256];
     __shared__ uint32_t whist[2][kSampleWindow];      // leading 16 key bits, counted down from the extreme
     __shared__ uint32_t wave_ext[2][kSampleThreads / 64];
+    __shared__ uint32_t wave_above[kSampleThreads / 64];
     __shared__ uint32_t blist[2][kSampleThreads];     // subsampled variant: the sampled keys of the threshold's bucket
     __shared__ uint32_t bcnt[2], btau[2];
     __shared__ uint32_t res[4][8];
@@ -91,8 +95,12 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
     SBC_TS(0, 0);
     const int t = blockIdx.x, tid = threadIdx.x;
     const TensorDesc d = desc[t];
+    const uint32_t old_p = st[t].lo_key[0], old_n = st[t].lo_key[1];      // what the previous call left
+    __syncthreads();                                  // (every thread has them before the state is cleared)
     if (tid == 0) {
-        if (t == 0) { result->err = 0u; result->pad = 0u; result->msg_bytes = 0ull; }
+        // (the call's result block is clean already: the previous call's last kernel, or the host
+        // after an error, cleared it.  A plain store to it here would sit in this compute-unit group's
+        // L2 until the kernel ends and then overwrite the bits other groups' workgroups raise below.)
         TensorState z;
         z.lo_key[0] = z.lo_key[1] = force_exact ? 0xFFFFFFFFu : 0u;
         z.cand_cnt[0] = z.cand_cnt[1] = 0u;
@@ -160,7 +168,7 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
             }
         }
         // Keys, and the most extreme key of each side (this thread's, then the workgroup's).
-        uint32_t key[PER], ext_p = 0u, ext_n = 0u;
+        uint32_t key[PER], ext_p = 0u, ext_n = 0u, above = 0u;       // above: sampled entries at or beyond the old keys, 16 bits per side
 #pragma unroll
         for (int s = 0; s < PER; ++s) {
             key[s] = key_of_bits(__float_as_uint(a[s] + w[s]));
@@ -168,6 +176,7 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
             if ((uint32_t)(s * kSampleThreads + tid) < m) {
                 ext_p = key[s] > ext_p ? key[s] : ext_p;
                 ext_n = ~key[s] > ext_n ? ~key[s] : ext_n;
+                above += (key[s] >= old_p ? 1u : 0u) + (~key[s] >= old_n ? 0x10000u : 0u);
             }
         }
 #pragma unroll
@@ -175,10 +184,18 @@ __global__ __launch_bounds__(kSampleThreads) void k_sample_thresholds(
             const uint32_t op = __shfl_xor(ext_p, off, 64), on = __shfl_xor(ext_n, off, 64);
             ext_p = op > ext_p ? op : ext_p;
             ext_n = on > ext_n ? on : ext_n;
+            above += __shfl_xor(above, off, 64);      // (at most 2048 per side and wavefront)
         }
-        if ((tid & 63) == 0) { wave_ext[0][tid >> 6] = ext_p; wave_ext[1][tid >> 6] = ext_n; }
+        if ((tid & 63) == 0) { wave_ext[0][tid >> 6] = ext_p; wave_ext[1][tid >> 6] = ext_n; wave_above[tid >> 6] = above; }
         __syncthreads();
         SBC_TS(0, 1);                                 // sample loaded
+        if (tid == 0) {
+            uint32_t ap = 0u, an = 0u;
+            for (int wv = 0; wv < kSampleThreads / 64; ++wv) { ap += wave_above[wv] & 0xFFFFu; an += wave_above[wv] >> 16; }
+            // scaled to the tensor; the limit is the one beyond which k_select calls a list loose
+            const double scale = (double)n / (double)m, many = (double)loose_limit(d.k, n);
+            if ((double)ap * scale > many || (double)an * scale > many) atomicOr(&result->err, kErrStaleKeys);
+        }
 #pragma unroll
         for (int wv = 0; wv < kSampleThreads / 64; ++wv) {
             ext_p = wave_ext[0][wv] > ext_p ? wave_ext[0][wv] : ext_p;

@@ -75,7 +75,20 @@ constexpr uint32_t kErrOverflow = 128u;  // a candidate list of a compact contex
 constexpr uint32_t kErrPrefilter = 8u;   // not an error: some tensor needs the histogram path
 constexpr uint32_t kErrWide = 32u;       // not an error: the grid-wide selection kernels completed some tensor
 constexpr uint32_t kErrLoose = 16u;      // not an error: a carried-over filter key let far too many entries pass
+constexpr uint32_t kErrStaleKeys = 256u; // not an error: the filter keys the previous call left would have let far too many entries pass now
 constexpr uint32_t kErrDeferred = 64u;   // not an error: a tensor the streaming kernel could not finish itself is left to k_select
+
+// Candidates per side beyond which a list counts as a flood (the next call then estimates its keys
+// afresh): 16 k + 8192, but at most one entry in 16 of the tensor if that is above 8 k + 4096 (a
+// workgroup of the streaming kernel queues up to 1024 candidates per side of its 8192 entries in
+// LDS; beyond that it reads its chunk a second time).  Lists of a few times k are the normal
+// state while a residual still builds up and cost a selection a few microseconds; a key that has
+// fallen behind the data lets 30 to 60 times k pass.
+__host__ __device__ inline unsigned long long loose_limit(uint32_t k, uint32_t n) {
+    const unsigned long long lo = 8ull * k + 4096ull, hi = 16ull * k + 8192ull, dense = (unsigned long long)n / 16ull;
+    const unsigned long long cap = dense > lo ? dense : lo;
+    return hi < cap ? hi : cap;
+}
 
 // TensorDesc::flags
 constexpr int kWindow = 2048;             // bins of the leading-bits histograms (k_select, grid-wide selection)

@@ -141,6 +141,7 @@ struct sbc_ctx {
     // ---- options ----
     int force_exact = 0;
     int carry_keys = 1;
+    int carry_stale_run = 0;                 // sampled calls in a row that found the previous call's keys stale
     int carry_backoff = 0, carry_hold = 0;   // sampled calls after a call whose carried keys let a flood pass
     int fused_step = 0;                   // the streaming kernel finishes the tensors it can by itself
     int sampled = 0;                      // subsampled variant: the sampled threshold decides what is kept
@@ -1009,7 +1010,7 @@ int sbc_compress_end(sbc_ctx* c, size_t* msg_bytes) {
     // ---- histogram path for the tensors whose filter kept fewer than k candidates ----
     // ---- second pass: the histogram route for the tensors whose filter kept fewer than k candidates,
     // and k_select for the tensors the streaming kernel left to it ----
-    const uint32_t loose = err & kErrLoose;
+    const uint32_t loose = err & (kErrLoose | kErrStaleKeys);
     c->last_deferred = (err & kErrDeferred) != 0u;
     if ((err & (kErrPrefilter | kErrDeferred)) && !(err & (kErrInternal | kErrNonFinite | kErrOverflow))) {
         c->last_used_exact_path = (err & kErrPrefilter) != 0u;
@@ -1043,17 +1044,32 @@ int sbc_compress_end(sbc_ctx* c, size_t* msg_bytes) {
     c->last_loose = (err & kErrLoose) != 0u;
     c->result_dirty = false;
     // the next call may start from this call's thresholds unless they proved unhelpful
-    c->hist_valid = c->carry_keys && !P.sampled && !P.force_exact && !c->last_used_exact_path && !(err & kErrLoose);
+    // (a sampled call with long lists says nothing about the keys it leaves: those go by rank)
+    const bool flood = (err & kErrLoose) && P.use_history;
+    c->hist_valid = c->carry_keys && !P.sampled && !P.force_exact && !c->last_used_exact_path && !flood;
     // While the data still grows from call to call (the first rounds of a run, when the residual
-    // builds up) carried keys let floods of candidates pass again and again: every such call
-    // doubles the number of sampled calls that follow it, and a carried call that goes well ends that.
-    if (err & kErrLoose) {
+    // builds up) carried keys let floods of candidates pass.  After such a call the next calls
+    // sample, and each of their samples also tells whether the keys the call before it left would
+    // have held on its data (kErrStaleKeys if not): sampling goes on until they would (for at most
+    // 64 calls in a row, then a carried call is tried whatever the samples say).  Should carried
+    // calls flood again and again all the same, each flood doubles the number of sampled calls
+    // that follow it at the least; a carried call that goes well ends that.
+    if (flood) {
         c->carry_backoff = std::min(64, std::max(1, 2 * c->carry_backoff));
         c->carry_hold = c->carry_backoff;
+        c->carry_stale_run = 0;
     } else if (P.use_history) {
         c->carry_backoff = 0;
-    } else if (c->carry_hold > 0 && --c->carry_hold > 0) {
+    } else if (c->carry_hold > 1) {
+        --c->carry_hold;
         c->hist_valid = false;
+    } else if (c->carry_hold == 1) {
+        if ((err & kErrStaleKeys) && ++c->carry_stale_run <= 64) {
+            c->hist_valid = false;
+        } else {
+            c->carry_hold = 0;
+            c->carry_stale_run = 0;
+        }
     }
     if (c->hist_valid) {
         c->hist_p = P.p;

@@ -541,7 +541,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(
         }
         // many times more candidates than needed: the next call should estimate its keys afresh
         // (lists somewhat too long for LDS only cost one more sweep here)
-        const uint32_t many = 8u * k + 4096u;
+        const unsigned long long many = loose_limit(k, n);
         if (cnt_p > many || cnt_n > many) atomicOr(&result->err, kErrLoose);
     }
     if (!ok) return;

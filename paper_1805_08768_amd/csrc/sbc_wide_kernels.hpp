@@ -403,7 +403,7 @@ __global__ __launch_bounds__(kWideThreads) void k_wide_apply(
         st[t].lo_key[1] = ws[w].next_key[1];
         st[t].expect[0] = 0u; st[t].expect[1] = 0u;
         // many times more candidates than needed: the next call should estimate its keys afresh
-        const uint32_t many = 8u * d.k + 4096u;
+        const unsigned long long many = loose_limit(d.k, d.n);
         if (st[t].cand_cnt[0] > many || st[t].cand_cnt[1] > many) atomicOr(&result->err, kErrLoose);
     }
     const int s = chosen;

@@ -185,14 +185,16 @@ def test_misleading_sample_falls_back_per_tensor():
 def test_carried_filter_keys():
     """From the second round on the filter keys come from the previous round's exact thresholds.
     Results stay exact when the data scale drifts, jumps up (keys far too low: a flood of
-    candidates) or collapses (keys far too high: the histogram route takes over)."""
+    candidates, after which rounds sample until their samples say that carried keys would hold
+    again) or collapses (keys far too high: the histogram route takes over)."""
     sizes = [300000, 64, 20000, 8193]
-    scales = [1.0, 1.05, 0.9, 1.2, 40.0, 40.0, 0.01, 0.01, 1.0]
     routes = []
     with DeviceRun(sizes) as run:                            # (the option is set by default)
         R = [np.zeros(n, np.float32) for n in sizes]
-        for r, sc in enumerate(scales):
-            if r == 6:                                       # the client starts over: residual cleared
+
+        def one_round(r, sc, clear=False):
+            nonlocal R
+            if clear:                                        # the client starts over: residual cleared
                 R = [np.zeros(n, np.float32) for n in sizes]
                 for x in run.R:
                     x.zero_()
@@ -200,11 +202,23 @@ def test_carried_filter_keys():
             res = check_round(run, dWs, R, 0.001, check_decode=(r % 4 == 0))
             routes.append(main_route(run.ctx))
             R = [x.R_new for x in res]
+
+        for r, sc in enumerate([1.0, 1.05, 0.9, 1.2, 40.0, 40.0]):
+            one_round(r, sc)
+        assert routes[0] == 0                                # first round samples
+        assert routes[1] == sbc.SBC_ROUTE_CARRIED_KEYS and routes[2] == sbc.SBC_ROUTE_CARRIED_KEYS
+        assert routes[4] & sbc.SBC_ROUTE_CARRIED_KEYS        # the jump: carried keys, a flood of candidates
+        assert routes[5] == 0                                # ... which made round 5 sample again
+        r = 6
+        while not routes[-1] & sbc.SBC_ROUTE_CARRIED_KEYS:   # sampling goes on while the residual still grows fast
+            assert r < 16
+            one_round(r, 40.0)
+            r += 1
+        one_round(r, 0.01, clear=True)                       # the collapse forces the exact route
+        assert routes[-1] & sbc.SBC_ROUTE_CARRIED_KEYS and routes[-1] & sbc.SBC_ROUTE_HISTOGRAM
+        one_round(r + 1, 0.01)
+        one_round(r + 2, 1.0)
     print("routes", routes)
-    assert routes[0] == 0                                    # first round samples
-    assert routes[1] == sbc.SBC_ROUTE_CARRIED_KEYS and routes[2] == sbc.SBC_ROUTE_CARRIED_KEYS
-    assert routes[5] == 0                                    # the flood of candidates made round 5 sample again
-    assert routes[6] & sbc.SBC_ROUTE_HISTOGRAM               # the collapse forces the exact route
     with DeviceRun(sizes) as run:                            # option cleared: every round samples
         sbc.sbc_set_option(run.ctx, sbc.SBC_OPT_CARRY_FILTER_KEYS, 0)
         R = [np.zeros(n, np.float32) for n in sizes]
