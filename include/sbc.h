@@ -210,11 +210,13 @@ int sbc_decompress_accumulate_noalloc(int device, void* hip_stream,
  *   SBC_OPT_CARRY_FILTER_KEYS  (0/1, default 1)  1 lets a call start from filter keys that the
  *       previous successful call on this context left behind, when tensor sizes and p are
  *       unchanged (successive rounds of one training run), and skips the sampling kernel: per
- *       tensor and side the key of that call's entry of rank about 9/8 k.  Only a filter: a
- *       tensor for which it keeps fewer than k entries (the data shrank, the residual was
- *       cleared) is redone exactly through the histogram route, and the next call samples; so
- *       does the call after one that saw many times k candidates (the data grew).  0 estimates
- *       the keys from a sample of the new data in every call.
+ *       tensor and side the key of that call's entry of rank 9/8 k to 2 k (more while its
+ *       update moves many entries across the key).  Only a filter: a tensor for which it keeps
+ *       fewer than k entries (the data shrank, the residual was cleared) is redone exactly
+ *       through the histogram route, and the next call samples; so do the calls after one that
+ *       saw many times k candidates (the data grew), until a call's sample says that the keys
+ *       of the call before it would have held.  0 estimates the keys from a sample of the new
+ *       data in every call.
  *   SBC_OPT_WIDE_MIN_KEPT      (default 0 = 8192)  a tensor that keeps at least this many entries
  *       per side is selected by grid-wide kernels instead of one workgroup, and its stream is
  *       decoded tile by tile by many workgroups instead of one (a 1.5e9-entry tensor at
