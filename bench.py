@@ -44,7 +44,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 BYTES_PER_ENTRY = 12           # read dW, read R, write R'
 P = 0.001
-PROFILE_EVERY = 4            # timed steps between two event-bracketed launches of the streaming kernel
+PROFILE_EVERY = 6            # timed steps between two event-bracketed launches of the streaming kernel
 COLD_LAUNCHES = 12           # calls with the caches flushed before each
 CPU_ROUNDS = 3               # rounds of the whole update the CPU oracle is timed on, per leg
 
