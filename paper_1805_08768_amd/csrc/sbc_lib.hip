@@ -344,7 +344,7 @@ void launch_wide_selection(sbc_ctx* c, bool handback) {
     TensorDesc* const d_desc = P.d_desc;
     ResultBlock* const res_now = P.res_now;
     // (the sweeps that carry the second histogram have four times the threads per workgroup)
-    const dim3 sweep(c->wide_blocks, (unsigned)c->n_wide), sweep4(std::max(16u, c->wide_blocks / 4u), (unsigned)c->n_wide);
+    const dim3 sweep(c->wide_blocks, (unsigned)c->n_wide), sweep4(std::max(128u, c->wide_blocks / 4u), (unsigned)c->n_wide);
     const bool time_wide = lvl >= 2;
     WideIds ids = {};
     std::memcpy(ids.id, c->h_wide_ids, sizeof(uint32_t) * (size_t)c->n_wide);
@@ -802,7 +802,7 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
         if (chunks >= (1ull << 31)) return SBC_ECAPACITY;
         c->n_wide = n_wide;
         // sweeps over a candidate list: enough workgroups to fill the chip, each with several rounds
-        c->wide_blocks = (uint32_t)std::min<uint64_t>(2048, std::max<uint64_t>(64, wide_max_n / 65536));
+        c->wide_blocks = (uint32_t)std::min<uint64_t>(2048, std::max<uint64_t>(128, wide_max_n / 65536));
     }
     const size_t need = (size_t)(32 + 24ull * (unsigned)T + 4ull * stage_words);
     if (msg_capacity < need) return SBC_ECAPACITY;
