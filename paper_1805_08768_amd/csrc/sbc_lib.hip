@@ -801,7 +801,9 @@ static int compress_begin(sbc_ctx* c, void* hip_stream, const float* const* dW, 
         }
         if (chunks >= (1ull << 31)) return SBC_ECAPACITY;
         c->n_wide = n_wide;
-        // sweeps over a candidate list: enough workgroups to fill the chip, each with several rounds
+        // sweeps over a candidate list: enough workgroups to fill the chip, each with several rounds;
+        // at least 128 even for short lists (a compute unit pulls a small share sooner than a large one,
+        // and the tensor-wide step every workgroup repeats costs the same in all of them at once)
         c->wide_blocks = (uint32_t)std::min<uint64_t>(2048, std::max<uint64_t>(128, wide_max_n / 65536));
     }
     const size_t need = (size_t)(32 + 24ull * (unsigned)T + 4ull * stage_words);
